@@ -1,0 +1,412 @@
+"""Pins of the CPU oracle against things other than itself: brute force in numpy fp64 written
+from the layer's definition, closed forms, special cases that reduce to a dense FFN, finite
+differences, and the numbers the paper prints in Table 4.  CPU only."""
+import os
+
+import numpy as np
+import pytest
+from scipy.special import erf
+
+from paper_2502_16927_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def gelu64(a):
+    return 0.5 * a * (1.0 + erf(a / np.sqrt(2.0)))
+
+
+def rand_layer(rng, T, d, r, N, k, h, x_std=1.0, w_std=0.2):
+    f = lambda *s, std=w_std: (rng.standard_normal(s) * std).astype(np.float32)
+    return dict(x=f(T, d, std=x_std), w_gate=f(d, N), w_down=f(d, r), w_up=f(r, d),
+                w1=f(N, r, h), w2=f(N, h, r), k=k)
+
+
+def brute_force_forward(p, bias=None):
+    """Eq. 2 with the expert of Eq. 4, one token at a time, everything in fp64."""
+    x = p["x"].astype(np.float64)
+    T, d = x.shape
+    k = p["k"]
+    y = np.zeros((T, d))
+    ylow = np.zeros((T, p["w_down"].shape[1]))
+    for t in range(T):
+        logit = x[t] @ p["w_gate"].astype(np.float64)
+        if bias is not None:
+            logit = logit + bias
+        chosen = sorted(range(len(logit)), key=lambda n: (-logit[n], n))[:k]
+        z = np.exp(logit[chosen] - logit[chosen].max())
+        gate = z / z.sum()
+        xl = x[t] @ p["w_down"].astype(np.float64)
+        acc = np.zeros_like(xl)
+        for g, e in zip(gate, chosen):
+            acc += g * (gelu64(xl @ p["w1"][e].astype(np.float64)) @ p["w2"][e].astype(np.float64))
+        ylow[t] = acc
+        y[t] = acc @ p["w_up"].astype(np.float64)
+    return y, ylow
+
+
+def oracle_fwd(oracle, p, bias=None, **kw):
+    return oracle.bigmac_forward(p["x"], p["w_gate"], bias, p["w_down"], p["w_up"], p["w1"], p["w2"],
+                                 p["k"], **kw)
+
+
+# ------------------------------------------------------------------ router -------------------
+
+def test_router_close_to_fp64_matmul(oracle):
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((33, 256)).astype(np.float32)
+    wg = (rng.standard_normal((256, 12)) * 0.05).astype(np.float32)
+    b = rng.standard_normal(12).astype(np.float32)
+    ref = x.astype(np.float64) @ wg.astype(np.float64)
+    assert np.abs(oracle.router_logits(x, wg) - ref).max() < 2e-5
+    assert np.abs(oracle.router_logits(x, wg, b) - (ref + b)).max() < 2e-5
+
+
+def test_router_exact_on_integers(oracle):
+    # small integers: every partial sum is exact in fp32, so the logits must equal the integer
+    # dot product whatever the order - catches a wrong index, stride or dropped block
+    rng = np.random.default_rng(1)
+    x = rng.integers(-8, 9, (17, 192)).astype(np.float32)
+    wg = rng.integers(-8, 9, (192, 5)).astype(np.float32)
+    ref = x.astype(np.int64) @ wg.astype(np.int64)
+    assert np.array_equal(oracle.router_logits(x, wg).astype(np.int64), ref)
+
+
+def test_router_fixed_summation_order(oracle):
+    # values chosen so that fp32 absorption makes the result depend on the order
+    d = 128
+    wg = np.ones((d, 1), np.float32)
+    # (a) lane partial sums are strided by 64: elements 0 and 64 meet first and cancel
+    x = np.zeros((1, d), np.float32)
+    x[0, 0], x[0, 1], x[0, 64] = 1e8, 1.0, -1e8
+    assert oracle.router_logits(x, wg)[0, 0] == 1.0      # sequential order would give 0
+    # (b) the tree pairs lane l with lane l+32 first
+    x = np.zeros((1, d), np.float32)
+    x[0, 0], x[0, 1], x[0, 32] = 1e8, 1.0, -1e8
+    assert oracle.router_logits(x, wg)[0, 0] == 1.0      # pairing neighbours first would give 0
+    # (c) ... then with l+16: lanes 0 and 16 survive the first level and cancel at the second
+    x = np.zeros((1, d), np.float32)
+    x[0, 0], x[0, 8], x[0, 16] = 1e8, 1.0, -1e8
+    assert oracle.router_logits(x, wg)[0, 0] == 1.0
+    # (d) the bias is added last
+    x = np.zeros((1, d), np.float32)
+    x[0, 0], x[0, 64] = 1e8, -1e8
+    assert oracle.router_logits(x, wg, np.array([0.5], np.float32))[0, 0] == 0.5
+    # (e) products are fused: x*w rounded separately would lose the low bits
+    x = np.zeros((1, d), np.float32)
+    a = np.float32(1.0 + 2.0 ** -12)
+    x[0, 0], x[0, 64] = -1.0, a
+    wg2 = np.ones((d, 1), np.float32)
+    wg2[0, 0], wg2[64, 0] = np.float32(np.float64(a) * np.float64(a)), a   # rounded product first
+    exact = np.float64(a) * np.float64(a) - np.float64(wg2[0, 0])
+    assert oracle.router_logits(x, wg2)[0, 0] == np.float32(exact) and exact != 0.0
+
+
+def test_topk_ties_go_to_lowest_index(oracle):
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((64, 128)).astype(np.float32)
+    col = rng.standard_normal((128, 3)).astype(np.float32)
+    # experts 1, 4, 6 share a column, so do 0 and 5, so do 2 and 3: exactly equal logits
+    wg = np.stack([col[:, 0], col[:, 1], col[:, 2], col[:, 2], col[:, 1], col[:, 0], col[:, 1]], axis=1)
+    idx, gate, logits = oracle.route(x, wg, None, 3)
+    assert np.array_equal(logits[:, 1], logits[:, 4]) and np.array_equal(logits[:, 0], logits[:, 5])
+    for t in range(x.shape[0]):
+        order = sorted(range(7), key=lambda n: (-float(logits[t, n]), n))[:3]
+        assert list(idx[t]) == order
+    # equal logits get equal gate values
+    idx, gate, logits = oracle.route(x, wg, None, 7)
+    for t in range(x.shape[0]):
+        pos = {int(e): j for j, e in enumerate(idx[t])}
+        assert gate[t, pos[1]] == gate[t, pos[4]] == gate[t, pos[6]]
+
+
+def test_topk_degenerate_k(oracle):
+    rng = np.random.default_rng(3)
+    logits = rng.standard_normal((50, 9)).astype(np.float32)
+    idx, gate = oracle.topk_gate(logits, 9)
+    assert np.array_equal(np.sort(idx, axis=1), np.tile(np.arange(9), (50, 1)))
+    assert np.all(np.diff(np.take_along_axis(logits, idx, 1), axis=1) <= 0)
+    idx1, gate1 = oracle.topk_gate(logits, 1)
+    assert np.array_equal(idx1[:, 0], logits.argmax(1)) and np.all(gate1 == 1.0)
+
+
+def test_gate_is_renormalised_softmax(oracle):
+    rng = np.random.default_rng(4)
+    logits = (rng.standard_normal((200, 16)) * 3).astype(np.float32)
+    idx, gate = oracle.topk_gate(logits, 4)
+    assert np.all(gate >= 0) and np.abs(gate.sum(1) - 1).max() < 1e-12
+    full = np.exp(logits.astype(np.float64) - logits.max(1, keepdims=True))
+    full /= full.sum(1, keepdims=True)
+    pick = np.take_along_axis(full, idx, 1)
+    assert np.abs(gate - pick / pick.sum(1, keepdims=True)).max() < 1e-12
+    assert np.all(np.diff(gate, axis=1) <= 0)
+
+
+# ------------------------------------------------------------------ permutation --------------
+
+@pytest.mark.parametrize("T,k,N", [(1, 1, 1), (37, 3, 5), (256, 8, 64), (100, 2, 128)])
+def test_permutation_is_stable_sort(oracle, T, k, N):
+    rng = np.random.default_rng(5)
+    idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+    if N >= 4:
+        idx[idx == 3] = 2 if k == 1 else idx[idx == 3]      # leave expert 3 possibly empty
+    offsets, slot_of, src_of = oracle.permutation(idx, N)
+    flat = idx.ravel()
+    assert np.array_equal(src_of, np.argsort(flat, kind="stable"))
+    assert np.array_equal(slot_of.ravel()[src_of], np.arange(T * k))
+    assert np.array_equal(np.sort(src_of), np.arange(T * k))
+    assert np.array_equal(offsets, np.concatenate([[0], np.cumsum(np.bincount(flat, minlength=N))]))
+    assert offsets[N] == T * k
+    ex = flat[src_of]
+    assert np.all(np.diff(ex) >= 0)
+    tok = src_of // k
+    assert np.all((np.diff(tok) > 0) | (np.diff(ex) > 0))   # tokens increase inside an expert
+
+
+def test_dispatch_combine_round_trip(oracle):
+    rng = np.random.default_rng(6)
+    T, k, N, w = 70, 3, 6, 16
+    idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+    offsets, slot_of, src_of = oracle.permutation(idx, N)
+    xl = rng.standard_normal((T, w)).astype(np.float32)
+    xp = oracle.dispatch(xl, slot_of)
+    assert np.array_equal(xp, xl[src_of // k])
+    assert np.array_equal(xp[slot_of[:, 0]], xl)                      # un-dispatch is the identity
+    gate = np.full((T, k), 1.0 / k)
+    back = oracle.combine(xp.astype(np.float64), slot_of, gate)
+    assert np.abs(back - xl).max() < 1e-6
+    unit = oracle.combine(xp.astype(np.float64), slot_of, None)
+    assert np.abs(unit - k * xl.astype(np.float64)).max() < 1e-6
+
+
+# ------------------------------------------------------------------ forward ------------------
+
+@pytest.mark.parametrize("T,d,r,N,k,h", [(4, 64, 4, 3, 2, 8), (9, 128, 16, 5, 5, 24), (6, 64, 8, 4, 1, 8)])
+def test_forward_matches_brute_force(oracle, T, d, r, N, k, h):
+    p = rand_layer(np.random.default_rng(7), T, d, r, N, k, h)
+    y, ylow = oracle_fwd(oracle, p, want_y_low=True)
+    yb, ylb = brute_force_forward(p)
+    # the oracle's logits are fp32 (they decide the routing), the brute force's are fp64: the
+    # gate values differ by ~1e-7 relative, everything else is fp64 on both sides
+    assert np.abs(ylow - ylb).max() < 1e-6 * np.abs(ylb).max()
+    assert np.abs(y - yb).max() < 1e-6 * np.abs(yb).max()
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    yb2 = brute_force_forward(p, bias.astype(np.float64))[0]
+    assert np.abs(oracle_fwd(oracle, p, bias) - yb2).max() < 1e-6 * np.abs(yb2).max()
+
+
+def test_forward_selected_tokens(oracle):
+    p = rand_layer(np.random.default_rng(8), 20, 64, 8, 6, 2, 16)
+    full = oracle_fwd(oracle, p)
+    sel = np.array([17, 3, 3, 0], np.int32)
+    assert np.array_equal(oracle_fwd(oracle, p, sel=sel), full[sel])
+
+
+def test_single_expert_is_a_dense_ffn(oracle):
+    p = rand_layer(np.random.default_rng(9), 12, 64, 16, 1, 1, 32)
+    x = p["x"].astype(np.float64)
+    dense = gelu64(x @ p["w_down"] @ p["w1"][0].astype(np.float64)) @ p["w2"][0].astype(np.float64) @ p["w_up"]
+    assert np.abs(oracle_fwd(oracle, p) - dense).max() < 1e-9
+
+
+def test_identical_experts_are_a_dense_ffn(oracle):
+    # the gate values sum to one, so with equal experts the routing cannot matter
+    p = rand_layer(np.random.default_rng(10), 12, 64, 16, 6, 3, 32)
+    p["w1"][:] = p["w1"][0]
+    p["w2"][:] = p["w2"][0]
+    x = p["x"].astype(np.float64)
+    dense = gelu64(x @ p["w_down"] @ p["w1"][0].astype(np.float64)) @ p["w2"][0].astype(np.float64) @ p["w_up"]
+    assert np.abs(oracle_fwd(oracle, p) - dense).max() < 1e-9
+    p["w2"][:] = 0
+    assert np.all(oracle_fwd(oracle, p) == 0)
+
+
+def test_identity_projections_give_the_fine_grained_layer(oracle):
+    # r = d and W_down = W_up = I: DCCA collapses to a plain top-k MoE whose experts are the
+    # BigMac experts; multiplying by I is exact, so the two oracles must agree to the last bit
+    rng = np.random.default_rng(11)
+    p = rand_layer(rng, 10, 64, 64, 5, 2, 24)
+    p["w_down"] = np.eye(64, dtype=np.float32)
+    p["w_up"] = np.eye(64, dtype=np.float32)
+    y = oracle_fwd(oracle, p)
+    y_fg = oracle.cdac_forward(p["x"], p["w_gate"], None, p["w1"], p["w2"], p["k"])
+    assert np.array_equal(y, y_fg)
+
+
+def test_fine_grained_layer_brute_force(oracle):
+    rng = np.random.default_rng(12)
+    T, d, r, N, k = 7, 64, 8, 4, 2
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    wg = (rng.standard_normal((d, N)) * 0.2).astype(np.float32)
+    wdn = (rng.standard_normal((N, d, r)) * 0.2).astype(np.float32)
+    wup = (rng.standard_normal((N, r, d)) * 0.2).astype(np.float32)
+    y = oracle.cdac_forward(x, wg, None, wdn, wup, k)
+    idx, gate, _ = oracle.route(x, wg, None, k)
+    for t in range(T):
+        ref = sum(gate[t, j] * (gelu64(x[t].astype(np.float64) @ wdn[idx[t, j]]) @ wup[idx[t, j]].astype(np.float64))
+                  for j in range(k))
+        assert np.abs(y[t] - ref).max() < 1e-10
+
+
+def test_pieces_compose_to_the_layer(oracle):
+    p = rand_layer(np.random.default_rng(13), 40, 64, 16, 7, 3, 32)
+    idx, gate, _ = oracle.route(p["x"], p["w_gate"], None, p["k"])
+    offsets, slot_of, src_of = oracle.permutation(idx, 7)
+    xl = (p["x"].astype(np.float64) @ p["w_down"].astype(np.float64))
+    xl32 = xl.astype(np.float32)                  # the piece API carries fp32 rows
+    o = oracle.expert_rows(oracle.dispatch(xl32, slot_of), offsets, p["w1"], p["w2"])
+    ylow = oracle.combine(o, slot_of, gate)
+    y, ylow_ref = oracle_fwd(oracle, p, want_y_low=True)
+    assert np.abs(ylow - ylow_ref).max() < 1e-6 * np.abs(ylow_ref).max()
+    assert np.abs(ylow @ p["w_up"].astype(np.float64) - y).max() < 1e-6 * np.abs(y).max()
+
+
+# ------------------------------------------------------------------ backward -----------------
+
+def _loss(oracle, p, dy):
+    return float((oracle_fwd(oracle, p) * dy).sum())
+
+
+def test_backward_matches_finite_differences(oracle):
+    rng = np.random.default_rng(14)
+    T, d, r, N, k, h = 5, 64, 8, 4, 2, 12
+    p = rand_layer(rng, T, d, r, N, k, h, w_std=0.3)
+    dy = rng.standard_normal((T, d)).astype(np.float32)
+    g = oracle.bigmac_backward(p["x"], dy, p["w_gate"], None, p["w_down"], p["w_up"], p["w1"], p["w2"], k)
+    idx0, _, _ = oracle.route(p["x"], p["w_gate"], None, k)
+    names = {"x": "dx", "w_down": "d_w_down", "w_up": "d_w_up", "w_gate": "d_w_gate", "w1": "d_w1", "w2": "d_w2"}
+    checked = 0
+    for name, gname in names.items():
+        flat = p[name].reshape(-1)
+        for pos in rng.choice(flat.size, size=12, replace=False):
+            keep = flat[pos]
+            hi, lo = np.float32(keep + 2e-3), np.float32(keep - 2e-3)
+            flat[pos] = hi
+            idx_hi, _, _ = oracle.route(p["x"], p["w_gate"], None, k)
+            lp = _loss(oracle, p, dy)
+            flat[pos] = lo
+            idx_lo, _, _ = oracle.route(p["x"], p["w_gate"], None, k)
+            lm = _loss(oracle, p, dy)
+            flat[pos] = keep
+            if not (np.array_equal(idx_hi, idx0) and np.array_equal(idx_lo, idx0)):
+                continue                                        # the top-k set moved: not differentiable there
+            fd = (lp - lm) / (np.float64(hi) - np.float64(lo))
+            an = g[gname].reshape(-1)[pos]
+            # fp32 logits put ~1e-7 of noise on the loss; over a 4e-3 step that is ~1e-4 on the slope
+            assert abs(fd - an) <= 5e-4 * max(1.0, abs(an)), (name, pos, fd, an)
+            checked += 1
+    assert checked > 50
+    assert np.abs(g["d_w_gate"].sum(1)).max() < 1e-10 * np.abs(g["d_w_gate"]).max() + 1e-12
+
+
+def test_backward_identical_experts_is_dense_ffn_gradient(oracle):
+    rng = np.random.default_rng(15)
+    T, d, r, N, k, h = 6, 64, 8, 5, 3, 10
+    p = rand_layer(rng, T, d, r, N, k, h)
+    p["w1"][:] = p["w1"][0]
+    p["w2"][:] = p["w2"][0]
+    dy = rng.standard_normal((T, d)).astype(np.float32)
+    g = oracle.bigmac_backward(p["x"], dy, p["w_gate"], None, p["w_down"], p["w_up"], p["w1"], p["w2"], k)
+    x, W1, W2 = p["x"].astype(np.float64), p["w1"][0].astype(np.float64), p["w2"][0].astype(np.float64)
+    Wd, Wu = p["w_down"].astype(np.float64), p["w_up"].astype(np.float64)
+    xl = x @ Wd
+    a = xl @ W1
+    hh = gelu64(a)
+    dyl = dy.astype(np.float64) @ Wu.T
+    da = (dyl @ W2.T) * (0.5 * (1 + erf(a / np.sqrt(2))) + a * np.exp(-a * a / 2) / np.sqrt(2 * np.pi))
+    assert np.abs(g["d_w_up"] - (hh @ W2).T @ dy).max() < 1e-9
+    assert np.abs(g["d_w2"].sum(0) - hh.T @ dyl).max() < 1e-9     # the gate values sum to one
+    assert np.abs(g["d_w1"].sum(0) - xl.T @ da).max() < 1e-9
+    assert np.abs(g["d_w_down"] - x.T @ (da @ W1.T)).max() < 1e-9
+    assert np.abs(g["dx"] - (da @ W1.T) @ Wd.T).max() < 1e-9       # equal experts: no gate gradient
+    assert np.abs(g["d_w_gate"]).max() < 1e-9
+
+
+def test_backward_accumulates_and_selects(oracle):
+    rng = np.random.default_rng(16)
+    T, d, r, N, k, h = 8, 64, 8, 4, 2, 10
+    p = rand_layer(rng, T, d, r, N, k, h)
+    dy = rng.standard_normal((T, d)).astype(np.float32)
+    args = (p["x"], dy, p["w_gate"], None, p["w_down"], p["w_up"], p["w1"], p["w2"], k)
+    g0 = oracle.bigmac_backward(*args)
+    init = {n: rng.standard_normal(v.shape) for n, v in g0.items() if n != "dx"}
+    g1 = oracle.bigmac_backward(*args, init=init)
+    for n in init:
+        assert np.abs(g1[n] - (init[n] + g0[n])).max() < 1e-12
+    sel = np.array([1, 4, 6], np.int32)
+    dyz = np.zeros_like(dy)
+    dyz[sel] = dy[sel]
+    gs = oracle.bigmac_backward(*args, sel=sel)
+    gz = oracle.bigmac_backward(p["x"], dyz, *args[2:])
+    for n in gs:
+        assert np.abs(gs[n] - gz[n]).max() < 1e-12, n
+
+
+def test_fine_grained_backward_finite_differences(oracle):
+    rng = np.random.default_rng(17)
+    T, d, r, N, k = 4, 64, 6, 4, 2
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    wg = (rng.standard_normal((d, N)) * 0.3).astype(np.float32)
+    wdn = (rng.standard_normal((N, d, r)) * 0.3).astype(np.float32)
+    wup = (rng.standard_normal((N, r, d)) * 0.3).astype(np.float32)
+    dy = rng.standard_normal((T, d)).astype(np.float32)
+    g = oracle.cdac_backward(x, dy, wg, None, wdn, wup, k)
+    idx0, _, _ = oracle.route(x, wg, None, k)
+    tensors = {"dx": x, "d_w_gate": wg, "d_w1": wdn, "d_w2": wup}
+    for gname, arr in tensors.items():
+        flat = arr.reshape(-1)
+        for pos in rng.choice(flat.size, size=10, replace=False):
+            keep = flat[pos]
+            hi, lo = np.float32(keep + 2e-3), np.float32(keep - 2e-3)
+            flat[pos] = hi
+            ok = np.array_equal(oracle.route(x, wg, None, k)[0], idx0)
+            lp = float((oracle.cdac_forward(x, wg, None, wdn, wup, k) * dy).sum())
+            flat[pos] = lo
+            ok &= np.array_equal(oracle.route(x, wg, None, k)[0], idx0)
+            lm = float((oracle.cdac_forward(x, wg, None, wdn, wup, k) * dy).sum())
+            flat[pos] = keep
+            if ok:
+                fd = (lp - lm) / (np.float64(hi) - np.float64(lo))
+                an = g[gname].reshape(-1)[pos]
+                assert abs(fd - an) <= 5e-4 * max(1.0, abs(an)), (gname, pos, fd, an)
+
+
+# ------------------------------------------------------------------ the paper's numbers ------
+
+def _golden():
+    out = {}
+    with open(os.path.join(GOLDEN, "paper_table4.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                key, val = line.split()
+                out[key] = float(val)
+    return out
+
+
+def test_closed_forms_reproduce_table_4(oracle):
+    g = _golden()
+    d, k, layers, tokens = int(g["hidden"]), int(g["top_k"]), g["layers"], g["tokens_per_iteration"]
+    r = int(d * g["ratio"])
+    # extra FLOPs of the two shared projections = the printed difference of the two columns
+    extra = (oracle.moe_flops_per_token(d, r, k, True) - oracle.moe_flops_per_token(d, r, k, False)) * layers * tokens
+    assert abs(extra / 1e12 - (g["flops_bigmac_T"] - g["flops_fine_grained_T"])) < 0.01
+    assert abs(extra / (g["flops_fine_grained_T"] * 1e12) - 0.0454) < 1e-4
+    # All-to-All bytes per iteration, BF16, ep = 32
+    scale = layers * tokens * (g["ep"] - 1) / g["ep"] / 2 ** 30
+    assert abs(oracle.a2a_bytes_per_token(d, r, k, False) * scale - g["a2a_fine_grained_GB"]) < 0.005
+    assert abs(oracle.a2a_bytes_per_token(d, r, k, True) * scale - g["a2a_bigmac_GB"]) < 0.005
+    # extra parameters 2 * ratio * layers * hidden^2
+    assert abs(2 * r * d * layers / 1e9 - (g["param_bigmac_B"] - g["param_fine_grained_B"])) < 0.005
+
+
+def test_synth_inputs_are_reproducible_and_rounded():
+    wl = synth.small()
+    a, b = synth.generate(wl), synth.generate(wl)
+    for n in a:
+        assert a[n] is None and b[n] is None or np.array_equal(a[n], b[n])
+    assert np.array_equal(synth.round_to_bf16(a["x"]), a["x"])
+    assert np.array_equal(synth.bits_to_f32(synth.bf16_bits(a["w1"])), a["w1"])
+    v = np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -9], np.float32)   # ties to even
+    assert np.array_equal(synth.round_to_bf16(v), np.array([1.0, 1.0 + 2 ** -6, 1.0], np.float32))
+    z = synth.generate(synth.small(N=128, k=8, zipf_s=1.2))
+    assert z["gate_bias"].shape == (128,) and np.isclose(z["gate_bias"].min(), -1.2 * np.log(128))
