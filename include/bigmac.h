@@ -1,0 +1,152 @@
+/*
+ * bigmac.h - C ABI of the MI355X (gfx950) BigMac MoE layer library.
+ *
+ * The layer (paper Section 3.1, Eq. 2, "descend-communicate-communicate-ascend"):
+ *     x' = x W_down ;   y' = sum_{i in T} p_i(x) E_i(x') ;   y = y' W_up
+ * with the BigMac expert (Section 3.2, Eq. 4)  E_i(x') = act(x' W1[i]) W2[i]  (r -> h -> r),
+ * T the top_k experts of the token (Section 2) and p_i its gate value.  On one GPU the two
+ * All-to-Alls of Section 3.1 are an on-device permute (dispatch) and un-permute (combine) of
+ * r-wide rows.  The fine-grained layer the paper compares with (CDAC order, Eq. 3) is the same
+ * calls with order = BIGMAC_ORDER_CDAC: dispatch/combine at width d, expert d -> r -> d, no
+ * shared projections.
+ *
+ * Conventions for every call
+ *  - All data pointers are DEVICE pointers; `dims`, `params` are HOST structs read during the
+ *    call.  Matrices are row-major and contiguous, weights are [in, out] (the paper's x.W),
+ *    base pointers 16-byte aligned.  Index arrays are int32.
+ *  - dtype is the storage type of x, dy, W_down, W_up, W1, W2 and of every permuted row
+ *    (BIGMAC_F32: float, BIGMAC_BF16: bfloat16 bit patterns).  w_gate, gate_bias, gate values,
+ *    logits and all weight gradients are always fp32.  All accumulation is fp32.
+ *  - Widths: win = dispatch width (r for DCCA, d for CDAC), hid = expert hidden width (h for
+ *    DCCA, r for CDAC).  d, r, h must be multiples of 64; 1 <= k <= N <= 1024; k <= 64; T*k < 2^31.
+ *  - The caller owns every buffer (inputs, outputs, workspace, saved block).  The library
+ *    allocates nothing, keeps no state and never synchronises: a call only enqueues kernels on
+ *    `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns.  Nothing
+ *    on the path is read back by the host; per-expert counts stay on the device.
+ *  - Return value: 0 on success; negative on failure, in which case nothing was launched by the
+ *    failing step: BIGMAC_ERR_INVALID_ARG (NULL required pointer, bad dimension or enum),
+ *    BIGMAC_ERR_WORKSPACE (workspace too small), BIGMAC_ERR_UNSUPPORTED, BIGMAC_ERR_HIP (a
+ *    launch failed).  Inputs are assumed finite; NaN/Inf logits give unspecified routing.
+ *  - Routing is dropless (Section 3.3): every (token, choice) pair keeps a row, the rows of an
+ *    expert are contiguous and ordered by token, expert_offsets[N] = T*k.
+ */
+#ifndef BIGMAC_H
+#define BIGMAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { BIGMAC_F32 = 0, BIGMAC_BF16 = 1 } bigmac_dtype;
+typedef enum { BIGMAC_ACT_GELU_ERF = 0 } bigmac_act;             /* 0.5 a (1 + erf(a / sqrt 2)) */
+typedef enum { BIGMAC_ORDER_DCCA = 0, BIGMAC_ORDER_CDAC = 1 } bigmac_order;
+
+enum {
+  BIGMAC_FLAG_ACCUMULATE = 1, /* backward: add weight gradients to the caller's buffers (else overwrite) */
+  BIGMAC_FLAG_OUT_BF16 = 2    /* layer calls with dtype BF16: write y / dx as bf16 (default: fp32)       */
+};
+
+enum {
+  BIGMAC_OK = 0,
+  BIGMAC_ERR_INVALID_ARG = -1,
+  BIGMAC_ERR_WORKSPACE = -2,
+  BIGMAC_ERR_UNSUPPORTED = -3,
+  BIGMAC_ERR_HIP = -4
+};
+
+typedef struct {
+  int32_t T, d, r, N, k, h; /* tokens, model width, low width, experts, top_k, expert hidden width */
+  int32_t dtype, act, order;
+  int32_t flags;
+} bigmac_dims;
+
+typedef struct {          /* parameters: caller-owned, never written                              */
+  const void *w_down;     /* [d, r]   dtype   W'_down of Eq. 2         (ignored for CDAC)          */
+  const void *w_up;       /* [r, d]   dtype   W'_up   of Eq. 2         (ignored for CDAC)          */
+  const float *w_gate;    /* [d, N]   fp32    router weights                                       */
+  const float *gate_bias; /* [N]      fp32 or NULL, added to the logits                            */
+  const void *w1;         /* [N, win, hid] dtype   first expert matrix  (Eq. 4: W_i,up; Eq. 3: W_i,down) */
+  const void *w2;         /* [N, hid, win] dtype   second expert matrix (Eq. 4: W_i,down; Eq. 3: W_i,up) */
+} bigmac_params;
+
+typedef enum {
+  BIGMAC_WS_ROUTE = 0,
+  BIGMAC_WS_DISPATCH = 1,
+  BIGMAC_WS_GROUPED_FFN = 2,
+  BIGMAC_WS_LAYER_FORWARD = 3,   /* inference (saved == NULL)                                      */
+  BIGMAC_WS_LAYER_TRAIN = 4,     /* forward with a saved block, and backward                       */
+  BIGMAC_WS_SAVED = 5            /* size of the saved-activation block of a training forward       */
+} bigmac_ws_kind;
+
+/* Host only, touches no GPU.  Bytes of workspace the given call needs for these dims
+ * (0 if the dims are invalid).  Workspace contents are scratch: undefined after a call. */
+size_t bigmac_workspace_bytes(const bigmac_dims *dims, int kind);
+
+/* Host only.  Static text for a status code. */
+const char *bigmac_status_string(int status);
+
+/* Host only.  Algorithmic work of one call, from the closed forms behind the paper's Table 3:
+ * matrix FLOPs of a forward pass (2 flops per multiply-add, real rows only), and the bytes the
+ * four permutes (two forward, two backward) must move per layer call at this width. */
+double bigmac_forward_matrix_flops(const bigmac_dims *dims);
+double bigmac_permute_bytes(const bigmac_dims *dims);
+
+/* Gating (Section 3.1: the router reads the full-width token x).
+ * logits[t, n] = sum_i x[t, i] w_gate[i, n] (+ gate_bias[n]) in fp32 in a fixed order: 64
+ * partial sums p_l over i = l mod 64 (ascending i, fused multiply-add), then a halving tree
+ * p_l += p_{l+off} for off = 32, 16, 8, 4, 2, 1, then the bias.  topk_idx[t, 0..k) are the k
+ * largest logits in descending order, equal logits to the lowest expert index; topk_w[t, j] is
+ * the softmax over those k logits.  logits_out ([T, N], fp32) may be NULL. */
+int bigmac_route(const bigmac_dims *dims, const void *x /*[T,d] dtype*/, const float *w_gate,
+                 const float *gate_bias, int32_t *topk_idx /*[T,k]*/, float *topk_w /*[T,k]*/,
+                 float *logits_out, void *ws, size_t ws_bytes, void *stream);
+
+/* First All-to-All of Section 3.1 on one device.  Builds the stable counting-sort permutation
+ * of the flat pairs f = t*k + j by expert (expert_offsets [N+1], slot_of [T,k], src_of [T*k]
+ * with src_of[slot_of[f]] = f) and copies x_low[t, :] to x_perm[slot_of[t, j], :] for every j.
+ * x_low is [T, win], x_perm is [T*k, win], both dtype.  x_low == NULL (with x_perm == NULL)
+ * builds the permutation only. */
+int bigmac_dispatch(const bigmac_dims *dims, const void *x_low, const int32_t *topk_idx,
+                    void *x_perm, int32_t *expert_offsets, int32_t *slot_of, int32_t *src_of,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* The experts of Eq. 4 (Eq. 3 for CDAC) on permuted rows: for the rows s of expert e,
+ * o_perm[s, :] = act(x_perm[s, :] W1[e]) W2[e].  act_saved ([T*k, hid] dtype, the
+ * pre-activation x_perm W1) may be NULL. */
+int bigmac_grouped_ffn(const bigmac_dims *dims, const void *x_perm, const int32_t *expert_offsets,
+                       const void *w1, const void *w2, void *act_saved, void *o_perm /*[T*k,win] dtype*/,
+                       void *ws, size_t ws_bytes, void *stream);
+
+/* Second All-to-All plus the weighted sum of Eq. 2: y_low[t, :] = sum_j topk_w[t, j] *
+ * o_perm[slot_of[t, j], :], added in j order in fp32.  topk_w == NULL means unit weights (the
+ * backward of dispatch).  y_low is [T, win] fp32. */
+int bigmac_combine(const bigmac_dims *dims, const void *o_perm, const int32_t *slot_of,
+                   const float *topk_w, float *y_low, void *stream);
+
+/* Whole layer forward (Eq. 2).  y is [T, d]: fp32, or bf16 with BIGMAC_FLAG_OUT_BF16 (always
+ * float for dtype F32).  saved == NULL: inference.  Otherwise `saved` receives the activations
+ * the backward call needs (size: BIGMAC_WS_SAVED) and ws must have BIGMAC_WS_LAYER_TRAIN bytes. */
+int bigmac_layer_forward(const bigmac_dims *dims, const bigmac_params *params, const void *x,
+                         void *y, void *saved, void *ws, size_t ws_bytes, void *stream);
+
+/* Whole layer backward with the top-k set held fixed.  dy is [T, d] dtype, dx is [T, d] (type
+ * as y).  Weight gradients are fp32 with the shapes of their weights and are overwritten, or
+ * added to with BIGMAC_FLAG_ACCUMULATE; d_w_down / d_w_up are ignored for CDAC.  `saved` is
+ * the block written by the forward call with the same dims, params and x. */
+int bigmac_layer_backward(const bigmac_dims *dims, const bigmac_params *params, const void *x,
+                          const void *dy, const void *saved, void *dx, float *d_w_down,
+                          float *d_w_up, float *d_w_gate, float *d_w1, float *d_w2, void *ws,
+                          size_t ws_bytes, void *stream);
+
+/* Views into a saved block, for tests and tools: byte offsets of topk_idx [T,k] int32, topk_w
+ * [T,k] fp32, expert_offsets [N+1] int32 and slot_of [T,k] int32 inside it.  Host only. */
+int bigmac_saved_layout(const bigmac_dims *dims, size_t *off_topk_idx, size_t *off_topk_w,
+                        size_t *off_expert_offsets, size_t *off_slot_of);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BIGMAC_H */

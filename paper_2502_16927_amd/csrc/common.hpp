@@ -1,0 +1,122 @@
+// Internal declarations shared by the translation units of libbigmac (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/bigmac.h"
+
+namespace bigmac {
+
+typedef uint16_t bf16_t;  // bfloat16 bit pattern in memory
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {  // round to nearest even; inputs are finite
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float gelu_f(float a) { return 0.5f * a * (1.0f + erff(a * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float a) {
+  return 0.5f * (1.0f + erff(a * 0.70710678118654752f)) + a * __expf(-0.5f * a * a) * 0.39894228040143268f;
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf2f(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f2bf(v); }
+};
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline int esize(int dtype) { return dtype == BIGMAC_BF16 ? 2 : 4; }
+
+struct Widths {
+  int win, hid;  // dispatch width and expert hidden width for the given order
+};
+inline Widths widths(const bigmac_dims& D) {
+  return D.order == BIGMAC_ORDER_CDAC ? Widths{D.d, D.r} : Widths{D.r, D.h};
+}
+int check_dims(const bigmac_dims* D);  // BIGMAC_OK or an error code
+
+// ----------------------------------------------------------------------------- GEMM -----
+// C[M,N] (op)= A[M,K] . B[K,N], fp32 accumulate.  "k-contiguous" says which index is the fast
+// one in memory: A k-contiguous = A stored [M][K] (lda between rows m), otherwise stored
+// [K][M]; B k-contiguous = B stored [N][K], otherwise stored [K][N].
+enum GemmMode { GEMM_DENSE = 0, GEMM_RAGGED_M = 1, GEMM_RAGGED_K = 2 };
+enum GemmEpilogue {
+  EPI_STORE = 0,   // C = acc                                   (C type: out_f32 ? float : dtype)
+  EPI_GELU = 1,    // aux_out = acc (pre-activation, optional); C = gelu(acc)        (dtype)
+  EPI_DGELU = 2,   // C = acc * gelu'(aux_in)                                        (dtype)
+  EPI_ACCUM = 3    // fp32 C = (beta ? C : 0) + acc
+};
+
+struct GemmDesc {
+  int dtype;                 // BIGMAC_F32 or BIGMAC_BF16: element type of A, B, aux
+  int a_kcontig, b_kcontig;
+  int mode, epilogue;
+  int out_f32;               // EPI_STORE only
+  int beta;                  // EPI_ACCUM only
+  const void* A;
+  const void* B;
+  void* C;
+  const void* aux_in;        // EPI_DGELU: saved pre-activation, same shape/ld as C
+  void* aux_out;             // EPI_GELU: optional pre-activation output, same shape/ld as C
+  long lda, ldb, ldc;
+  int M, N, K;               // dense: all three.  ragged-M: N, K (rows from offsets).  ragged-K: M, N.
+  int groups;                // ragged modes: number of groups (experts)
+  int max_rows;              // ragged-M: total rows (upper bound for the tile count)
+  const int* offsets;        // device [groups+1]: row ranges (ragged-M) or k ranges (ragged-K)
+  const int* tile_map;       // device, ragged-M: [0] = number of tiles, then (group, first row) pairs
+  long gstride_b;            // ragged-M: elements between the B matrices of consecutive groups
+  long gstride_c;            // ragged-K / split-K: elements between consecutive C outputs
+  int ksplit;                // dense: number of K slices (each writes C + z*gstride_c); 1 = none
+  int kwrap_b;               // B's k index is taken modulo this (0 = off); multiple of 64
+};
+// Rows per M tile of the ragged-M schedule for this dtype (the tile map must be built with it).
+int gemm_ragged_tile_rows(int dtype);
+int launch_gemm(const GemmDesc& g, hipStream_t s);
+// tile_map capacity in int32 for a ragged-M problem
+inline size_t tile_map_ints(int total_rows, int groups, int tile_rows) {
+  return 1 + 2 * ((size_t)total_rows / tile_rows + groups + 1);
+}
+int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* tile_map, hipStream_t s);
+// out[i] = (beta ? out[i] : 0) + sum_z part[z*n + i]
+int launch_reduce_partials(const float* part, int nslices, size_t n, float* out, int beta, hipStream_t s);
+
+// ----------------------------------------------------------------------------- route ----
+int launch_route(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias,
+                 int32_t* topk_idx, float* topk_w, float* logits_out, hipStream_t s);
+// Gate backward (softmax over the k picked logits) and the router's share of dx:
+//   dlogit[t,j] = w[t,j] (dgate[t,j] - sum_m w[t,m] dgate[t,m])
+//   dL_out [T,N] (storage dtype) = dlogit scattered to its expert columns, zeros elsewhere
+//   dx_f32[t,:] = sum_j dlogit[t,j] * w_gate[:, idx[t,j]]      (overwritten)
+// ws: route_backward_ws_bytes (a transposed copy of w_gate).
+size_t route_backward_ws_bytes(const bigmac_dims& D);
+int launch_route_backward(const bigmac_dims& D, const float* w_gate, const int32_t* topk_idx,
+                          const float* topk_w, const float* dgate, float* dx_f32, void* dL_out,
+                          void* ws, hipStream_t s);
+
+// ----------------------------------------------------------------------------- permute --
+size_t permutation_ws_bytes(int T, int k, int N);
+int launch_build_permutation(int T, int k, int N, const int32_t* topk_idx, int32_t* expert_offsets,
+                             int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s);
+int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, const int32_t* slot_of,
+                         void* x_perm, hipStream_t s);
+enum CombineOut { COMBINE_F32 = 0, COMBINE_SPLIT_BF16 = 1 };  // fp32 [T,w]  |  bf16 [T,2w] = (hi | lo)
+int launch_combine_rows(int dtype, int T, int k, int width, const void* o_perm, const int32_t* slot_of,
+                        const float* topk_w, void* y_low, int out_kind, hipStream_t s);
+// backward of the weighted combine: dgate[t,j] = <dy_low[t], o_perm[slot]>, do_perm[slot] = w[t,j]*dy_low[t]
+int launch_combine_backward(int dtype, int T, int k, int width, const float* dy_low, const void* o_perm,
+                            const int32_t* slot_of, const float* topk_w, float* dgate, void* do_perm,
+                            hipStream_t s);
+
+#define BIGMAC_CHECK_LAUNCH()                                   \
+  do {                                                          \
+    if (hipGetLastError() != hipSuccess) return BIGMAC_ERR_HIP; \
+  } while (0)
+
+}  // namespace bigmac

@@ -1,0 +1,484 @@
+// C ABI of libbigmac: argument checks, workspace planning and the launch sequences of the
+// layer (Eq. 2 with the expert of Eq. 4; CDAC order with the expert of Eq. 3) and its backward.
+#include "common.hpp"
+
+namespace bigmac {
+
+int check_dims(const bigmac_dims* D) {
+  if (!D) return BIGMAC_ERR_INVALID_ARG;
+  if (D->T < 1 || D->d < 64 || D->r < 64 || D->N < 1 || D->k < 1) return BIGMAC_ERR_INVALID_ARG;
+  if (D->d % 64 || D->r % 64) return BIGMAC_ERR_INVALID_ARG;
+  if (D->order != BIGMAC_ORDER_DCCA && D->order != BIGMAC_ORDER_CDAC) return BIGMAC_ERR_INVALID_ARG;
+  if (D->order == BIGMAC_ORDER_DCCA && (D->h < 64 || D->h % 64)) return BIGMAC_ERR_INVALID_ARG;
+  if (D->k > D->N || D->N > 1024 || D->k > 64) return BIGMAC_ERR_INVALID_ARG;
+  if ((long long)D->T * D->k >= (1ll << 31)) return BIGMAC_ERR_INVALID_ARG;
+  if (D->dtype != BIGMAC_F32 && D->dtype != BIGMAC_BF16) return BIGMAC_ERR_INVALID_ARG;
+  if (D->act != BIGMAC_ACT_GELU_ERF) return BIGMAC_ERR_INVALID_ARG;
+  if (D->flags & ~(BIGMAC_FLAG_ACCUMULATE | BIGMAC_FLAG_OUT_BF16)) return BIGMAC_ERR_INVALID_ARG;
+  if (D->order == BIGMAC_ORDER_CDAC && D->dtype == BIGMAC_BF16 && (D->flags & BIGMAC_FLAG_OUT_BF16)) return BIGMAC_ERR_UNSUPPORTED;
+  return BIGMAC_OK;
+}
+
+namespace {
+
+struct Carver {  // hands out 256-byte aligned pieces of one buffer
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off += align_up(bytes);
+    return o;
+  }
+};
+
+struct SavedPlan {
+  size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, x_perm, act, hact, o_perm, y_low, total;
+};
+struct FwdPlan {
+  size_t logits, perm, x_low, total;
+};
+struct BwdPlan {
+  size_t dy_low, dgate, do_perm, dact, dx_low, dL, route, dx_f32, partials, tmp_f32, total;
+};
+
+inline bool bf(const bigmac_dims& D) { return D.dtype == BIGMAC_BF16; }
+// y' and dx' feed a bf16 MFMA product; they are carried as two bf16 halves (hi | lo) so that
+// the product sees them at fp32 precision.  Row length of that operand:
+inline int low_ld(const bigmac_dims& D) { return bf(D) ? 2 * D.r : D.r; }
+inline size_t low_bytes(const bigmac_dims& D) { return (size_t)D.T * (bf(D) ? 2 * D.r * 2 : D.r * 4); }
+
+SavedPlan plan_saved(const bigmac_dims& D) {
+  const Widths W = widths(D);
+  const size_t Tk = (size_t)D.T * D.k, es = esize(D.dtype);
+  Carver c;
+  SavedPlan p;
+  p.topk_idx = c.take(Tk * 4);
+  p.topk_w = c.take(Tk * 4);
+  p.offsets = c.take((size_t)(D.N + 1) * 4);
+  p.slot_of = c.take(Tk * 4);
+  p.src_of = c.take(Tk * 4);
+  p.tile_map = c.take(tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype)) * 4);
+  p.x_perm = c.take(Tk * W.win * es);
+  p.act = c.take(Tk * W.hid * es);
+  p.hact = c.take(Tk * W.hid * es);
+  p.o_perm = c.take(Tk * W.win * es);
+  p.y_low = c.take(D.order == BIGMAC_ORDER_DCCA ? low_bytes(D) : 0);
+  p.total = c.off;
+  return p;
+}
+
+FwdPlan plan_fwd(const bigmac_dims& D) {
+  Carver c;
+  FwdPlan p;
+  p.logits = c.take((size_t)D.T * D.N * 4);
+  p.perm = c.take(permutation_ws_bytes(D.T, D.k, D.N));
+  p.x_low = c.take(D.order == BIGMAC_ORDER_DCCA ? (size_t)D.T * D.r * esize(D.dtype) : 0);
+  p.total = c.off;
+  return p;
+}
+
+int choose_ksplit(int M, int N, int K) {
+  const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
+  int ks = 1024 / tiles;
+  if (ks > K / 256) ks = K / 256;
+  if (ks > 64) ks = 64;
+  return ks < 1 ? 1 : ks;
+}
+
+BwdPlan plan_bwd(const bigmac_dims& D) {
+  const Widths W = widths(D);
+  const size_t Tk = (size_t)D.T * D.k, es = esize(D.dtype);
+  const bool dcca = D.order == BIGMAC_ORDER_DCCA;
+  Carver c;
+  BwdPlan p;
+  p.dy_low = c.take((size_t)D.T * W.win * 4);
+  p.dgate = c.take(Tk * 4);
+  p.do_perm = c.take(Tk * W.win * es);
+  p.dact = c.take(Tk * W.hid * es);
+  p.dx_low = c.take(dcca ? low_bytes(D) : (size_t)D.T * D.d * 4);
+  p.dL = c.take((size_t)D.T * D.N * es);
+  p.route = c.take(route_backward_ws_bytes(D));
+  p.dx_f32 = c.take((bf(D) && (D.flags & BIGMAC_FLAG_OUT_BF16)) ? (size_t)D.T * D.d * 4 : 0);
+  size_t part = (size_t)choose_ksplit(D.d, D.N, D.T) * D.d * D.N;
+  if (dcca) {
+    const size_t a = (size_t)choose_ksplit(D.r, D.d, D.T) * D.r * D.d;
+    const size_t b = (size_t)choose_ksplit(D.d, D.r, D.T) * D.d * D.r;
+    part = part > a ? part : a;
+    part = part > b ? part : b;
+  }
+  p.partials = c.take(part * 4);
+  p.tmp_f32 = 0;
+  p.total = c.off;
+  return p;
+}
+
+size_t ffn_ws_bytes(const bigmac_dims& D) {
+  const Widths W = widths(D);
+  const size_t Tk = (size_t)D.T * D.k;
+  return align_up(Tk * W.hid * esize(D.dtype)) + align_up(tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype)) * 4);
+}
+
+template <typename ET>
+__global__ void to_f32_kernel(const ET* __restrict__ in, float* __restrict__ out, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = Elem<ET>::load(in + i);
+}
+__global__ void f32_to_bf16_kernel(const float* __restrict__ in, bf16_t* __restrict__ out, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = f2bf(in[i]);
+}
+__global__ void add_f32_kernel(float* __restrict__ acc, const float* __restrict__ in, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) acc[i] += in[i];
+}
+inline dim3 grid1d(size_t n) { return dim3((unsigned)((n + 255) / 256)); }
+
+GemmDesc base_desc(const bigmac_dims& D) {
+  GemmDesc g = {};
+  g.dtype = D.dtype;
+  g.ksplit = 1;
+  g.mode = GEMM_DENSE;
+  return g;
+}
+
+// The two expert products on permuted rows (ragged per-expert row ranges).
+int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* offsets, const int* tile_map,
+                        const void* w1, const void* w2, void* act, void* hact, void* o_perm, hipStream_t s) {
+  const Widths W = widths(D);
+  const int Tk = D.T * D.k;
+  GemmDesc g = base_desc(D);
+  g.mode = GEMM_RAGGED_M;
+  g.a_kcontig = 1; g.b_kcontig = 0;
+  g.groups = D.N; g.max_rows = Tk; g.offsets = offsets; g.tile_map = tile_map;
+  // hact = gelu(x_perm W1[e])
+  g.epilogue = EPI_GELU;
+  g.A = x_perm; g.lda = W.win; g.K = W.win;
+  g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
+  g.C = hact; g.ldc = W.hid; g.aux_out = act;
+  int rc = launch_gemm(g, s);
+  if (rc) return rc;
+  // o_perm = hact W2[e]
+  g.epilogue = EPI_STORE; g.out_f32 = 0; g.aux_out = nullptr;
+  g.A = hact; g.lda = W.hid; g.K = W.hid;
+  g.B = w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.win;
+  g.C = o_perm; g.ldc = W.win;
+  return launch_gemm(g, s);
+}
+
+// dense fp32 C (+)= A^T-style product over the token index, split over K and reduced in a fixed order
+int run_token_wgrad(const bigmac_dims& D, const void* A, long lda, int M, const void* B, long ldb, int N,
+                    float* out, float* partials, hipStream_t s) {
+  GemmDesc g = base_desc(D);
+  g.a_kcontig = 0; g.b_kcontig = 0;
+  g.epilogue = EPI_ACCUM; g.beta = 0;
+  g.A = A; g.lda = lda; g.M = M; g.B = B; g.ldb = ldb; g.N = N; g.K = D.T;
+  g.ksplit = choose_ksplit(M, N, D.T);
+  g.C = partials; g.ldc = N; g.gstride_c = (long)M * N;
+  int rc = launch_gemm(g, s);
+  if (rc) return rc;
+  return launch_reduce_partials(partials, g.ksplit, (size_t)M * N, out, (D.flags & BIGMAC_FLAG_ACCUMULATE) ? 1 : 0, s);
+}
+
+}  // namespace
+}  // namespace bigmac
+
+using namespace bigmac;
+
+extern "C" {
+
+size_t bigmac_workspace_bytes(const bigmac_dims* D, int kind) {
+  if (check_dims(D) != BIGMAC_OK) return 0;
+  switch (kind) {
+    case BIGMAC_WS_ROUTE: return align_up((size_t)D->T * D->N * 4);
+    case BIGMAC_WS_DISPATCH: return permutation_ws_bytes(D->T, D->k, D->N);
+    case BIGMAC_WS_GROUPED_FFN: return ffn_ws_bytes(*D);
+    case BIGMAC_WS_LAYER_FORWARD: return plan_fwd(*D).total + plan_saved(*D).total;
+    case BIGMAC_WS_LAYER_TRAIN: {
+      const size_t f = plan_fwd(*D).total, b = plan_bwd(*D).total;
+      return f > b ? f : b;
+    }
+    case BIGMAC_WS_SAVED: return plan_saved(*D).total;
+    default: return 0;
+  }
+}
+
+const char* bigmac_status_string(int status) {
+  switch (status) {
+    case BIGMAC_OK: return "ok";
+    case BIGMAC_ERR_INVALID_ARG: return "invalid argument (null pointer, bad dimension or enum)";
+    case BIGMAC_ERR_WORKSPACE: return "workspace too small";
+    case BIGMAC_ERR_UNSUPPORTED: return "unsupported combination";
+    case BIGMAC_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+double bigmac_forward_matrix_flops(const bigmac_dims* D) {
+  if (check_dims(D) != BIGMAC_OK) return 0.0;
+  const Widths W = widths(*D);
+  double f = 4.0 * (double)D->T * D->k * W.win * W.hid;
+  if (D->order == BIGMAC_ORDER_DCCA) f += 4.0 * (double)D->T * D->d * D->r;
+  return f;
+}
+
+double bigmac_permute_bytes(const bigmac_dims* D) {
+  if (check_dims(D) != BIGMAC_OK) return 0.0;
+  return 4.0 * (double)D->T * D->k * widths(*D).win * esize(D->dtype);
+}
+
+int bigmac_saved_layout(const bigmac_dims* D, size_t* off_topk_idx, size_t* off_topk_w, size_t* off_expert_offsets,
+                        size_t* off_slot_of) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  const SavedPlan p = plan_saved(*D);
+  if (off_topk_idx) *off_topk_idx = p.topk_idx;
+  if (off_topk_w) *off_topk_w = p.topk_w;
+  if (off_expert_offsets) *off_expert_offsets = p.offsets;
+  if (off_slot_of) *off_slot_of = p.slot_of;
+  return BIGMAC_OK;
+}
+
+int bigmac_route(const bigmac_dims* D, const void* x, const float* w_gate, const float* gate_bias, int32_t* topk_idx,
+                 float* topk_w, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  if (!x || !w_gate || !topk_idx || !topk_w) return BIGMAC_ERR_INVALID_ARG;
+  float* logits = logits_out;
+  if (!logits) {
+    if (!ws) return BIGMAC_ERR_INVALID_ARG;
+    if (ws_bytes < bigmac_workspace_bytes(D, BIGMAC_WS_ROUTE)) return BIGMAC_ERR_WORKSPACE;
+    logits = (float*)ws;
+  }
+  return launch_route(*D, x, w_gate, gate_bias, topk_idx, topk_w, logits, (hipStream_t)stream);
+}
+
+int bigmac_dispatch(const bigmac_dims* D, const void* x_low, const int32_t* topk_idx, void* x_perm, int32_t* expert_offsets,
+                    int32_t* slot_of, int32_t* src_of, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  if (!topk_idx || !expert_offsets || !slot_of || !src_of || !ws) return BIGMAC_ERR_INVALID_ARG;
+  if ((x_low == nullptr) != (x_perm == nullptr)) return BIGMAC_ERR_INVALID_ARG;
+  if (ws_bytes < bigmac_workspace_bytes(D, BIGMAC_WS_DISPATCH)) return BIGMAC_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  rc = launch_build_permutation(D->T, D->k, D->N, topk_idx, expert_offsets, slot_of, src_of, ws, s);
+  if (rc || !x_low) return rc;
+  return launch_dispatch_rows(D->dtype, D->T, D->k, widths(*D).win, x_low, slot_of, x_perm, s);
+}
+
+int bigmac_grouped_ffn(const bigmac_dims* D, const void* x_perm, const int32_t* expert_offsets, const void* w1, const void* w2,
+                       void* act_saved, void* o_perm, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  if (!x_perm || !expert_offsets || !w1 || !w2 || !o_perm || !ws) return BIGMAC_ERR_INVALID_ARG;
+  if (ws_bytes < ffn_ws_bytes(*D)) return BIGMAC_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const Widths W = widths(*D);
+  const size_t Tk = (size_t)D->T * D->k;
+  void* hact = ws;
+  int* tile_map = (int*)((char*)ws + align_up(Tk * W.hid * esize(D->dtype)));
+  rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype), tile_map, s);
+  if (rc) return rc;
+  return run_experts_forward(*D, x_perm, expert_offsets, tile_map, w1, w2, act_saved, hact, o_perm, s);
+}
+
+int bigmac_combine(const bigmac_dims* D, const void* o_perm, const int32_t* slot_of, const float* topk_w, float* y_low, void* stream) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  if (!o_perm || !slot_of || !y_low) return BIGMAC_ERR_INVALID_ARG;
+  return launch_combine_rows(D->dtype, D->T, D->k, widths(*D).win, o_perm, slot_of, topk_w, y_low, COMBINE_F32, (hipStream_t)stream);
+}
+
+int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const void* x, void* y, void* saved, void* ws,
+                         size_t ws_bytes, void* stream) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  const bool dcca = D->order == BIGMAC_ORDER_DCCA;
+  if (!P || !x || !y || !ws || !P->w_gate || !P->w1 || !P->w2) return BIGMAC_ERR_INVALID_ARG;
+  if (dcca && (!P->w_down || !P->w_up)) return BIGMAC_ERR_INVALID_ARG;
+  if (ws_bytes < bigmac_workspace_bytes(D, saved ? BIGMAC_WS_LAYER_TRAIN : BIGMAC_WS_LAYER_FORWARD)) return BIGMAC_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const Widths W = widths(*D);
+  const FwdPlan F = plan_fwd(*D);
+  const SavedPlan S = plan_saved(*D);
+  char* wsb = (char*)ws;
+  char* sv = saved ? (char*)saved : wsb + F.total;  // inference keeps the same pieces in the workspace
+  int32_t* topk_idx = (int32_t*)(sv + S.topk_idx);
+  float* topk_w = (float*)(sv + S.topk_w);
+  int32_t* offsets = (int32_t*)(sv + S.offsets);
+  int32_t* slot_of = (int32_t*)(sv + S.slot_of);
+  int32_t* src_of = (int32_t*)(sv + S.src_of);
+  int* tile_map = (int*)(sv + S.tile_map);
+  void* x_perm = sv + S.x_perm;
+  void* act = saved ? sv + S.act : nullptr;
+  void* hact = sv + S.hact;
+  void* o_perm = sv + S.o_perm;
+  void* y_low = sv + S.y_low;
+  const bool out_bf16 = bf(*D) && (D->flags & BIGMAC_FLAG_OUT_BF16);
+
+  rc = launch_route(*D, x, P->w_gate, P->gate_bias, topk_idx, topk_w, (float*)(wsb + F.logits), s);
+  if (rc) return rc;
+  const void* x_low = x;
+  if (dcca) {  // x' = x W_down
+    GemmDesc g = base_desc(*D);
+    g.a_kcontig = 1; g.b_kcontig = 0; g.epilogue = EPI_STORE; g.out_f32 = bf(*D) ? 0 : 1;
+    g.A = x; g.lda = D->d; g.M = D->T; g.K = D->d;
+    g.B = P->w_down; g.ldb = D->r; g.N = D->r;
+    g.C = wsb + F.x_low; g.ldc = D->r;
+    rc = launch_gemm(g, s);
+    if (rc) return rc;
+    x_low = wsb + F.x_low;
+  }
+  rc = launch_build_permutation(D->T, D->k, D->N, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s);
+  if (rc) return rc;
+  rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype), tile_map, s);
+  if (rc) return rc;
+  rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);
+  if (rc) return rc;
+  rc = run_experts_forward(*D, x_perm, offsets, tile_map, P->w1, P->w2, act, hact, o_perm, s);
+  if (rc) return rc;
+  if (!dcca) {  // fine-grained layer: the weighted sum is the output
+    return launch_combine_rows(D->dtype, D->T, D->k, W.win, o_perm, slot_of, topk_w, y, COMBINE_F32, s);
+  }
+  rc = launch_combine_rows(D->dtype, D->T, D->k, W.win, o_perm, slot_of, topk_w, y_low, bf(*D) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
+  if (rc) return rc;
+  {  // y = y' W_up
+    GemmDesc g = base_desc(*D);
+    g.a_kcontig = 1; g.b_kcontig = 0; g.epilogue = EPI_STORE; g.out_f32 = out_bf16 ? 0 : 1;
+    g.A = y_low; g.lda = low_ld(*D); g.M = D->T; g.K = low_ld(*D);
+    g.B = P->w_up; g.ldb = D->d; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
+    g.C = y; g.ldc = D->d;
+    rc = launch_gemm(g, s);
+  }
+  return rc;
+}
+
+int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const void* x, const void* dy, const void* saved,
+                          void* dx, float* d_w_down, float* d_w_up, float* d_w_gate, float* d_w1, float* d_w2, void* ws,
+                          size_t ws_bytes, void* stream) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  const bool dcca = D->order == BIGMAC_ORDER_DCCA;
+  if (!P || !x || !dy || !saved || !dx || !ws || !d_w_gate || !d_w1 || !d_w2 || !P->w_gate || !P->w1 || !P->w2)
+    return BIGMAC_ERR_INVALID_ARG;
+  if (dcca && (!P->w_down || !P->w_up || !d_w_down || !d_w_up)) return BIGMAC_ERR_INVALID_ARG;
+  if (bf(*D) && D->N % 8) return BIGMAC_ERR_UNSUPPORTED;  // the dense logit gradient has 16-byte rows
+  if (ws_bytes < bigmac_workspace_bytes(D, BIGMAC_WS_LAYER_TRAIN)) return BIGMAC_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const Widths W = widths(*D);
+  const SavedPlan S = plan_saved(*D);
+  const BwdPlan B = plan_bwd(*D);
+  const char* sv = (const char*)saved;
+  char* wsb = (char*)ws;
+  const int32_t* topk_idx = (const int32_t*)(sv + S.topk_idx);
+  const float* topk_w = (const float*)(sv + S.topk_w);
+  const int32_t* offsets = (const int32_t*)(sv + S.offsets);
+  const int32_t* slot_of = (const int32_t*)(sv + S.slot_of);
+  const int* tile_map = (const int*)(sv + S.tile_map);
+  const void* x_perm = sv + S.x_perm;
+  const void* act = sv + S.act;
+  const void* hact = sv + S.hact;
+  const void* o_perm = sv + S.o_perm;
+  const void* y_low = sv + S.y_low;
+  float* dy_low = (float*)(wsb + B.dy_low);
+  float* dgate = (float*)(wsb + B.dgate);
+  void* do_perm = wsb + B.do_perm;
+  void* dact = wsb + B.dact;
+  void* dx_perm = do_perm;  // do_perm is dead once the second expert matrix's gradients are done
+  void* dx_low = wsb + B.dx_low;
+  void* dL = wsb + B.dL;
+  float* partials = (float*)(wsb + B.partials);
+  const bool out_bf16 = bf(*D) && (D->flags & BIGMAC_FLAG_OUT_BF16);
+  float* dx_f32 = out_bf16 ? (float*)(wsb + B.dx_f32) : (float*)dx;
+  const int accumulate = (D->flags & BIGMAC_FLAG_ACCUMULATE) ? 1 : 0;
+  const int Tk = D->T * D->k;
+  const size_t Td = (size_t)D->T * D->d;
+
+  if (dcca) {
+    // dy' = dy W_up^T (kept in fp32)
+    GemmDesc g = base_desc(*D);
+    g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE; g.out_f32 = 1;
+    g.A = dy; g.lda = D->d; g.M = D->T; g.K = D->d;
+    g.B = P->w_up; g.ldb = D->d; g.N = D->r;
+    g.C = dy_low; g.ldc = D->r;
+    rc = launch_gemm(g, s);
+    if (rc) return rc;
+    // dW_up (+)= y'^T dy
+    rc = run_token_wgrad(*D, y_low, low_ld(*D), D->r, dy, D->d, D->d, d_w_up, partials, s);
+    if (rc) return rc;
+  } else {
+    if (bf(*D)) hipLaunchKernelGGL(to_f32_kernel<bf16_t>, grid1d(Td), dim3(256), 0, s, (const bf16_t*)dy, dy_low, Td);
+    else hipLaunchKernelGGL(to_f32_kernel<float>, grid1d(Td), dim3(256), 0, s, (const float*)dy, dy_low, Td);
+    BIGMAC_CHECK_LAUNCH();
+  }
+  // weighted-sum backward: gate gradients and the scaled scatter of dy' to the expert rows
+  rc = launch_combine_backward(D->dtype, D->T, D->k, W.win, dy_low, o_perm, slot_of, topk_w, dgate, do_perm, s);
+  if (rc) return rc;
+  {  // dact = (do_perm W2[e]^T) * act'(act)
+    GemmDesc g = base_desc(*D);
+    g.mode = GEMM_RAGGED_M; g.groups = D->N; g.max_rows = Tk; g.offsets = offsets; g.tile_map = tile_map;
+    g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_DGELU;
+    g.A = do_perm; g.lda = W.win; g.K = W.win;
+    g.B = P->w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.hid;
+    g.C = dact; g.ldc = W.hid; g.aux_in = act;
+    rc = launch_gemm(g, s);
+    if (rc) return rc;
+  }
+  {  // dW2[e] (+)= hact_e^T do_perm_e
+    GemmDesc g = base_desc(*D);
+    g.mode = GEMM_RAGGED_K; g.groups = D->N; g.offsets = offsets;
+    g.a_kcontig = 0; g.b_kcontig = 0; g.epilogue = EPI_ACCUM; g.beta = accumulate;
+    g.A = hact; g.lda = W.hid; g.M = W.hid;
+    g.B = do_perm; g.ldb = W.win; g.N = W.win;
+    g.C = d_w2; g.ldc = W.win; g.gstride_c = (long)W.hid * W.win;
+    rc = launch_gemm(g, s);
+    if (rc) return rc;
+    // dW1[e] (+)= x_perm_e^T dact_e
+    g.A = x_perm; g.lda = W.win; g.M = W.win;
+    g.B = dact; g.ldb = W.hid; g.N = W.hid;
+    g.C = d_w1; g.ldc = W.hid; g.gstride_c = (long)W.win * W.hid;
+    rc = launch_gemm(g, s);
+    if (rc) return rc;
+  }
+  {  // dx_perm = dact W1[e]^T
+    GemmDesc g = base_desc(*D);
+    g.mode = GEMM_RAGGED_M; g.groups = D->N; g.max_rows = Tk; g.offsets = offsets; g.tile_map = tile_map;
+    g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE; g.out_f32 = bf(*D) ? 0 : 1;
+    g.A = dact; g.lda = W.hid; g.K = W.hid;
+    g.B = P->w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.win;
+    g.C = dx_perm; g.ldc = W.win;
+    rc = launch_gemm(g, s);
+    if (rc) return rc;
+  }
+  // dispatch backward: dx' = sum_j dx_perm[slot_of[t, j]]
+  rc = launch_combine_rows(D->dtype, D->T, D->k, W.win, dx_perm, slot_of, nullptr, dx_low,
+                           (dcca && bf(*D)) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
+  if (rc) return rc;
+  // gate backward; the router's share of dx is written to dx_f32
+  rc = launch_route_backward(*D, P->w_gate, topk_idx, topk_w, dgate, dx_f32, dL, wsb + B.route, s);
+  if (rc) return rc;
+  // dW_g (+)= x^T dL
+  rc = run_token_wgrad(*D, x, D->d, D->d, dL, D->N, D->N, d_w_gate, partials, s);
+  if (rc) return rc;
+  if (dcca) {
+    // dW_down (+)= x^T dx'
+    rc = run_token_wgrad(*D, x, D->d, D->d, dx_low, low_ld(*D), D->r, d_w_down, partials, s);
+    if (rc) return rc;
+    // dx += dx' W_down^T
+    GemmDesc g = base_desc(*D);
+    g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ACCUM; g.beta = 1;
+    g.A = dx_low; g.lda = low_ld(*D); g.M = D->T; g.K = low_ld(*D);
+    g.B = P->w_down; g.ldb = D->r; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
+    g.C = dx_f32; g.ldc = D->d;
+    rc = launch_gemm(g, s);
+    if (rc) return rc;
+  } else {
+    hipLaunchKernelGGL(add_f32_kernel, grid1d(Td), dim3(256), 0, s, dx_f32, (const float*)dx_low, Td);
+    BIGMAC_CHECK_LAUNCH();
+  }
+  if (out_bf16) {
+    hipLaunchKernelGGL(f32_to_bf16_kernel, grid1d(Td), dim3(256), 0, s, dx_f32, (bf16_t*)dx, Td);
+    BIGMAC_CHECK_LAUNCH();
+  }
+  return BIGMAC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,254 @@
+// The two All-to-Alls of the layer (Section 3.1) as on-device permutes of win-wide rows:
+// a stable counting sort of the (token, choice) pairs by expert, a row scatter (dispatch), a
+// weighted row gather-sum (combine, the middle term of Eq. 2) and their backward forms.
+// Slot assignment uses no atomics whose order could matter: counts are order-free, ranks come
+// from ballots inside one wavefront walking its chunk in order.
+#include "common.hpp"
+
+namespace bigmac {
+
+namespace {
+
+constexpr int P_CHUNK = 1024;  // flat pairs per chunk of the counting sort
+
+// counts[c][e] = number of pairs of chunk c routed to expert e
+__global__ __launch_bounds__(256) void perm_count_kernel(const int32_t* __restrict__ idx, int Tk, int N, int32_t* __restrict__ counts) {
+  extern __shared__ int cnt[];
+  for (int e = threadIdx.x; e < N; e += 256) cnt[e] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * P_CHUNK;
+  for (int i = threadIdx.x; i < P_CHUNK; i += 256) {
+    const int f = base + i;
+    if (f < Tk) atomicAdd(&cnt[idx[f]], 1);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < N; e += 256) counts[(size_t)blockIdx.x * N + e] = cnt[e];
+}
+
+// in place: counts[c][e] -> first slot of expert e's pairs of chunk c;  offsets[e] = first slot of e
+__global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ counts, int nchunks, int N, int32_t* __restrict__ offsets) {
+  __shared__ int scan[1024];
+  const int e = threadIdx.x;
+  int total = 0;
+  if (e < N)
+    for (int c = 0; c < nchunks; ++c) total += counts[(size_t)c * N + e];
+  scan[e] = total;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    int v = e >= off ? scan[e - off] : 0;
+    __syncthreads();
+    scan[e] += v;
+    __syncthreads();
+  }
+  if (e < N) {
+    int run = scan[e] - total;
+    offsets[e] = run;
+    for (int c = 0; c < nchunks; ++c) {
+      int v = counts[(size_t)c * N + e];
+      counts[(size_t)c * N + e] = run;
+      run += v;
+    }
+    if (e == N - 1) offsets[N] = run;
+  }
+}
+
+// One wavefront per chunk walks its pairs in flat order, 64 at a time.  A pair's slot is the
+// running first-free slot of its expert plus the number of earlier lanes with the same expert.
+__global__ __launch_bounds__(64) void perm_rank_kernel(const int32_t* __restrict__ idx, int Tk, int N, int nbits,
+                                                       const int32_t* __restrict__ base, int32_t* __restrict__ slot_of,
+                                                       int32_t* __restrict__ src_of) {
+  extern __shared__ int run[];
+  const int lane = threadIdx.x;
+  for (int e = lane; e < N; e += 64) run[e] = base[(size_t)blockIdx.x * N + e];
+  __syncthreads();
+  const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  for (int i = 0; i < P_CHUNK; i += 64) {
+    const int f = blockIdx.x * P_CHUNK + i + lane;
+    const bool live = f < Tk;
+    const int e = live ? idx[f] : 0;
+    unsigned long long same = __ballot(live);
+    for (int b = 0; b < nbits; ++b) {
+      const unsigned long long bal = __ballot((e >> b) & 1);
+      same &= ((e >> b) & 1) ? bal : ~bal;
+    }
+    if (live) {
+      const int slot = run[e] + __popcll(same & below);
+      slot_of[f] = slot;
+      src_of[slot] = f;
+    }
+    __syncthreads();
+    if (live && (same >> lane) == 1ull) run[e] += __popcll(same);  // highest lane of each expert group
+    __syncthreads();
+  }
+}
+
+// 16-byte chunks: thread (t, c) copies chunk c of row t to its k destination rows
+__global__ __launch_bounds__(256) void dispatch_rows_kernel(const uint4* __restrict__ x_low, const int32_t* __restrict__ slot_of,
+                                                            uint4* __restrict__ x_perm, int T, int k, int cpr) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= (size_t)T * cpr) return;
+  const int t = (int)(g / cpr), c = (int)(g % cpr);
+  const uint4 v = x_low[g];
+  for (int j = 0; j < k; ++j) x_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c] = v;
+}
+
+__device__ __forceinline__ void unpack8(const uint4& v, float* f) {
+  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+  uint4 v;
+  v.x = (uint32_t)f2bf(f[0]) | ((uint32_t)f2bf(f[1]) << 16);
+  v.y = (uint32_t)f2bf(f[2]) | ((uint32_t)f2bf(f[3]) << 16);
+  v.z = (uint32_t)f2bf(f[4]) | ((uint32_t)f2bf(f[5]) << 16);
+  v.w = (uint32_t)f2bf(f[6]) | ((uint32_t)f2bf(f[7]) << 16);
+  return v;
+}
+
+// y_low[t] = sum_j w[t,j] * o_perm[slot_of[t,j]], j ascending, fp32.  Thread = (token, 8 columns).
+template <int OUT>
+__global__ __launch_bounds__(256) void combine_rows_bf16_kernel(const uint4* __restrict__ o_perm, const int32_t* __restrict__ slot_of,
+                                                                const float* __restrict__ w, void* __restrict__ y, int T, int k, int width) {
+  const int cpr = width / 8;
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= (size_t)T * cpr) return;
+  const int t = (int)(g / cpr), c = (int)(g % cpr);
+  float acc[8] = {};
+  for (int j = 0; j < k; ++j) {
+    const float wj = w ? w[(size_t)t * k + j] : 1.0f;
+    float o[8];
+    unpack8(o_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c], o);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = fmaf(wj, o[i], acc[i]);
+  }
+  if (OUT == COMBINE_F32) {
+    float4* out = (float4*)((float*)y + (size_t)t * width + c * 8);
+    out[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    out[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  } else {  // bf16 (hi | lo): acc = hi + lo up to 2^-17 relative
+    float lo[8];
+    uint4 hi = pack8(acc);
+    float hf[8];
+    unpack8(hi, hf);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) lo[i] = acc[i] - hf[i];
+    uint4* out = (uint4*)((bf16_t*)y + (size_t)t * 2 * width);
+    out[c] = hi;
+    out[cpr + c] = pack8(lo);
+  }
+}
+
+__global__ __launch_bounds__(256) void combine_rows_f32_kernel(const float4* __restrict__ o_perm, const int32_t* __restrict__ slot_of,
+                                                               const float* __restrict__ w, float4* __restrict__ y, int T, int k, int width) {
+  const int cpr = width / 4;
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= (size_t)T * cpr) return;
+  const int t = (int)(g / cpr), c = (int)(g % cpr);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int j = 0; j < k; ++j) {
+    const float wj = w ? w[(size_t)t * k + j] : 1.0f;
+    const float4 o = o_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c];
+    acc.x = fmaf(wj, o.x, acc.x); acc.y = fmaf(wj, o.y, acc.y);
+    acc.z = fmaf(wj, o.z, acc.z); acc.w = fmaf(wj, o.w, acc.w);
+  }
+  y[g] = acc;
+}
+
+// One wavefront per token: dgate[t,j] = <dy_low[t], o_perm[slot]>; do_perm[slot] = w[t,j] * dy_low[t].
+template <typename ET>
+__global__ __launch_bounds__(256) void combine_backward_kernel(const float* __restrict__ dy_low, const ET* __restrict__ o_perm,
+                                                               const int32_t* __restrict__ slot_of, const float* __restrict__ w,
+                                                               float* __restrict__ dgate, ET* __restrict__ do_perm, int T, int k, int width) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  for (int j = 0; j < k; ++j) {
+    const size_t slot = (size_t)slot_of[(size_t)t * k + j];
+    const float wj = w[(size_t)t * k + j];
+    float dot = 0.0f;
+    for (int c0 = 0; c0 < width; c0 += 256) {
+      const int c = c0 + lane * 4;
+      if (c < width) {
+        const float4 g = *(const float4*)(dy_low + (size_t)t * width + c);
+        const ET* o = o_perm + slot * width + c;
+        ET* q = do_perm + slot * width + c;
+        dot = fmaf(g.x, Elem<ET>::load(o + 0), dot); dot = fmaf(g.y, Elem<ET>::load(o + 1), dot);
+        dot = fmaf(g.z, Elem<ET>::load(o + 2), dot); dot = fmaf(g.w, Elem<ET>::load(o + 3), dot);
+        Elem<ET>::store(q + 0, wj * g.x); Elem<ET>::store(q + 1, wj * g.y);
+        Elem<ET>::store(q + 2, wj * g.z); Elem<ET>::store(q + 3, wj * g.w);
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
+    if (lane == 0) dgate[(size_t)t * k + j] = dot;
+  }
+}
+
+}  // namespace
+
+size_t permutation_ws_bytes(int T, int k, int N) {
+  const size_t nchunks = ((size_t)T * k + P_CHUNK - 1) / P_CHUNK;
+  return align_up(nchunks * N * sizeof(int32_t));
+}
+
+int launch_build_permutation(int T, int k, int N, const int32_t* topk_idx, int32_t* expert_offsets,
+                             int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s) {
+  const int Tk = T * k;
+  const int nchunks = (Tk + P_CHUNK - 1) / P_CHUNK;
+  int nbits = 0;
+  while ((1 << nbits) < N) ++nbits;
+  int32_t* counts = (int32_t*)ws;
+  hipLaunchKernelGGL(perm_count_kernel, dim3(nchunks), dim3(256), N * sizeof(int), s, topk_idx, Tk, N, counts);
+  BIGMAC_CHECK_LAUNCH();
+  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, counts, nchunks, N, expert_offsets);
+  BIGMAC_CHECK_LAUNCH();
+  hipLaunchKernelGGL(perm_rank_kernel, dim3(nchunks), dim3(64), N * sizeof(int), s, topk_idx, Tk, N, nbits, counts, slot_of, src_of);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, const int32_t* slot_of,
+                         void* x_perm, hipStream_t s) {
+  const int cpr = width * esize(dtype) / 16;
+  const size_t n = (size_t)T * cpr;
+  hipLaunchKernelGGL(dispatch_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const uint4*)x_low, slot_of,
+                     (uint4*)x_perm, T, k, cpr);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+int launch_combine_rows(int dtype, int T, int k, int width, const void* o_perm, const int32_t* slot_of,
+                        const float* topk_w, void* y_low, int out_kind, hipStream_t s) {
+  if (dtype == BIGMAC_BF16) {
+    const size_t n = (size_t)T * (width / 8);
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (out_kind == COMBINE_F32)
+      hipLaunchKernelGGL(combine_rows_bf16_kernel<COMBINE_F32>, grid, block, 0, s, (const uint4*)o_perm, slot_of, topk_w, y_low, T, k, width);
+    else
+      hipLaunchKernelGGL(combine_rows_bf16_kernel<COMBINE_SPLIT_BF16>, grid, block, 0, s, (const uint4*)o_perm, slot_of, topk_w, y_low, T, k, width);
+  } else {
+    if (out_kind != COMBINE_F32) return BIGMAC_ERR_UNSUPPORTED;
+    const size_t n = (size_t)T * (width / 4);
+    hipLaunchKernelGGL(combine_rows_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float4*)o_perm, slot_of,
+                       topk_w, (float4*)y_low, T, k, width);
+  }
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+int launch_combine_backward(int dtype, int T, int k, int width, const float* dy_low, const void* o_perm,
+                            const int32_t* slot_of, const float* topk_w, float* dgate, void* do_perm, hipStream_t s) {
+  const dim3 grid((T + 3) / 4), block(256);
+  if (dtype == BIGMAC_BF16)
+    hipLaunchKernelGGL(combine_backward_kernel<bf16_t>, grid, block, 0, s, dy_low, (const bf16_t*)o_perm, slot_of, topk_w, dgate,
+                       (bf16_t*)do_perm, T, k, width);
+  else
+    hipLaunchKernelGGL(combine_backward_kernel<float>, grid, block, 0, s, dy_low, (const float*)o_perm, slot_of, topk_w, dgate,
+                       (float*)do_perm, T, k, width);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+}  // namespace bigmac

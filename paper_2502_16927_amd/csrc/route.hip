@@ -1,0 +1,228 @@
+// Gating of the BigMac layer (Section 3.1: the router reads the full-width token x; T is the
+// set of top_k experts, p_i the gate value).  The logits decide integers, so their fp32
+// summation order is fixed and every product is a fused multiply-add:
+//   p_l  = fma(x[t, 64q + l], W_g[64q + l, n], p_l),  q ascending, l = 0..63   (one lane each)
+//   tree = p_l + p_{l+off} for off = 32, 16, 8, 4, 2, 1;  logit = tree (+ bias[n], added last)
+// The tree is evaluated as a reduce-scatter over the wavefront: same pairs, 1/6 of the adds.
+#include "common.hpp"
+
+namespace bigmac {
+
+namespace {
+
+constexpr int R_TB = 8;     // tokens per wave
+constexpr int R_NB = 16;    // experts per pass
+constexpr int R_QT = 4;     // 64-row blocks of W_g staged per LDS tile
+constexpr int R_PAD = 20;   // floats per staged row (16 + 4: conflict-free 16-byte reads)
+
+template <typename XT>
+__global__ __launch_bounds__(256) void router_logits_kernel(const XT* __restrict__ x, const float* __restrict__ wg,
+                                                            const float* __restrict__ bias, float* __restrict__ logits,
+                                                            int T, int d, int N) {
+  __shared__ float sw[R_QT * 64 * R_PAD];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t0 = blockIdx.x * (4 * R_TB) + wave * R_TB;
+  const int nq = d / 64;
+  for (int n0 = 0; n0 < N; n0 += R_NB) {
+    float acc[R_TB * R_NB];
+#pragma unroll
+    for (int v = 0; v < R_TB * R_NB; ++v) acc[v] = 0.0f;
+    for (int q0 = 0; q0 < nq; q0 += R_QT) {
+      __syncthreads();
+      for (int e = threadIdx.x; e < R_QT * 64 * R_NB; e += 256) {
+        const int row = e / R_NB, c = e % R_NB;
+        const int gi = q0 * 64 + row, gn = n0 + c;
+        sw[row * R_PAD + c] = (gi < d && gn < N) ? wg[(size_t)gi * N + gn] : 0.0f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int qq = 0; qq < R_QT; ++qq) {
+        if (q0 + qq >= nq) break;
+        float xv[R_TB];
+#pragma unroll
+        for (int i = 0; i < R_TB; ++i) {
+          const int t = t0 + i;
+          xv[i] = t < T ? Elem<XT>::load(x + (size_t)t * d + (size_t)(q0 + qq) * 64 + lane) : 0.0f;
+        }
+        const float4* wrow = (const float4*)(sw + (qq * 64 + lane) * R_PAD);
+        float wv[R_NB];
+#pragma unroll
+        for (int c4 = 0; c4 < R_NB / 4; ++c4) {
+          float4 w = wrow[c4];
+          wv[c4 * 4 + 0] = w.x; wv[c4 * 4 + 1] = w.y; wv[c4 * 4 + 2] = w.z; wv[c4 * 4 + 3] = w.w;
+        }
+#pragma unroll
+        for (int i = 0; i < R_TB; ++i)
+#pragma unroll
+          for (int c = 0; c < R_NB; ++c) acc[i * R_NB + c] = fmaf(xv[i], wv[c], acc[i * R_NB + c]);
+      }
+    }
+    // halving tree as a reduce-scatter: at distance off the lanes with that bit set keep the
+    // upper half of the values, the others the lower half; value 2*lane + {0,1} ends on lane.
+#pragma unroll
+    for (int off = 32, half = R_TB * R_NB / 2; off >= 1; off >>= 1, half >>= 1) {
+      const bool hi = (lane & off) != 0;
+#pragma unroll
+      for (int v = 0; v < half; ++v) {
+        const float send = hi ? acc[v] : acc[v + half];
+        const float keep = hi ? acc[v + half] : acc[v];
+        acc[v] = keep + __shfl_xor(send, off, 64);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int v = 2 * lane + u;
+      const int t = t0 + v / R_NB, n = n0 + v % R_NB;
+      if (t < T && n < N) {
+        float val = acc[u];
+        if (bias) val = val + bias[n];
+        logits[(size_t)t * N + n] = val;
+      }
+    }
+  }
+}
+
+// One wavefront per token: k rounds of arg-max over the remaining logits (ties to the lowest
+// index), then the softmax over the k picked logits.  PER = logits held per lane.
+template <int PER>
+__global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict__ logits, int T, int N, int k,
+                                                        int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  float v[PER];
+  bool taken[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int n = i * 64 + lane;
+    v[i] = n < N ? logits[(size_t)t * N + n] : -INFINITY;
+    taken[i] = n >= N;
+  }
+  float selv = 0.0f;
+  int seli = 0;
+  for (int j = 0; j < k; ++j) {
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+      if (!taken[i] && (bi == 0x7FFFFFFF || v[i] > bv)) { bv = v[i]; bi = i * 64 + lane; }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(bv, off, 64);
+      const int oi = __shfl_xor(bi, off, 64);
+      if (oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+      if (bi == i * 64 + lane) taken[i] = true;
+    if (lane == j) { selv = bv; seli = bi; }
+  }
+  const float m = __shfl(selv, 0, 64);
+  const float e = lane < k ? expf(selv - m) : 0.0f;
+  float s = 0.0f;
+  for (int j = 0; j < k; ++j) s += __shfl(e, j, 64);
+  if (lane < k) {
+    topk_idx[(size_t)t * k + lane] = seli;
+    topk_w[(size_t)t * k + lane] = e / s;
+  }
+}
+
+__global__ void transpose_f32_kernel(const float* __restrict__ in, float* __restrict__ out, int rows, int cols) {
+  __shared__ float tile[32][33];
+  int c = blockIdx.x * 32 + threadIdx.x, r0 = blockIdx.y * 32;
+  for (int i = threadIdx.y; i < 32; i += 8)
+    if (r0 + i < rows && c < cols) tile[i][threadIdx.x] = in[(size_t)(r0 + i) * cols + c];
+  __syncthreads();
+  int r = r0 + threadIdx.x, c0 = blockIdx.x * 32;
+  for (int i = threadIdx.y; i < 32; i += 8)
+    if (c0 + i < cols && r < rows) out[(size_t)(c0 + i) * rows + r] = tile[threadIdx.x][i];
+}
+
+// Backward of the gate (softmax over the k picked logits) and the router's share of dx.
+// One wavefront per token.  dL (dense [T, N], storage type DT) feeds d_w_gate = x^T dL.
+template <typename DT>
+__global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
+                                                            const float* __restrict__ dgate, const float* __restrict__ wg_t /*[N,d]*/,
+                                                            DT* __restrict__ dL, float* __restrict__ dx, int T, int d, int N, int k) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  float w = 0.0f, g = 0.0f;
+  int e = 0;
+  if (lane < k) {
+    w = topk_w[(size_t)t * k + lane];
+    g = dgate[(size_t)t * k + lane];
+    e = topk_idx[(size_t)t * k + lane];
+  }
+  float mix = 0.0f;
+  for (int j = 0; j < k; ++j) mix = fmaf(__shfl(w, j, 64), __shfl(g, j, 64), mix);
+  const float dl = w * (g - mix);
+  // every lane takes part in the shuffles (uniform trip counts); only loads and stores are guarded
+  for (int n0 = 0; n0 < N; n0 += 64) {   // dense row of dL: the k picked experts, zeros elsewhere
+    const int n = n0 + lane;
+    float val = 0.0f;
+    for (int j = 0; j < k; ++j) {
+      const float dj = __shfl(dl, j, 64);
+      if (__shfl(e, j, 64) == n) val = dj;
+    }
+    if (n < N) Elem<DT>::store(dL + (size_t)t * N + n, val);
+  }
+  for (int c0 = 0; c0 < d; c0 += 256) {
+    const int c = c0 + lane * 4;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < k; ++j) {
+      const float dj = __shfl(dl, j, 64);
+      const int ej = __shfl(e, j, 64);
+      if (c < d) {
+        const float4 wv = *(const float4*)(wg_t + (size_t)ej * d + c);
+        acc.x = fmaf(dj, wv.x, acc.x); acc.y = fmaf(dj, wv.y, acc.y);
+        acc.z = fmaf(dj, wv.z, acc.z); acc.w = fmaf(dj, wv.w, acc.w);
+      }
+    }
+    if (c < d) *(float4*)(dx + (size_t)t * d + c) = acc;
+  }
+}
+
+}  // namespace
+
+int launch_route(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias,
+                 int32_t* topk_idx, float* topk_w, float* logits, hipStream_t s) {
+  const dim3 grid((D.T + 31) / 32), block(256);
+  if (D.dtype == BIGMAC_BF16)
+    hipLaunchKernelGGL(router_logits_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
+  else
+    hipLaunchKernelGGL(router_logits_kernel<float>, grid, block, 0, s, (const float*)x, w_gate, bias, logits, D.T, D.d, D.N);
+  BIGMAC_CHECK_LAUNCH();
+  const dim3 g2((D.T + 3) / 4);
+  const int per = (D.N + 63) / 64;
+#define BIGMAC_TOPK(P) hipLaunchKernelGGL(topk_gate_kernel<P>, g2, block, 0, s, logits, D.T, D.N, D.k, topk_idx, topk_w)
+  if (per <= 1) BIGMAC_TOPK(1);
+  else if (per <= 2) BIGMAC_TOPK(2);
+  else if (per <= 4) BIGMAC_TOPK(4);
+  else if (per <= 8) BIGMAC_TOPK(8);
+  else BIGMAC_TOPK(16);
+#undef BIGMAC_TOPK
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+size_t route_backward_ws_bytes(const bigmac_dims& D) {
+  return align_up((size_t)D.N * D.d * sizeof(float));  // transposed router weights
+}
+
+int launch_route_backward(const bigmac_dims& D, const float* w_gate, const int32_t* topk_idx,
+                          const float* topk_w, const float* dgate, float* dx_f32, void* dL_out,
+                          void* ws, hipStream_t s) {
+  float* wg_t = (float*)ws;
+  hipLaunchKernelGGL(transpose_f32_kernel, dim3((D.N + 31) / 32, (D.d + 31) / 32), dim3(32, 8), 0, s, w_gate, wg_t, D.d, D.N);
+  BIGMAC_CHECK_LAUNCH();
+  const dim3 grid((D.T + 3) / 4), block(256);
+  if (D.dtype == BIGMAC_BF16)
+    hipLaunchKernelGGL(gate_backward_kernel<bf16_t>, grid, block, 0, s, topk_idx, topk_w, dgate, wg_t, (bf16_t*)dL_out, dx_f32, D.T, D.d, D.N, D.k);
+  else
+    hipLaunchKernelGGL(gate_backward_kernel<float>, grid, block, 0, s, topk_idx, topk_w, dgate, wg_t, (float*)dL_out, dx_f32, D.T, D.d, D.N, D.k);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+}  // namespace bigmac

@@ -1,0 +1,155 @@
+"""Parity of the whole layer (forward and backward, both orders) against the CPU oracle.
+
+Small workloads are compared element by element.  The full-size workloads run in the launch
+configuration the benchmark times; there the routing and permutation are still compared in full
+(the oracle's routing is cheap), outputs and dx on sampled tokens, and the weight gradients
+through a dy that is zero outside the sampled tokens (exactly what the oracle's token selection
+computes), plus properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_16927_amd import binding as B
+from paper_2502_16927_amd import synth
+from gpu_util import TOL, DeviceLayer, add_cdac_weights, check_weight_grads, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [
+    dict(T=96, d=128, r=64, N=8, k=2, h=128, dtype=B.BF16),
+    dict(T=300, d=256, r=128, N=16, k=4, h=320, dtype=B.BF16),
+    dict(T=1500, d=256, r=128, N=8, k=2, h=256, dtype=B.BF16),
+    dict(T=257, d=192, r=64, N=24, k=8, h=192, dtype=B.BF16, zipf_s=1.2),
+    dict(T=64, d=64, r=64, N=8, k=8, h=64, dtype=B.BF16),
+    dict(T=1, d=64, r=64, N=8, k=1, h=64, dtype=B.BF16),
+    dict(T=130, d=128, r=64, N=8, k=3, h=192, dtype=B.F32, x_std=0.5),
+]
+
+
+def oracle_forward(oracle, data, k, sel=None):
+    return oracle.bigmac_forward(data["x"], data["w_gate"], data["gate_bias"], data["w_down"], data["w_up"],
+                                 data["w1"], data["w2"], k, sel=sel)
+
+
+def check_routing(oracle, layer, data):
+    wl = layer.wl
+    v = layer.saved_views()
+    idx, gate, _ = oracle.route(data["x"], data["w_gate"], data["gate_bias"], wl.k)
+    off, slot, _ = oracle.permutation(idx, wl.N)
+    assert np.array_equal(v["topk_idx"], idx), "top-k sets differ"
+    assert np.array_equal(v["expert_offsets"], off)
+    assert np.array_equal(v["slot_of"], slot)
+    assert np.abs(v["topk_w"] - gate).max() < 1e-6
+    return idx
+
+
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: "T{T}_d{d}_r{r}_N{N}_k{k}_h{h}_t{dtype}".format(**c))
+def test_small_forward_backward(oracle, case):
+    print("small layer", case, flush=True)
+    wl = synth.small(**case)
+    data = synth.generate(wl)
+    layer = DeviceLayer(wl, data)
+    tol = TOL if wl.dtype == B.BF16 else 1e-4
+    y_inf = host(layer.forward(training=False)).copy()
+    y = host(layer.forward(training=True))
+    torch.cuda.synchronize()
+    ref = oracle_forward(oracle, data, wl.k)
+    assert np.array_equal(y_inf, y), "inference and training forward differ"
+    assert rel_err(y, ref) < tol
+    idx = check_routing(oracle, layer, data)
+    counts = np.bincount(idx.ravel(), minlength=wl.N)
+    g_ref = oracle.bigmac_backward(data["x"], data["dy"], data["w_gate"], data["gate_bias"], data["w_down"],
+                                   data["w_up"], data["w1"], data["w2"], wl.k)
+    layer.alloc_grads()
+    layer.backward()
+    torch.cuda.synchronize()
+    assert rel_err(host(layer.dx), g_ref["dx"]) < tol, "dx"
+    print(check_weight_grads({n: host(v) for n, v in layer.grads.items()}, g_ref, counts, wl.T, tol), flush=True)
+    # accumulate flag: gradients are added to what the buffers hold
+    rng = np.random.default_rng(5)
+    init = {n: rng.standard_normal(v.shape).astype(np.float32) * float(np.sqrt(np.mean(v * v)) + 1e-12)
+            for n, v in g_ref.items() if n != "dx"}
+    layer2 = DeviceLayer(wl, data, flags=B.FLAG_ACCUMULATE)
+    layer2.forward(training=True)
+    layer2.alloc_grads(init)
+    layer2.backward()
+    torch.cuda.synchronize()
+    check_weight_grads({n: host(v) - init[n] for n, v in layer2.grads.items()}, g_ref, counts, wl.T, tol, scale=1.5)
+
+
+def test_bf16_output_is_the_rounded_fp32_output(oracle):
+    wl = synth.small(T=200, d=128, r=64, N=8, k=2, h=128)
+    data = synth.generate(wl)
+    a = DeviceLayer(wl, data)
+    b = DeviceLayer(wl, data, flags=B.FLAG_OUT_BF16)
+    ya, yb = a.forward(training=True), b.forward(training=True)
+    assert torch.equal(ya.to(torch.bfloat16), yb)
+    a.alloc_grads(); b.alloc_grads()
+    a.backward(); b.backward()
+    torch.cuda.synchronize()
+    assert torch.equal(a.dx.to(torch.bfloat16), b.dx)
+    for n in a.grads:
+        assert torch.equal(a.grads[n], b.grads[n])
+
+
+def test_run_to_run_determinism():
+    wl = synth.small(T=700, d=256, r=128, N=16, k=4, h=256, zipf_s=1.2)
+    data = synth.generate(wl)
+    outs = []
+    for _ in range(2):
+        layer = DeviceLayer(wl, data)
+        layer.forward(training=True)
+        layer.alloc_grads()
+        layer.backward()
+        torch.cuda.synchronize()
+        outs.append([layer.y.clone(), layer.dx.clone()] + [layer.grads[n].clone() for n in sorted(layer.grads)])
+    for u, v in zip(*outs):
+        assert torch.equal(u, v)
+
+
+def test_identity_projections_reduce_to_fine_grained(oracle):
+    # r = d and W_down = W_up = I: the BigMac layer is the fine-grained top-k MoE of its experts
+    rng = np.random.default_rng(2)
+    wl = synth.small(T=150, d=128, r=128, N=8, k=2, h=64)
+    data = synth.generate(wl)
+    data["w_down"] = np.eye(128, dtype=np.float32)
+    data["w_up"] = np.eye(128, dtype=np.float32)
+    y = host(DeviceLayer(wl, data).forward(training=False))
+    fg = dict(data, cdac_w1=data["w1"], cdac_w2=data["w2"])
+    wl_fg = synth.small(T=150, d=128, r=64, N=8, k=2, h=64)      # expert d=128 -> r=64 -> d
+    y_fg = host(DeviceLayer(wl_fg, fg, order=B.ORDER_CDAC).forward(training=False))
+    torch.cuda.synchronize()
+    ref = oracle.cdac_forward(data["x"], data["w_gate"], None, data["w1"], data["w2"], 2)
+    assert rel_err(y, ref) < TOL and rel_err(y_fg, ref) < TOL
+    assert rel_err(y, y_fg) < TOL
+
+
+@pytest.mark.parametrize("dtype", [B.BF16, B.F32])
+def test_small_fine_grained_layer(oracle, dtype):
+    print("small CDAC layer", dtype, flush=True)
+    wl = synth.small(T=210, d=128, r=64, N=8, k=3, h=128, dtype=dtype)
+    data = add_cdac_weights(synth.generate(wl))
+    layer = DeviceLayer(wl, data, order=B.ORDER_CDAC)
+    tol = TOL if dtype == B.BF16 else 1e-4
+    y = host(layer.forward(training=True))
+    torch.cuda.synchronize()
+    ref = oracle.cdac_forward(data["x"], data["w_gate"], None, data["cdac_w1"], data["cdac_w2"], wl.k)
+    assert rel_err(y, ref) < tol
+    idx = check_routing(oracle, layer, data)
+    g_ref = oracle.cdac_backward(data["x"], data["dy"], data["w_gate"], None, data["cdac_w1"], data["cdac_w2"], wl.k)
+    layer.alloc_grads()
+    layer.backward()
+    torch.cuda.synchronize()
+    assert rel_err(host(layer.dx), g_ref["dx"]) < tol
+    grads = {n: host(layer.grads[n]) for n in ("d_w_gate", "d_w1", "d_w2")}
+    check_weight_grads(grads, g_ref, np.bincount(idx.ravel(), minlength=wl.N), wl.T, tol, dcca=False)
+
+
+def test_tiny_fp32_workload_full(oracle):
+    wl = synth.WORKLOADS["tiny_f32"]
+    data = synth.generate(wl)
+    layer = DeviceLayer(wl, data)
+    y = host(layer.forward(training=True))
+    torch.cuda.synchronize()
+    assert rel_err(y, oracle_forward(oracle, data, wl.k)) < 1e-4
+    check_routing(oracle, layer, data)
