@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the BigMac MoE layer on one MI355X: tokens/s of one layer step (forward +
+backward on workloads that train, forward only otherwise) on seeded synthetic inputs resident in
+HBM, the roofline of the kernel that dominates the step, and the CPU oracle timed beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt_medium] [--order dcca|cdac]
+
+Prints ONE JSON line.  Runs on one GPU only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM = 8.0e12          # bytes/s, MI355X HBM3E
+PEAK_MFMA_BF16 = 2.5e15    # flop/s, dense bf16 MFMA
+PEAK_ALU_F32 = 78.6e12     # flop/s: 256 CUs x 64 fp32 lanes x 2 (fma) x 2.4 GHz, no packed fp32 ops
+
+
+def stage_work(wl, order_cdac: bool, training: bool):
+    """Algorithmic work per stage: (kind, flops, bytes).  Bytes are compulsory traffic: every
+    input read once, every output written once, real rows only.  e = bytes per stored element."""
+    T, d, r, N, k, h = wl.T, wl.d, wl.r, wl.N, wl.k, wl.h
+    e = 2 if wl.dtype == 1 else 4
+    Tk = T * k
+    win, hid = (d, r) if order_cdac else (r, h)
+    low = 2 * r if e == 2 else r          # y' and dx' travel as (hi | lo) bf16 pairs
+    W = {}
+    W["router_logits"] = ("alu", 2.0 * T * d * N, T * d * e + d * N * 4 + T * N * 4)
+    W["topk_gate"] = ("hbm", 0.0, T * N * 4 + 8 * Tk)
+    W["descend"] = ("mfma", 2.0 * T * d * r, T * d * e + d * r * e + T * r * e)
+    W["permutation"] = ("hbm", 0.0, 4 * Tk * 4)
+    W["dispatch"] = ("hbm", 0.0, (T + Tk) * win * e + 4 * Tk)
+    W["expert_up"] = ("mfma", 2.0 * Tk * win * hid, Tk * win * e + N * win * hid * e + Tk * hid * e * (2 if training else 1))
+    W["expert_down"] = ("mfma", 2.0 * Tk * hid * win, Tk * hid * e + N * win * hid * e + Tk * win * e)
+    W["combine"] = ("hbm", 2.0 * Tk * win, Tk * win * e + T * (low * e if not order_cdac else d * 4) + 8 * Tk)
+    W["ascend"] = ("mfma", 2.0 * T * r * d, T * low * e + r * d * e + T * d * 4)
+    W["bwd_ascend_dgrad"] = ("mfma", 2.0 * T * d * r, T * d * e + r * d * e + T * r * 4)
+    W["bwd_ascend_wgrad"] = ("mfma", 2.0 * T * r * d, T * r * e + T * d * e + r * d * 4)
+    W["bwd_combine"] = ("hbm", 4.0 * Tk * win, T * win * 4 + 2 * Tk * win * e + 12 * Tk)
+    W["bwd_down_dgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * win * e + N * win * hid * e + 2 * Tk * hid * e)
+    W["bwd_down_wgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * hid * e + Tk * win * e + N * win * hid * 4)
+    W["bwd_up_wgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * hid * e + Tk * win * e + N * win * hid * 4)
+    W["bwd_up_dgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * hid * e + N * win * hid * e + Tk * win * e)
+    W["bwd_dispatch"] = ("hbm", 1.0 * Tk * win, Tk * win * e + T * (low * e if not order_cdac else d * 4) + 4 * Tk)
+    W["bwd_gate"] = ("hbm", 2.0 * Tk * d, T * d * 4 + T * N * e + 12 * Tk)
+    W["bwd_router_wgrad"] = ("mfma", 2.0 * T * d * N, T * d * e + T * N * e + d * N * 4)
+    W["bwd_descend_wgrad"] = ("mfma", 2.0 * T * d * r, T * d * e + T * r * e + d * r * 4)
+    W["bwd_descend_dgrad"] = ("mfma", 2.0 * T * r * d, T * low * e + d * r * e + 2 * T * d * 4)
+    W["bwd_output_cast"] = ("hbm", 0.0, 3 * T * d * 4)
+    return W
+
+
+def roofline_of(name, kind, flops, nbytes, seconds):
+    """The roofline that bounds this kernel: whichever of its algorithmic flops or bytes takes
+    longer at the chip's peak."""
+    peak_f = PEAK_ALU_F32 if kind == "alu" else PEAK_MFMA_BF16
+    t_f = flops / peak_f if flops else 0.0
+    t_b = nbytes / PEAK_HBM
+    if kind != "hbm" and t_f >= t_b:
+        achieved, peak = flops / seconds / 1e12, peak_f / 1e12
+        return {"kernel": name, "bound": "alu" if kind == "alu" else "mfma", "achieved": achieved, "peak": peak,
+                "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None, "algorithmic_flops": flops,
+                "algorithmic_bytes": nbytes, "avg_ms": seconds * 1e3}
+    achieved, peak = nbytes / seconds / 1e9, PEAK_HBM / 1e9
+    return {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": peak, "unit": "GB/s", "frac": achieved / peak,
+            "traffic": None, "algorithmic_flops": flops, "algorithmic_bytes": nbytes, "avg_ms": seconds * 1e3}
+
+
+def cpu_baseline(wl, data, sample_tokens: int, training: bool):
+    """The oracle as it stands, timed on the host cores on a bounded token sample."""
+    import numpy as np
+    from oracle import cpu_oracle
+    n = min(sample_tokens, wl.T)
+    sel = np.linspace(0, wl.T - 1, n).astype(np.int32)
+    t0 = time.perf_counter()
+    cpu_oracle.bigmac_forward(data["x"], data["w_gate"], data["gate_bias"], data["w_down"], data["w_up"],
+                              data["w1"], data["w2"], wl.k, sel=sel)
+    if training:
+        cpu_oracle.bigmac_backward(data["x"], data["dy"], data["w_gate"], data["gate_bias"], data["w_down"],
+                                   data["w_up"], data["w1"], data["w2"], wl.k, sel=sel)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "tokens/s", "cores": cpu_oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n} evenly spaced tokens of the same workload, forward{'+backward' if training else ''}, "
+                      f"{dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt_medium")
+    ap.add_argument("--tokens", type=int, default=0, help="override T (decode sweep)")
+    ap.add_argument("--order", default="dcca", choices=["dcca", "cdac"])
+    ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of the oracle timing sample (0: skip)")
+    ap.add_argument("--no-stage-events", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2502_16927_amd import binding as B
+    from paper_2502_16927_amd import synth
+
+    wl = synth.WORKLOADS[args.workload]
+    if args.tokens:
+        wl = wl.with_T(args.tokens)
+    cdac = args.order == "cdac"
+    training = wl.backward
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    data = synth.generate(wl)
+    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA)
+    x = B.to_device(data["x"], wl.dtype, dev)
+    dy = B.to_device(data.get("dy"), wl.dtype, dev)
+    wg = B.to_device(data["w_gate"], B.F32, dev)
+    bias = B.to_device(data["gate_bias"], B.F32, dev)
+    if cdac:   # same parameters: the BigMac expert matrices with their roles swapped (needs h == d)
+        assert wl.h == wl.d
+        w1, w2 = B.to_device(data["w2"], wl.dtype, dev), B.to_device(data["w1"], wl.dtype, dev)
+        w_down = w_up = None
+        win, hid = wl.d, wl.r
+    else:
+        w1, w2 = B.to_device(data["w1"], wl.dtype, dev), B.to_device(data["w2"], wl.dtype, dev)
+        w_down, w_up = B.to_device(data["w_down"], wl.dtype, dev), B.to_device(data["w_up"], wl.dtype, dev)
+        win, hid = wl.r, wl.h
+    params = B.make_params(w_down, w_up, wg, bias, w1, w2)
+    y = torch.empty((wl.T, wl.d), dtype=torch.float32, device=dev)
+    ws = B.alloc_bytes(B.workspace_bytes(dims, B.WS_LAYER_TRAIN if training else B.WS_LAYER_FORWARD), dev)
+    saved = B.alloc_bytes(B.workspace_bytes(dims, B.WS_SAVED), dev) if training else None
+    if training:
+        dx = torch.empty_like(y)
+        f32 = lambda *s: torch.empty(s, dtype=torch.float32, device=dev)
+        gw = {"d_w_down": None if cdac else f32(wl.d, wl.r), "d_w_up": None if cdac else f32(wl.r, wl.d),
+              "d_w_gate": f32(wl.d, wl.N), "d_w1": f32(wl.N, win, hid), "d_w2": f32(wl.N, hid, win)}
+
+    def step():
+        B.bigmac_layer_forward(dims, params, x, y, saved, ws)
+        if training:
+            B.bigmac_layer_backward(dims, params, x, dy, saved, dx, gw["d_w_down"], gw["d_w_up"], gw["d_w_gate"],
+                                    gw["d_w1"], gw["d_w2"], ws)
+
+    for _ in range(args.warmup):
+        step()
+    tables = [] if args.no_stage_events else [B.StageEvents() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        if tables:
+            tables[i].install()
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    B.StageEvents.clear()
+
+    ms_per_step = elapsed / args.steps * 1e3
+    work = stage_work(wl, cdac, training)
+    stage_ms = {}
+    if tables:
+        names = [B.stage_name(s) for s in range(B.STAGE_COUNT)]
+        fwd_only = {"router_logits", "topk_gate", "descend", "permutation", "dispatch", "expert_up", "expert_down", "combine", "ascend"}
+        live = [s for s, n in enumerate(names)
+                if (training or n in fwd_only)
+                and not (cdac and n in ("descend", "ascend", "bwd_ascend_wgrad", "bwd_descend_wgrad", "bwd_descend_dgrad"))
+                and not (not cdac and n == "bwd_output_cast")]
+        for tb in tables:
+            for s, ms in tb.elapsed_ms(set(live)).items():
+                stage_ms[names[s]] = stage_ms.get(names[s], 0.0) + ms / args.steps
+    roofline = None
+    if stage_ms:
+        dom = max(stage_ms, key=stage_ms.get)
+        kind, flops, nbytes = work[dom]
+        roofline = roofline_of(dom, kind, flops, nbytes, stage_ms[dom] * 1e-3)
+    fwd_flops = B.forward_matrix_flops(dims)
+    out = {
+        "metric": "BigMac MoE layer tokens/sec fwd+bwd (1 GPU)" if training else "BigMac MoE layer tokens/sec fwd (1 GPU)",
+        "value": wl.T / (elapsed / args.steps),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == B.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "order": args.order, "T": wl.T, "d": wl.d, "r": wl.r, "N": wl.N, "k": wl.k,
+                   "h": wl.h, "pass": "fwd+bwd" if training else "fwd"},
+        "roofline": roofline,
+        "matrix_tflops": fwd_flops * (3 if training else 1) / (elapsed / args.steps) / 1e12,
+        "permute_bytes_per_step": B.permute_bytes(dims) * (1.0 if training else 0.5),
+        "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
+        "stage_sum_ms": round(sum(stage_ms.values()), 4),
+    }
+    if args.cpu_sample > 0 and not cdac:
+        out["cpu_baseline"] = cpu_baseline(wl, data, args.cpu_sample, training)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -146,6 +146,41 @@ int bigmac_layer_backward(const bigmac_dims *dims, const bigmac_params *params, 
 int bigmac_saved_layout(const bigmac_dims *dims, size_t *off_topk_idx, size_t *off_topk_w,
                         size_t *off_expert_offsets, size_t *off_slot_of);
 
+/* Profiling aid for callers that cannot allocate or want per-kernel times (benchmarks).  The
+ * layer calls launch one kernel per stage below (a stage that a configuration skips records
+ * nothing).  While an event table is set, bigmac_layer_forward / bigmac_layer_backward record
+ * events[2*s] before and events[2*s + 1] after stage s on the call's stream; `events` is a HOST
+ * array of 2 * BIGMAC_STAGE_COUNT hipEvent_t handles owned by the caller, which must stay alive
+ * until it is replaced or cleared with NULL.  This is the library's only process-wide setting;
+ * it is not thread-safe.  Returns BIGMAC_OK. */
+typedef enum {
+  BIGMAC_STAGE_ROUTER_LOGITS = 0, /* F0  x W_g                                   */
+  BIGMAC_STAGE_TOPK_GATE,         /* F1  top-k and gate values                   */
+  BIGMAC_STAGE_DESCEND,           /* F2  x' = x W_down                           */
+  BIGMAC_STAGE_PERMUTATION,       /* F3  counting sort (3 small kernels) + tile map */
+  BIGMAC_STAGE_DISPATCH,          /* F4  first All-to-All (row scatter)          */
+  BIGMAC_STAGE_EXPERT_UP,         /* F5  act(x_perm W1[e])                       */
+  BIGMAC_STAGE_EXPERT_DOWN,       /* F6  . W2[e]                                 */
+  BIGMAC_STAGE_COMBINE,           /* F7  second All-to-All + weighted sum        */
+  BIGMAC_STAGE_ASCEND,            /* F8  y = y' W_up                             */
+  BIGMAC_STAGE_BWD_ASCEND_DGRAD,  /* B8  dy' = dy W_up^T                         */
+  BIGMAC_STAGE_BWD_ASCEND_WGRAD,  /* B8  dW_up (split-K product + reduction)     */
+  BIGMAC_STAGE_BWD_COMBINE,       /* B7  gate gradients, scaled scatter of dy'   */
+  BIGMAC_STAGE_BWD_DOWN_DGRAD,    /* B6  dact = (do W2[e]^T) act'                */
+  BIGMAC_STAGE_BWD_DOWN_WGRAD,    /* B6  dW2[e]                                  */
+  BIGMAC_STAGE_BWD_UP_WGRAD,      /* B5  dW1[e]                                  */
+  BIGMAC_STAGE_BWD_UP_DGRAD,      /* B5  dx_perm = dact W1[e]^T                  */
+  BIGMAC_STAGE_BWD_DISPATCH,      /* B4  dx' = sum_j dx_perm                     */
+  BIGMAC_STAGE_BWD_GATE,          /* B1  gate backward, router share of dx       */
+  BIGMAC_STAGE_BWD_ROUTER_WGRAD,  /* B0  dW_g                                    */
+  BIGMAC_STAGE_BWD_DESCEND_WGRAD, /* B2  dW_down                                 */
+  BIGMAC_STAGE_BWD_DESCEND_DGRAD, /* B2  dx += dx' W_down^T                      */
+  BIGMAC_STAGE_BWD_OUTPUT_CAST,   /* dx to bf16 / fine-grained dx sum            */
+  BIGMAC_STAGE_COUNT
+} bigmac_stage;
+int bigmac_set_stage_events(void *const *events);
+const char *bigmac_stage_name(int stage);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,6 +37,10 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
 def _f32(a):
     return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
 

@@ -63,13 +63,18 @@ def lib() -> ctypes.CDLL:
         L.bigmac_layer_forward.argtypes = [dp, ctypes.POINTER(Params), vp, vp, vp, vp, sz, vp]
         L.bigmac_layer_backward.restype = ci
         L.bigmac_layer_backward.argtypes = [dp, ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bigmac_set_stage_events.restype = ci
+        L.bigmac_set_stage_events.argtypes = [ctypes.POINTER(vp)]
+        L.bigmac_stage_name.restype = ctypes.c_char_p
+        L.bigmac_stage_name.argtypes = [ci]
         _lib = L
     return _lib
 
 
 EXPORTS = ("bigmac_workspace_bytes", "bigmac_status_string", "bigmac_forward_matrix_flops", "bigmac_permute_bytes",
            "bigmac_saved_layout", "bigmac_route", "bigmac_dispatch", "bigmac_grouped_ffn", "bigmac_combine",
-           "bigmac_layer_forward", "bigmac_layer_backward")
+           "bigmac_layer_forward", "bigmac_layer_backward", "bigmac_set_stage_events", "bigmac_stage_name")
+STAGE_COUNT = 22
 
 
 def make_dims(T, d, r, N, k, h, dtype=BF16, order=ORDER_DCCA, flags=0, act=0) -> Dims:
@@ -159,6 +164,32 @@ def bigmac_layer_backward(dims, params, x, dy, saved, dx, d_w_down, d_w_up, d_w_
     _check(lib().bigmac_layer_backward(ctypes.byref(dims), ctypes.byref(params), _ptr(x), _ptr(dy), _ptr(saved), _ptr(dx),
                                        _ptr(d_w_down), _ptr(d_w_up), _ptr(d_w_gate), _ptr(d_w1), _ptr(d_w2), _ptr(ws),
                                        _nbytes(ws), _stream(stream)), "bigmac_layer_backward")
+
+
+def stage_name(stage: int) -> str:
+    return lib().bigmac_stage_name(stage).decode()
+
+
+class StageEvents:
+    """A table of 2 * STAGE_COUNT timing events (torch events, so they live on torch's runtime)
+    that the layer calls record around each stage while the table is installed."""
+
+    def __init__(self):
+        self.events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * STAGE_COUNT)]
+        for e in self.events:
+            e.record()                       # materialise the underlying hipEvent_t
+        self.table = (ctypes.c_void_p * (2 * STAGE_COUNT))(*[e.cuda_event for e in self.events])
+
+    def install(self):
+        _check(lib().bigmac_set_stage_events(self.table), "bigmac_set_stage_events")
+
+    @staticmethod
+    def clear():
+        _check(lib().bigmac_set_stage_events(None), "bigmac_set_stage_events")
+
+    def elapsed_ms(self, recorded: set) -> dict:
+        """Per-stage milliseconds for the stages in `recorded` (call after a synchronize)."""
+        return {s: self.events[2 * s].elapsed_time(self.events[2 * s + 1]) for s in recorded}
 
 
 # ----------------------------------------------------------------- device buffers (allocation only)

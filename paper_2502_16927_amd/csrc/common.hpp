@@ -88,8 +88,9 @@ int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* ti
 int launch_reduce_partials(const float* part, int nslices, size_t n, float* out, int beta, hipStream_t s);
 
 // ----------------------------------------------------------------------------- route ----
-int launch_route(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias,
-                 int32_t* topk_idx, float* topk_w, float* logits_out, hipStream_t s);
+int launch_router_logits(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias,
+                         float* logits, hipStream_t s);
+int launch_topk_gate(const bigmac_dims& D, const float* logits, int32_t* topk_idx, float* topk_w, hipStream_t s);
 // Gate backward (softmax over the k picked logits) and the router's share of dx:
 //   dlogit[t,j] = w[t,j] (dgate[t,j] - sum_m w[t,m] dgate[t,m])
 //   dL_out [T,N] (storage dtype) = dlogit scattered to its expert columns, zeros elsewhere

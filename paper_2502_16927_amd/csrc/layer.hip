@@ -21,6 +21,20 @@ int check_dims(const bigmac_dims* D) {
 
 namespace {
 
+void* const* g_stage_events = nullptr;  // profiling aid, see bigmac_set_stage_events
+
+struct StageTimer {  // records the caller's events around the launches of one stage
+  hipStream_t s;
+  int stage;
+  StageTimer(hipStream_t s_, int stage_) : s(s_), stage(stage_) {
+    if (g_stage_events) (void)hipEventRecord((hipEvent_t)g_stage_events[2 * stage], s);
+  }
+  ~StageTimer() {
+    if (g_stage_events) (void)hipEventRecord((hipEvent_t)g_stage_events[2 * stage + 1], s);
+  }
+};
+#define BIGMAC_STAGE(stage) StageTimer stage_timer_##stage(s, stage)
+
 struct Carver {  // hands out 256-byte aligned pieces of one buffer
   size_t off = 0;
   size_t take(size_t bytes) {
@@ -154,13 +168,18 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.A = x_perm; g.lda = W.win; g.K = W.win;
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
   g.C = hact; g.ldc = W.hid; g.aux_out = act;
-  int rc = launch_gemm(g, s);
+  int rc;
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_EXPERT_UP);
+    rc = launch_gemm(g, s);
+  }
   if (rc) return rc;
   // o_perm = hact W2[e]
   g.epilogue = EPI_STORE; g.out_f32 = 0; g.aux_out = nullptr;
   g.A = hact; g.lda = W.hid; g.K = W.hid;
   g.B = w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.win;
   g.C = o_perm; g.ldc = W.win;
+  BIGMAC_STAGE(BIGMAC_STAGE_EXPERT_DOWN);
   return launch_gemm(g, s);
 }
 
@@ -225,6 +244,20 @@ double bigmac_permute_bytes(const bigmac_dims* D) {
   return 4.0 * (double)D->T * D->k * widths(*D).win * esize(D->dtype);
 }
 
+int bigmac_set_stage_events(void* const* events) {
+  g_stage_events = events;
+  return BIGMAC_OK;
+}
+
+const char* bigmac_stage_name(int stage) {
+  static const char* names[BIGMAC_STAGE_COUNT] = {
+      "router_logits", "topk_gate", "descend", "permutation", "dispatch", "expert_up", "expert_down", "combine", "ascend",
+      "bwd_ascend_dgrad", "bwd_ascend_wgrad", "bwd_combine", "bwd_down_dgrad", "bwd_down_wgrad", "bwd_up_wgrad",
+      "bwd_up_dgrad", "bwd_dispatch", "bwd_gate", "bwd_router_wgrad", "bwd_descend_wgrad", "bwd_descend_dgrad",
+      "bwd_output_cast"};
+  return stage >= 0 && stage < BIGMAC_STAGE_COUNT ? names[stage] : "?";
+}
+
 int bigmac_saved_layout(const bigmac_dims* D, size_t* off_topk_idx, size_t* off_topk_w, size_t* off_expert_offsets,
                         size_t* off_slot_of) {
   int rc = check_dims(D);
@@ -248,7 +281,9 @@ int bigmac_route(const bigmac_dims* D, const void* x, const float* w_gate, const
     if (ws_bytes < bigmac_workspace_bytes(D, BIGMAC_WS_ROUTE)) return BIGMAC_ERR_WORKSPACE;
     logits = (float*)ws;
   }
-  return launch_route(*D, x, w_gate, gate_bias, topk_idx, topk_w, logits, (hipStream_t)stream);
+  rc = launch_router_logits(*D, x, w_gate, gate_bias, logits, (hipStream_t)stream);
+  if (rc) return rc;
+  return launch_topk_gate(*D, logits, topk_idx, topk_w, (hipStream_t)stream);
 }
 
 int bigmac_dispatch(const bigmac_dims* D, const void* x_low, const int32_t* topk_idx, void* x_perm, int32_t* expert_offsets,
@@ -314,7 +349,15 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   void* y_low = sv + S.y_low;
   const bool out_bf16 = bf(*D) && (D->flags & BIGMAC_FLAG_OUT_BF16);
 
-  rc = launch_route(*D, x, P->w_gate, P->gate_bias, topk_idx, topk_w, (float*)(wsb + F.logits), s);
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_ROUTER_LOGITS);
+    rc = launch_router_logits(*D, x, P->w_gate, P->gate_bias, (float*)(wsb + F.logits), s);
+  }
+  if (rc) return rc;
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_TOPK_GATE);
+    rc = launch_topk_gate(*D, (const float*)(wsb + F.logits), topk_idx, topk_w, s);
+  }
   if (rc) return rc;
   const void* x_low = x;
   if (dcca) {  // x' = x W_down
@@ -323,22 +366,33 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     g.A = x; g.lda = D->d; g.M = D->T; g.K = D->d;
     g.B = P->w_down; g.ldb = D->r; g.N = D->r;
     g.C = wsb + F.x_low; g.ldc = D->r;
+    BIGMAC_STAGE(BIGMAC_STAGE_DESCEND);
     rc = launch_gemm(g, s);
     if (rc) return rc;
     x_low = wsb + F.x_low;
   }
-  rc = launch_build_permutation(D->T, D->k, D->N, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s);
-  if (rc) return rc;
-  rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype), tile_map, s);
-  if (rc) return rc;
-  rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_PERMUTATION);
+    rc = launch_build_permutation(D->T, D->k, D->N, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s);
+    if (rc) return rc;
+    rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype), tile_map, s);
+    if (rc) return rc;
+  }
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_DISPATCH);
+    rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);
+  }
   if (rc) return rc;
   rc = run_experts_forward(*D, x_perm, offsets, tile_map, P->w1, P->w2, act, hact, o_perm, s);
   if (rc) return rc;
   if (!dcca) {  // fine-grained layer: the weighted sum is the output
+    BIGMAC_STAGE(BIGMAC_STAGE_COMBINE);
     return launch_combine_rows(D->dtype, D->T, D->k, W.win, o_perm, slot_of, topk_w, y, COMBINE_F32, s);
   }
-  rc = launch_combine_rows(D->dtype, D->T, D->k, W.win, o_perm, slot_of, topk_w, y_low, bf(*D) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_COMBINE);
+    rc = launch_combine_rows(D->dtype, D->T, D->k, W.win, o_perm, slot_of, topk_w, y_low, bf(*D) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
+  }
   if (rc) return rc;
   {  // y = y' W_up
     GemmDesc g = base_desc(*D);
@@ -346,6 +400,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     g.A = y_low; g.lda = low_ld(*D); g.M = D->T; g.K = low_ld(*D);
     g.B = P->w_up; g.ldb = D->d; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
     g.C = y; g.ldc = D->d;
+    BIGMAC_STAGE(BIGMAC_STAGE_ASCEND);
     rc = launch_gemm(g, s);
   }
   return rc;
@@ -399,18 +454,26 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = dy; g.lda = D->d; g.M = D->T; g.K = D->d;
     g.B = P->w_up; g.ldb = D->d; g.N = D->r;
     g.C = dy_low; g.ldc = D->r;
-    rc = launch_gemm(g, s);
+    {
+      BIGMAC_STAGE(BIGMAC_STAGE_BWD_ASCEND_DGRAD);
+      rc = launch_gemm(g, s);
+    }
     if (rc) return rc;
     // dW_up (+)= y'^T dy
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_ASCEND_WGRAD);
     rc = run_token_wgrad(*D, y_low, low_ld(*D), D->r, dy, D->d, D->d, d_w_up, partials, s);
     if (rc) return rc;
   } else {
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_ASCEND_DGRAD);
     if (bf(*D)) hipLaunchKernelGGL(to_f32_kernel<bf16_t>, grid1d(Td), dim3(256), 0, s, (const bf16_t*)dy, dy_low, Td);
     else hipLaunchKernelGGL(to_f32_kernel<float>, grid1d(Td), dim3(256), 0, s, (const float*)dy, dy_low, Td);
     BIGMAC_CHECK_LAUNCH();
   }
   // weighted-sum backward: gate gradients and the scaled scatter of dy' to the expert rows
-  rc = launch_combine_backward(D->dtype, D->T, D->k, W.win, dy_low, o_perm, slot_of, topk_w, dgate, do_perm, s);
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_COMBINE);
+    rc = launch_combine_backward(D->dtype, D->T, D->k, W.win, dy_low, o_perm, slot_of, topk_w, dgate, do_perm, s);
+  }
   if (rc) return rc;
   {  // dact = (do_perm W2[e]^T) * act'(act)
     GemmDesc g = base_desc(*D);
@@ -419,6 +482,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = do_perm; g.lda = W.win; g.K = W.win;
     g.B = P->w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.hid;
     g.C = dact; g.ldc = W.hid; g.aux_in = act;
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
   }
@@ -429,12 +493,16 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = hact; g.lda = W.hid; g.M = W.hid;
     g.B = do_perm; g.ldb = W.win; g.N = W.win;
     g.C = d_w2; g.ldc = W.win; g.gstride_c = (long)W.hid * W.win;
-    rc = launch_gemm(g, s);
+    {
+      BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_WGRAD);
+      rc = launch_gemm(g, s);
+    }
     if (rc) return rc;
     // dW1[e] (+)= x_perm_e^T dact_e
     g.A = x_perm; g.lda = W.win; g.M = W.win;
     g.B = dact; g.ldb = W.hid; g.N = W.hid;
     g.C = d_w1; g.ldc = W.hid; g.gstride_c = (long)W.win * W.hid;
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_WGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
   }
@@ -445,22 +513,34 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = dact; g.lda = W.hid; g.K = W.hid;
     g.B = P->w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.win;
     g.C = dx_perm; g.ldc = W.win;
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
   }
   // dispatch backward: dx' = sum_j dx_perm[slot_of[t, j]]
-  rc = launch_combine_rows(D->dtype, D->T, D->k, W.win, dx_perm, slot_of, nullptr, dx_low,
-                           (dcca && bf(*D)) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_DISPATCH);
+    rc = launch_combine_rows(D->dtype, D->T, D->k, W.win, dx_perm, slot_of, nullptr, dx_low,
+                             (dcca && bf(*D)) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
+  }
   if (rc) return rc;
   // gate backward; the router's share of dx is written to dx_f32
-  rc = launch_route_backward(*D, P->w_gate, topk_idx, topk_w, dgate, dx_f32, dL, wsb + B.route, s);
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_GATE);
+    rc = launch_route_backward(*D, P->w_gate, topk_idx, topk_w, dgate, dx_f32, dL, wsb + B.route, s);
+  }
   if (rc) return rc;
-  // dW_g (+)= x^T dL
-  rc = run_token_wgrad(*D, x, D->d, D->d, dL, D->N, D->N, d_w_gate, partials, s);
+  {  // dW_g (+)= x^T dL
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_ROUTER_WGRAD);
+    rc = run_token_wgrad(*D, x, D->d, D->d, dL, D->N, D->N, d_w_gate, partials, s);
+  }
   if (rc) return rc;
   if (dcca) {
     // dW_down (+)= x^T dx'
-    rc = run_token_wgrad(*D, x, D->d, D->d, dx_low, low_ld(*D), D->r, d_w_down, partials, s);
+    {
+      BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_WGRAD);
+      rc = run_token_wgrad(*D, x, D->d, D->d, dx_low, low_ld(*D), D->r, d_w_down, partials, s);
+    }
     if (rc) return rc;
     // dx += dx' W_down^T
     GemmDesc g = base_desc(*D);
@@ -468,13 +548,16 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = dx_low; g.lda = low_ld(*D); g.M = D->T; g.K = low_ld(*D);
     g.B = P->w_down; g.ldb = D->r; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
     g.C = dx_f32; g.ldc = D->d;
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
   } else {
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_OUTPUT_CAST);
     hipLaunchKernelGGL(add_f32_kernel, grid1d(Td), dim3(256), 0, s, dx_f32, (const float*)dx_low, Td);
     BIGMAC_CHECK_LAUNCH();
   }
   if (out_bf16) {
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_OUTPUT_CAST);
     hipLaunchKernelGGL(f32_to_bf16_kernel, grid1d(Td), dim3(256), 0, s, dx_f32, (bf16_t*)dx, Td);
     BIGMAC_CHECK_LAUNCH();
   }

@@ -185,15 +185,18 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __res
 
 }  // namespace
 
-int launch_route(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias,
-                 int32_t* topk_idx, float* topk_w, float* logits, hipStream_t s) {
+int launch_router_logits(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias, float* logits, hipStream_t s) {
   const dim3 grid((D.T + 31) / 32), block(256);
   if (D.dtype == BIGMAC_BF16)
     hipLaunchKernelGGL(router_logits_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
   else
     hipLaunchKernelGGL(router_logits_kernel<float>, grid, block, 0, s, (const float*)x, w_gate, bias, logits, D.T, D.d, D.N);
   BIGMAC_CHECK_LAUNCH();
-  const dim3 g2((D.T + 3) / 4);
+  return BIGMAC_OK;
+}
+
+int launch_topk_gate(const bigmac_dims& D, const float* logits, int32_t* topk_idx, float* topk_w, hipStream_t s) {
+  const dim3 g2((D.T + 3) / 4), block(256);
   const int per = (D.N + 63) / 64;
 #define BIGMAC_TOPK(P) hipLaunchKernelGGL(topk_gate_kernel<P>, g2, block, 0, s, logits, D.T, D.N, D.k, topk_idx, topk_w)
   if (per <= 1) BIGMAC_TOPK(1);
