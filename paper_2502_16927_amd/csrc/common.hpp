@@ -11,14 +11,53 @@ namespace bigmac {
 typedef uint16_t bf16_t;  // bfloat16 bit pattern in memory
 
 __device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {  // round to nearest even; inputs are finite
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// round to nearest even (the hardware conversion of gfx950)
+__device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
-__device__ __forceinline__ float gelu_f(float a) { return 0.5f * a * (1.0f + erff(a * 0.70710678118654752f)); }
+__device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(f2bf_pair(f, 0.0f) & 0xFFFFu); }
+__device__ __forceinline__ void unpack_bf16x8(const uint4& v, float* f) {
+  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ uint4 pack_bf16x8(const float* f) {
+  uint4 v;
+  v.x = f2bf_pair(f[0], f[1]);
+  v.y = f2bf_pair(f[2], f[3]);
+  v.z = f2bf_pair(f[4], f[5]);
+  v.w = f2bf_pair(f[6], f[7]);
+  return v;
+}
+
+// Normal cdf and pdf at a, for the exact (erf) GELU 0.5 a (1 + erf(a / sqrt 2)) = a Phi(a) and its
+// derivative Phi(a) + a pdf(a).  erfc(x) = poly(1 / (1 + p x)) exp(-x^2) (Abramowitz & Stegun
+// 7.1.26, absolute error < 1.5e-7), with x = |a| / sqrt 2 so that exp(-x^2) is also the pdf's.
+__device__ __forceinline__ void normal_cdf_pdf(float a, float& cdf, float& pdf) {
+  const float x = fabsf(a) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  const float e = __expf(-x * x);
+  float q = fmaf(t, 1.061405429f, -1.453152027f);
+  q = fmaf(t, q, 1.421413741f);
+  q = fmaf(t, q, -0.284496736f);
+  q = fmaf(t, q, 0.254829592f);
+  const float tail = 0.5f * (t * q) * e;  // 0.5 erfc(x)
+  cdf = a >= 0.0f ? 1.0f - tail : tail;
+  pdf = e * 0.39894228040143268f;
+}
+__device__ __forceinline__ float gelu_f(float a) {
+  float c, p;
+  normal_cdf_pdf(a, c, p);
+  return a * c;
+}
 __device__ __forceinline__ float gelu_grad_f(float a) {
-  return 0.5f * (1.0f + erff(a * 0.70710678118654752f)) + a * __expf(-0.5f * a * a) * 0.39894228040143268f;
+  float c, p;
+  normal_cdf_pdf(a, c, p);
+  return fmaf(a, p, c);
 }
 
 template <typename T> struct Elem;

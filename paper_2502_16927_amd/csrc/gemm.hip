@@ -8,6 +8,19 @@
 // fp32 storage: a plain tiled FMA kernel (only the tiny fp32 workload uses it).
 #include "common.hpp"
 
+// Block tile of the MFMA kernel (build-time tunables): BM x BN outputs per block, BK-deep LDS
+// stages, WM x WN wavefronts each owning a (BM/WM) x (BN/WN) sub-tile of 32x32 MFMA tiles.
+#ifndef BIGMAC_TILE_BM
+#define BIGMAC_TILE_BM 128
+#define BIGMAC_TILE_BN 128
+#define BIGMAC_TILE_BK 32
+#define BIGMAC_TILE_WM 2
+#define BIGMAC_TILE_WN 2
+#endif
+#ifndef BIGMAC_TILE_PREFETCH
+#define BIGMAC_TILE_PREFETCH 3   // k tiles of global loads in flight per block
+#endif
+
 namespace bigmac {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -25,46 +38,60 @@ struct TileCoord {
 };
 
 // Works out which tile this block owns.  BM/BN: tile shape.
+//
+// The launch is one-dimensional.  MI355X hands consecutive workgroup ids to its 8 XCDs in turn and
+// every XCD has its own L2, so the id is first turned into (xcd, position) and each XCD is given a
+// contiguous run of logical tiles, n tile fastest: the blocks that share an A tile, and the M
+// tiles that share one expert's weights, then meet in one L2 instead of being fetched eight times.
 template <int BM, int BN>
 __device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, int esz) {
   TileCoord t;
-  t.valid = true;
+  t.valid = false;
   t.B = p.B;
   t.C = p.C;
-  t.n0 = blockIdx.x * BN;
+  const int gx = (p.N + BN - 1) / BN;
+  const int gy = p.mode == GEMM_RAGGED_M ? p.tile_map[0] : (p.M + BM - 1) / BM;
+  const int gz = p.mode == GEMM_RAGGED_K ? p.groups : (p.mode == GEMM_DENSE ? p.ksplit : 1);
+  const int total = gx * gy * gz;
+  const int per_xcd = (total + 7) >> 3;
+  const int id = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per_xcd || id >= total) return t;
+  const int bx = id % gx, by = (id / gx) % gy, bz = id / (gx * gy);
+  t.valid = true;
+  t.n0 = bx * BN;
   if (p.mode == GEMM_RAGGED_M) {
-    int tile = blockIdx.y;
-    if (tile >= p.tile_map[0]) { t.valid = false; return t; }
-    int g = p.tile_map[1 + 2 * tile];
-    t.m0 = p.tile_map[2 + 2 * tile];
+    int g = p.tile_map[1 + 2 * by];
+    t.m0 = p.tile_map[2 + 2 * by];
     t.m_end = p.offsets[g + 1];
     t.kbeg = 0;
     t.kend = p.K;
     t.B = (const char*)p.B + (size_t)g * p.gstride_b * esz;
   } else if (p.mode == GEMM_RAGGED_K) {
-    int g = blockIdx.z;
-    t.m0 = blockIdx.y * BM;
+    t.m0 = by * BM;
     t.m_end = p.M;
-    t.kbeg = p.offsets[g];
-    t.kend = p.offsets[g + 1];
-    t.C = (char*)p.C + (size_t)g * p.gstride_c * sizeof(float);
+    t.kbeg = p.offsets[bz];
+    t.kend = p.offsets[bz + 1];
+    t.C = (char*)p.C + (size_t)bz * p.gstride_c * sizeof(float);
   } else {
-    t.m0 = blockIdx.y * BM;
+    t.m0 = by * BM;
     t.m_end = p.M;
     int per = (p.K + p.ksplit - 1) / p.ksplit;
     per = (per + 63) / 64 * 64;
-    t.kbeg = blockIdx.z * per;
+    t.kbeg = bz * per;
     t.kend = min(p.K, t.kbeg + per);
     if (t.kend < t.kbeg) t.kend = t.kbeg;
-    if (p.ksplit > 1) t.C = (char*)p.C + (size_t)blockIdx.z * p.gstride_c * sizeof(float);
+    if (p.ksplit > 1) t.C = (char*)p.C + (size_t)bz * p.gstride_c * sizeof(float);
   }
   return t;
 }
 
 // ------------------------------------------------------------------------ MFMA kernel ------
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
 // 16-byte chunk index inside an LDS tile.  "kc" tiles keep k contiguous (CPR = BK/8 chunks per
-// row); "tr" tiles keep the m (or n) index contiguous (CPR = BM/8 chunks per k row).
+// row); "tr" tiles keep the m (or n) index contiguous (CPR = BM/8 chunks per k row).  Both are
+// XOR-swizzled inside 128-byte lines so that fragment reads spread over the banks.
 template <int CPR>
 __device__ __forceinline__ int lds_chunk_kc(int row, int cc) {
   int L = row * CPR + cc;
@@ -76,57 +103,49 @@ __device__ __forceinline__ int lds_chunk_tr(int krow, int cc) {
   return krow * CPR + ((((cc >> 1) ^ (krow & 3)) << 1) | (cc & 1));
 }
 
+// Moves one operand tile (ROWS x COLS elements, COLS contiguous in memory) from global memory
+// to LDS in 16-byte chunks.  Loads are raw buffer loads: branch-free, and anything past the
+// buffer's byte range (rows of a ragged tail, k rows past the end) reads as zero in hardware.
 template <int ROWS, int COLS, int THREADS, bool KC>
-struct TileLoader {
-  // global tile of ROWS x COLS elements (COLS contiguous), moved as 16-byte chunks
+struct TileMover {
   static constexpr int CPR = COLS / 8;
   static constexpr int NCH = ROWS * COLS / 8 / THREADS;
   static_assert(ROWS * COLS / 8 % THREADS == 0, "tile does not divide over the block");
-  uint4 reg[NCH];
-  __device__ __forceinline__ void load(const bf16_t* base, long ld, int row0, int col0, int row_end, int col_end) {
+  __amdgpu_buffer_rsrc_t rsrc;
+  unsigned voff[NCH];   // byte offset of this thread's chunks at k tile 0
+  int lchunk[NCH];      // their LDS chunk index
+  unsigned step;        // byte advance per k tile
+  __device__ __forceinline__ void init(const bf16_t* base, unsigned range_bytes, long ld, unsigned step_bytes) {
+    rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)range_bytes, 0x00020000);
+    step = step_bytes;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      int q = i * THREADS + threadIdx.x;
-      int row = q / CPR, cc = q % CPR;
-      int gr = row0 + row, gc = col0 + cc * 8;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (gr < row_end && gc < col_end) v = *(const uint4*)(base + (size_t)gr * ld + gc);
-      reg[i] = v;
+      const int q = i * THREADS + threadIdx.x;
+      const int row = q / CPR, cc = q % CPR;
+      voff[i] = (unsigned)(row * ld + cc * 8) * 2u;
+      lchunk[i] = KC ? lds_chunk_kc<CPR>(row, cc) : lds_chunk_tr<CPR>(row, cc);
     }
   }
-  __device__ __forceinline__ void store(uint4* lds) const {
+  __device__ __forceinline__ void load(u32x4_t* reg, unsigned tile_off) const {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int q = i * THREADS + threadIdx.x;
-      int row = q / CPR, cc = q % CPR;
-      int c = KC ? lds_chunk_kc<CPR>(row, cc) : lds_chunk_tr<CPR>(row, cc);
-      lds[c] = reg[i];
-    }
+    for (int i = 0; i < NCH; ++i) reg[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[i] + tile_off, 0, 0);
+  }
+  __device__ __forceinline__ void store(const u32x4_t* reg, uint4* lds) const {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) *(u32x4_t*)(lds + lchunk[i]) = reg[i];
   }
 };
 
 // One 32x8 operand fragment of the 32x32x16 MFMA: lane l holds k = 8*(l/32) .. +8 of row l%32.
-template <int CPR>
-__device__ __forceinline__ bf16x8_t frag_kc(const uint4* lds, int rb, int ks, int lane) {
-  int row = rb + (lane & 31);
-  uint4 v = lds[lds_chunk_kc<CPR>(row, ks * 2 + (lane >> 5))];
-  return __builtin_bit_cast(bf16x8_t, v);
-}
-template <int CPR>
-__device__ __forceinline__ bf16x8_t frag_tr(const uint4* lds, int rb, int ks, int lane) {
+// `chunk` / `byte` are the lane's precomputed positions for sub-tile 0; sub-tile i of a k-contiguous
+// tile is 32 rows further (a whole number of swizzle periods), of a transposed tile 64 bytes further.
+__device__ __forceinline__ bf16x8_t frag_kc(const uint4* lds, int chunk) { return __builtin_bit_cast(bf16x8_t, lds[chunk]); }
+__device__ __forceinline__ bf16x8_t frag_tr(const uint4* lds, int byte0, int byte1) {
   // Transposing LDS read: in each group of 16 lanes, lane i gives the address of 4 consecutive
   // elements of row (i/4) and receives column i of the resulting 4 x 16 block.
-  int c = rb + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  int cc = c >> 3;
-  s16x4_t part[2];
-#pragma unroll
-  for (int jj = 0; jj < 2; ++jj) {
-    int krow = ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2);
-    const char* addr = (const char*)lds + lds_chunk_tr<CPR>(krow, cc) * 16 + (c & 7) * 2;
-    part[jj] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)addr);
-  }
-  s16x8_t v = __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8_t, v);
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)((const char*)lds + byte0));
+  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)((const char*)lds + byte1));
+  return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32>
@@ -134,29 +153,103 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
   constexpr int THREADS = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int KS = BK / 16;
   constexpr int A_CHUNKS = BM * BK / 8, B_CHUNKS = BN * BK / 8;
-  __shared__ uint4 lds_a[2][A_CHUNKS];
-  __shared__ uint4 lds_b[2][B_CHUNKS];
+  constexpr int STAGE_CHUNKS = (EPI == EPI_ACCUM || OUTF32) ? 0 : 32 * (WN + 4) * 4 * WAVES_M * WAVES_N / 16;
+  constexpr int OPER_CHUNKS = 2 * A_CHUNKS + 2 * B_CHUNKS;
+  __shared__ uint4 lds_raw[OPER_CHUNKS > STAGE_CHUNKS ? OPER_CHUNKS : STAGE_CHUNKS];
+  auto lds_a = [&](int buf) { return lds_raw + buf * A_CHUNKS; };
+  auto lds_b = [&](int buf) { return lds_raw + 2 * A_CHUNKS + buf * B_CHUNKS; };
 
   TileCoord t = resolve_tile<BM, BN>(p, 2);
   if (!t.valid) return;
-  const bf16_t* A = (const bf16_t*)p.A;
-  const bf16_t* B = (const bf16_t*)t.B;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = (wave / WAVES_N) * WM, wn = (wave % WAVES_N) * WN;
+  const int klen = t.kend - t.kbeg;
+  const int nk = (klen + BK - 1) / BK;
 
-  using LoadA = TileLoader<AK ? BM : BK, AK ? BK : BM, THREADS, AK>;
-  using LoadB = TileLoader<BKC ? BN : BK, BKC ? BK : BN, THREADS, BKC>;
-  LoadA la;
-  LoadB lb;
-  auto fetch = [&](int kt) {
-    int kb = p.kwrap_b ? kt % p.kwrap_b : kt;
-    int kb_end = p.kwrap_b ? kb + (t.kend - kt) : t.kend;
-    if (AK) la.load(A, p.lda, t.m0, kt, t.m_end, t.kend);
-    else    la.load(A, p.lda, kt, t.m0, t.kend, p.M);
-    if (BKC) lb.load(B, p.ldb, t.n0, kb, p.N, kb_end);
-    else     lb.load(B, p.ldb, kb, t.n0, kb_end, p.N);
+  // operand movers; buffer ranges end at the last valid row so that tails read as zeros
+  using MoveA = TileMover<AK ? BM : BK, AK ? BK : BM, THREADS, AK>;
+  using MoveB = TileMover<BKC ? BN : BK, BKC ? BK : BN, THREADS, BKC>;
+  MoveA ma;
+  MoveB mb;
+  {
+    const bf16_t* A = (const bf16_t*)p.A;
+    if (AK) {
+      const int rows = min(t.m_end - t.m0, BM);
+      ma.init(A + (size_t)t.m0 * p.lda + t.kbeg, rows > 0 ? (unsigned)(((size_t)(rows - 1) * p.lda + klen) * 2) : 0u, p.lda, BK * 2u);
+    } else {
+      const int cols = min(p.M - t.m0, BM);
+      ma.init(A + (size_t)t.kbeg * p.lda + t.m0, klen > 0 ? (unsigned)(((size_t)(klen - 1) * p.lda + cols) * 2) : 0u, p.lda,
+              (unsigned)(BK * p.lda * 2));
+    }
+    const bf16_t* B = (const bf16_t*)t.B;
+    const int kb0 = p.kwrap_b ? 0 : t.kbeg;                  // with a wrap the whole B is one k period
+    const int kblen = p.kwrap_b ? p.kwrap_b : klen;
+    if (BKC) {
+      const int rows = min(p.N - t.n0, BN);
+      mb.init(B + (size_t)t.n0 * p.ldb + kb0, rows > 0 ? (unsigned)(((size_t)(rows - 1) * p.ldb + kblen) * 2) : 0u, p.ldb, BK * 2u);
+    } else {
+      const int cols = min(p.N - t.n0, BN);
+      mb.init(B + (size_t)kb0 * p.ldb + t.n0, kblen > 0 ? (unsigned)(((size_t)(kblen - 1) * p.ldb + cols) * 2) : 0u, p.ldb,
+              (unsigned)(BK * p.ldb * 2));
+    }
+  }
+  const int wrap_tiles = p.kwrap_b ? p.kwrap_b / BK : 0x7FFFFFFF;
+
+  // Register prefetch ring: the global loads of k tile j sit in slot j % PF for PF - 1 whole
+  // iterations before they are written to LDS, so PF tiles are in flight per block.
+  constexpr int PF = BIGMAC_TILE_PREFETCH;
+  u32x4_t ra[PF][MoveA::NCH], rb[PF][MoveB::NCH];
+  auto fetch = [&](int tile, u32x4_t* qa, u32x4_t* qb) {
+    ma.load(qa, (unsigned)tile * ma.step);
+    mb.load(qb, (unsigned)(tile % wrap_tiles) * mb.step);
   };
+
+  // Per-lane fragment positions for every k step of a tile.  k-contiguous tiles: chunk index of
+  // sub-tile 0 (sub-tile i is 32 rows = a whole number of swizzle periods further).  Transposed
+  // tiles: byte offsets of the two 4-row reads for sub-tiles 0 and 1 (32 columns are half a
+  // swizzle period; sub-tile i is (i / 2) * 128 bytes past sub-tile i % 2).
+  int pa[KS][2][2], pb[KS][2][2];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    if (AK) {
+      pa[ks][0][0] = lds_chunk_kc<BK / 8>(wm + (lane & 31), ks * 2 + (lane >> 5));
+    } else {
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+        const int c = wm + par * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+          pa[ks][jj][par] = lds_chunk_tr<BM / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
+      }
+    }
+    if (BKC) {
+      pb[ks][0][0] = lds_chunk_kc<BK / 8>(wn + (lane & 31), ks * 2 + (lane >> 5));
+    } else {
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+        const int c = wn + par * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+          pb[ks][jj][par] = lds_chunk_tr<BN / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
+      }
+    }
+  }
+
+  // EPI_DGELU multiplies by act'(saved pre-activation): fetch that tile now, use it at the end
+  constexpr int LPR_E = WN / 8, RPP_E = 64 / LPR_E, NPASS_E = 32 / RPP_E;
+  uint4 aux[EPI == EPI_DGELU ? TM * NPASS_E : 1];
+  if (EPI == EPI_DGELU) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int q = 0; q < NPASS_E; ++q) {
+        const int row = t.m0 + wm + i * 32 + q * RPP_E + lane / LPR_E, col = t.n0 + wn + (lane % LPR_E) * 8;
+        aux[i * NPASS_E + q] = (row < t.m_end && col < p.N) ? *(const uint4*)((const bf16_t*)p.aux_in + (size_t)row * p.ldc + col)
+                                                             : make_uint4(0, 0, 0, 0);
+      }
+  }
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -166,64 +259,102 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const int nk = (t.kend - t.kbeg + BK - 1) / BK;
+#pragma unroll
+  for (int s = 0; s < PF; ++s)
+    if (s < nk) fetch(s, ra[s], rb[s]);
   if (nk > 0) {
-    fetch(t.kbeg);
-    la.store(lds_a[0]);
-    lb.store(lds_b[0]);
+    ma.store(ra[0], lds_a(0));
+    mb.store(rb[0], lds_b(0));
+    if (PF < nk) fetch(PF, ra[0], rb[0]);
   }
   __syncthreads();
-  for (int it = 0; it < nk; ++it) {
-    const int cur = it & 1;
-    if (it + 1 < nk) fetch(t.kbeg + (it + 1) * BK);
+  for (int it0 = 0; it0 < nk; it0 += PF) {
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8_t fa[TM], fb[TN];
+    for (int s = 0; s < PF; ++s) {
+      const int it = it0 + s;
+      if (it >= nk) break;
+      const int cur = it & 1;
+      const uint4* sa = lds_a(cur);
+      const uint4* sb = lds_b(cur);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = AK ? frag_kc<BK / 8>(lds_a[cur], wm + i * 32, ks, lane) : frag_tr<BM / 8>(lds_a[cur], wm + i * 32, ks, lane);
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8_t fa[TM], fb[TN];
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        fb[j] = BKC ? frag_kc<BK / 8>(lds_b[cur], wn + j * 32, ks, lane) : frag_tr<BN / 8>(lds_b[cur], wn + j * 32, ks, lane);
+        for (int i = 0; i < TM; ++i)
+          fa[i] = AK ? frag_kc(sa, pa[ks][0][0] + i * 32 * (BK / 8)) : frag_tr(sa, pa[ks][0][i & 1] + (i >> 1) * 128, pa[ks][1][i & 1] + (i >> 1) * 128);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j)
+          fb[j] = BKC ? frag_kc(sb, pb[ks][0][0] + j * 32 * (BK / 8)) : frag_tr(sb, pb[ks][0][j & 1] + (j >> 1) * 128, pb[ks][1][j & 1] + (j >> 1) * 128);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+      if (it + 1 < nk) {
+        ma.store(ra[(s + 1) % PF], lds_a(cur ^ 1));
+        mb.store(rb[(s + 1) % PF], lds_b(cur ^ 1));
+        if (it + 1 + PF < nk) fetch(it + 1 + PF, ra[(s + 1) % PF], rb[(s + 1) % PF]);
+      }
+      __syncthreads();
     }
-    if (it + 1 < nk) {
-      la.store(lds_a[cur ^ 1]);
-      lb.store(lds_b[cur ^ 1]);
-    }
-    __syncthreads();
   }
 
   // epilogue: lane l of a 32x32 tile holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4
+  if (EPI == EPI_ACCUM || OUTF32) {
+    // fp32 results: a lane group already writes 128 contiguous bytes per row
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = t.n0 + wn + j * 32 + (lane & 31);
-      if (col >= p.N) continue;
+      for (int j = 0; j < TN; ++j) {
+        const int col = t.n0 + wn + j * 32 + (lane & 31);
+        if (col >= p.N) continue;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = t.m0 + wm + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        if (row >= t.m_end) continue;
-        const size_t off = (size_t)row * p.ldc + col;
-        const float a = acc[i][j][v];
-        if (EPI == EPI_STORE) {
-          if (OUTF32) ((float*)t.C)[off] = a;
-          else ((bf16_t*)t.C)[off] = f2bf(a);
-        } else if (EPI == EPI_GELU) {
-          if (p.aux_out) ((bf16_t*)p.aux_out)[off] = f2bf(a);
-          ((bf16_t*)t.C)[off] = f2bf(gelu_f(a));
-        } else if (EPI == EPI_DGELU) {
-          ((bf16_t*)t.C)[off] = f2bf(a * gelu_grad_f(bf2f(((const bf16_t*)p.aux_in)[off])));
-        } else {
-          float* c = (float*)t.C + off;
-          *c = p.beta ? *c + a : a;
+        for (int v = 0; v < 16; ++v) {
+          const int row = t.m0 + wm + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          if (row >= t.m_end) continue;
+          float* c = (float*)t.C + (size_t)row * p.ldc + col;
+          const float a = acc[i][j][v];
+          *c = (EPI == EPI_ACCUM && p.beta) ? *c + a : a;
         }
       }
+    return;
+  }
+  // bf16 results: transpose through LDS (a private strip per wave) so that every lane handles 8
+  // consecutive columns of one row: 16-byte loads and stores, whole 128-byte lines per row.
+  constexpr int SLD = WN + 4;               // floats per staged row
+  constexpr int LPR = WN / 8;               // lanes per row
+  constexpr int RPP = 64 / LPR;             // rows per pass
+  float* const stage = (float*)lds_raw + wave * (32 * SLD);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        stage[((v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * SLD + j * 32 + (lane & 31)] = acc[i][j][v];
+    __syncthreads();
+#pragma unroll
+    for (int r0 = 0; r0 < 32; r0 += RPP) {
+      const int r = r0 + lane / LPR, c = (lane % LPR) * 8;
+      const int row = t.m0 + wm + i * 32 + r, col = t.n0 + wn + c;
+      if (row >= t.m_end || col >= p.N) continue;
+      const float4 v0 = *(const float4*)(stage + r * SLD + c), v1 = *(const float4*)(stage + r * SLD + c + 4);
+      float a[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      const size_t off = (size_t)row * p.ldc + col;
+      if (EPI == EPI_GELU) {
+        if (p.aux_out) *(uint4*)((bf16_t*)p.aux_out + off) = pack_bf16x8(a);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) a[q] = gelu_f(a[q]);
+      } else if (EPI == EPI_DGELU) {
+        float s[8];
+        unpack_bf16x8(aux[i * NPASS_E + r0 / RPP], s);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) a[q] *= gelu_grad_f(s[q]);
+      }
+      *(uint4*)((bf16_t*)t.C + off) = pack_bf16x8(a);
     }
+  }
 }
 
 // ------------------------------------------------------------------------ fp32 kernel ------
@@ -323,7 +454,7 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, int nslic
   out[i] = s;
 }
 
-int gemm_ragged_tile_rows(int dtype) { return dtype == BIGMAC_BF16 ? 128 : 64; }
+int gemm_ragged_tile_rows(int dtype) { return dtype == BIGMAC_BF16 ? BIGMAC_TILE_BM : 64; }
 
 int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* tile_map, hipStream_t s) {
   if (groups > 1024) return BIGMAC_ERR_UNSUPPORTED;
@@ -341,17 +472,18 @@ int launch_reduce_partials(const float* part, int nslices, size_t n, float* out,
 namespace {
 
 template <int BM, int BN>
-dim3 grid_for(const GemmDesc& g) {
-  unsigned gx = (g.N + BN - 1) / BN;
-  if (g.mode == GEMM_RAGGED_M) return dim3(gx, (unsigned)(g.max_rows / BM + g.groups + 1), 1);
-  unsigned gy = (g.M + BM - 1) / BM;
-  if (g.mode == GEMM_RAGGED_K) return dim3(gx, gy, g.groups);
-  return dim3(gx, gy, g.ksplit);
+dim3 grid_for(const GemmDesc& g) {  // one-dimensional, a multiple of the 8 XCDs; surplus blocks exit
+  long gx = (g.N + BN - 1) / BN, gy, gz = 1;
+  if (g.mode == GEMM_RAGGED_M) gy = g.max_rows / BM + g.groups + 1;
+  else gy = (g.M + BM - 1) / BM;
+  if (g.mode == GEMM_RAGGED_K) gz = g.groups;
+  if (g.mode == GEMM_DENSE) gz = g.ksplit;
+  return dim3((unsigned)((gx * gy * gz + 7) / 8 * 8), 1, 1);
 }
 
 template <bool AK, bool BKC>
 int launch_mfma(const GemmDesc& g, hipStream_t s) {
-  constexpr int BM = 128, BN = 128, BK = 64, WMs = 2, WNs = 2;
+  constexpr int BM = BIGMAC_TILE_BM, BN = BIGMAC_TILE_BN, BK = BIGMAC_TILE_BK, WMs = BIGMAC_TILE_WM, WNs = BIGMAC_TILE_WN;
   dim3 grid = grid_for<BM, BN>(g), block(64 * WMs * WNs);
 #define BIGMAC_MFMA(EPI, OUTF32) \
   hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI, OUTF32>), grid, block, 0, s, g)

@@ -92,21 +92,6 @@ __global__ __launch_bounds__(256) void dispatch_rows_kernel(const uint4* __restr
   for (int j = 0; j < k; ++j) x_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c] = v;
 }
 
-__device__ __forceinline__ void unpack8(const uint4& v, float* f) {
-  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
-  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
-  f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
-  f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
-}
-__device__ __forceinline__ uint4 pack8(const float* f) {
-  uint4 v;
-  v.x = (uint32_t)f2bf(f[0]) | ((uint32_t)f2bf(f[1]) << 16);
-  v.y = (uint32_t)f2bf(f[2]) | ((uint32_t)f2bf(f[3]) << 16);
-  v.z = (uint32_t)f2bf(f[4]) | ((uint32_t)f2bf(f[5]) << 16);
-  v.w = (uint32_t)f2bf(f[6]) | ((uint32_t)f2bf(f[7]) << 16);
-  return v;
-}
-
 // y_low[t] = sum_j w[t,j] * o_perm[slot_of[t,j]], j ascending, fp32.  Thread = (token, 8 columns).
 template <int OUT>
 __global__ __launch_bounds__(256) void combine_rows_bf16_kernel(const uint4* __restrict__ o_perm, const int32_t* __restrict__ slot_of,
@@ -119,7 +104,7 @@ __global__ __launch_bounds__(256) void combine_rows_bf16_kernel(const uint4* __r
   for (int j = 0; j < k; ++j) {
     const float wj = w ? w[(size_t)t * k + j] : 1.0f;
     float o[8];
-    unpack8(o_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c], o);
+    unpack_bf16x8(o_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c], o);
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = fmaf(wj, o[i], acc[i]);
   }
@@ -129,14 +114,14 @@ __global__ __launch_bounds__(256) void combine_rows_bf16_kernel(const uint4* __r
     out[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
   } else {  // bf16 (hi | lo): acc = hi + lo up to 2^-17 relative
     float lo[8];
-    uint4 hi = pack8(acc);
+    uint4 hi = pack_bf16x8(acc);
     float hf[8];
-    unpack8(hi, hf);
+    unpack_bf16x8(hi, hf);
 #pragma unroll
     for (int i = 0; i < 8; ++i) lo[i] = acc[i] - hf[i];
     uint4* out = (uint4*)((bf16_t*)y + (size_t)t * 2 * width);
     out[c] = hi;
-    out[cpr + c] = pack8(lo);
+    out[cpr + c] = pack_bf16x8(lo);
   }
 }
 

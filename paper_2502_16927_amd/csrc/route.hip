@@ -15,6 +15,8 @@ constexpr int R_NB = 16;    // experts per pass
 constexpr int R_QT = 4;     // 64-row blocks of W_g staged per LDS tile
 constexpr int R_PAD = 20;   // floats per staged row (16 + 4: conflict-free 16-byte reads)
 
+// Block = 4 wavefronts x 8 tokens, one pass of 16 experts (blockIdx.y); the 16 router columns are
+// staged through LDS in tiles of 256 rows and shared by the four wavefronts.
 template <typename XT>
 __global__ __launch_bounds__(256) void router_logits_kernel(const XT* __restrict__ x, const float* __restrict__ wg,
                                                             const float* __restrict__ bias, float* __restrict__ logits,
@@ -22,62 +24,75 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const XT* __restrict
   __shared__ float sw[R_QT * 64 * R_PAD];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int t0 = blockIdx.x * (4 * R_TB) + wave * R_TB;
+  const int n0 = blockIdx.y * R_NB;
   const int nq = d / 64;
-  for (int n0 = 0; n0 < N; n0 += R_NB) {
-    float acc[R_TB * R_NB];
+  const bool vec = (N % 4) == 0;
+  float acc[R_TB * R_NB];
 #pragma unroll
-    for (int v = 0; v < R_TB * R_NB; ++v) acc[v] = 0.0f;
-    for (int q0 = 0; q0 < nq; q0 += R_QT) {
-      __syncthreads();
+  for (int v = 0; v < R_TB * R_NB; ++v) acc[v] = 0.0f;
+  for (int q0 = 0; q0 < nq; q0 += R_QT) {
+    // this tile's tokens first: R_QT x R_TB independent loads in flight
+    float xv[R_QT][R_TB];
+#pragma unroll
+    for (int qq = 0; qq < R_QT; ++qq)
+#pragma unroll
+      for (int i = 0; i < R_TB; ++i) {
+        const int t = t0 + i;
+        xv[qq][i] = (t < T && q0 + qq < nq) ? Elem<XT>::load(x + (size_t)t * d + (size_t)(q0 + qq) * 64 + lane) : 0.0f;
+      }
+    __syncthreads();
+    if (vec) {
+      for (int e = threadIdx.x; e < R_QT * 64 * (R_NB / 4); e += 256) {
+        const int row = e / (R_NB / 4), c = (e % (R_NB / 4)) * 4;
+        const int gi = q0 * 64 + row, gn = n0 + c;
+        float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gi < d && gn < N) w = *(const float4*)(wg + (size_t)gi * N + gn);
+        *(float4*)(sw + row * R_PAD + c) = w;
+      }
+    } else {
       for (int e = threadIdx.x; e < R_QT * 64 * R_NB; e += 256) {
         const int row = e / R_NB, c = e % R_NB;
         const int gi = q0 * 64 + row, gn = n0 + c;
         sw[row * R_PAD + c] = (gi < d && gn < N) ? wg[(size_t)gi * N + gn] : 0.0f;
       }
-      __syncthreads();
-#pragma unroll
-      for (int qq = 0; qq < R_QT; ++qq) {
-        if (q0 + qq >= nq) break;
-        float xv[R_TB];
-#pragma unroll
-        for (int i = 0; i < R_TB; ++i) {
-          const int t = t0 + i;
-          xv[i] = t < T ? Elem<XT>::load(x + (size_t)t * d + (size_t)(q0 + qq) * 64 + lane) : 0.0f;
-        }
-        const float4* wrow = (const float4*)(sw + (qq * 64 + lane) * R_PAD);
-        float wv[R_NB];
-#pragma unroll
-        for (int c4 = 0; c4 < R_NB / 4; ++c4) {
-          float4 w = wrow[c4];
-          wv[c4 * 4 + 0] = w.x; wv[c4 * 4 + 1] = w.y; wv[c4 * 4 + 2] = w.z; wv[c4 * 4 + 3] = w.w;
-        }
-#pragma unroll
-        for (int i = 0; i < R_TB; ++i)
-#pragma unroll
-          for (int c = 0; c < R_NB; ++c) acc[i * R_NB + c] = fmaf(xv[i], wv[c], acc[i * R_NB + c]);
-      }
     }
-    // halving tree as a reduce-scatter: at distance off the lanes with that bit set keep the
-    // upper half of the values, the others the lower half; value 2*lane + {0,1} ends on lane.
+    __syncthreads();
 #pragma unroll
-    for (int off = 32, half = R_TB * R_NB / 2; off >= 1; off >>= 1, half >>= 1) {
-      const bool hi = (lane & off) != 0;
+    for (int qq = 0; qq < R_QT; ++qq) {
+      if (q0 + qq >= nq) break;
+      const float4* wrow = (const float4*)(sw + (qq * 64 + lane) * R_PAD);
+      float wv[R_NB];
 #pragma unroll
-      for (int v = 0; v < half; ++v) {
-        const float send = hi ? acc[v] : acc[v + half];
-        const float keep = hi ? acc[v + half] : acc[v];
-        acc[v] = keep + __shfl_xor(send, off, 64);
+      for (int c4 = 0; c4 < R_NB / 4; ++c4) {
+        float4 w = wrow[c4];
+        wv[c4 * 4 + 0] = w.x; wv[c4 * 4 + 1] = w.y; wv[c4 * 4 + 2] = w.z; wv[c4 * 4 + 3] = w.w;
       }
+#pragma unroll
+      for (int i = 0; i < R_TB; ++i)
+#pragma unroll
+        for (int c = 0; c < R_NB; ++c) acc[i * R_NB + c] = fmaf(xv[qq][i], wv[c], acc[i * R_NB + c]);
     }
+  }
+  // halving tree as a reduce-scatter: at distance off the lanes with that bit set keep the
+  // upper half of the values, the others the lower half; value 2*lane + {0,1} ends on lane.
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int v = 2 * lane + u;
-      const int t = t0 + v / R_NB, n = n0 + v % R_NB;
-      if (t < T && n < N) {
-        float val = acc[u];
-        if (bias) val = val + bias[n];
-        logits[(size_t)t * N + n] = val;
-      }
+  for (int off = 32, half = R_TB * R_NB / 2; off >= 1; off >>= 1, half >>= 1) {
+    const bool hi = (lane & off) != 0;
+#pragma unroll
+    for (int v = 0; v < half; ++v) {
+      const float send = hi ? acc[v] : acc[v + half];
+      const float keep = hi ? acc[v + half] : acc[v];
+      acc[v] = keep + __shfl_xor(send, off, 64);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int v = 2 * lane + u;
+    const int t = t0 + v / R_NB, n = n0 + v % R_NB;
+    if (t < T && n < N) {
+      float val = acc[u];
+      if (bias) val = val + bias[n];
+      logits[(size_t)t * N + n] = val;
     }
   }
 }
@@ -186,7 +201,7 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __res
 }  // namespace
 
 int launch_router_logits(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias, float* logits, hipStream_t s) {
-  const dim3 grid((D.T + 31) / 32), block(256);
+  const dim3 grid((D.T + 31) / 32, (D.N + R_NB - 1) / R_NB), block(256);
   if (D.dtype == BIGMAC_BF16)
     hipLaunchKernelGGL(router_logits_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
   else
