@@ -17,8 +17,8 @@
 #define BIGMAC_TILE_WM 2
 #define BIGMAC_TILE_WN 2
 #endif
-#ifndef BIGMAC_TILE_PREFETCH
-#define BIGMAC_TILE_PREFETCH 3   // k tiles of global loads in flight per block
+#ifndef BIGMAC_TILE_STAGES
+#define BIGMAC_TILE_STAGES 4     // LDS ring stages: STAGES - 1 k tiles of global loads in flight per block
 #endif
 
 namespace bigmac {
@@ -103,42 +103,61 @@ __device__ __forceinline__ int lds_chunk_tr(int krow, int cc) {
   return krow * CPR + ((((cc >> 1) ^ (krow & 3)) << 1) | (cc & 1));
 }
 
+// Inverse of the two swizzles: which (row, 16-byte column chunk) lives at LDS chunk position q.
+template <int CPR>
+__device__ __forceinline__ void lds_unchunk_kc(int q, int& row, int& cc) {
+  const int line = q >> 3;
+  const int L = (line << 3) | ((q & 7) ^ (line & 7));
+  row = L / CPR;
+  cc = L % CPR;
+}
+template <int CPR>
+__device__ __forceinline__ void lds_unchunk_tr(int q, int& krow, int& cc) {
+  krow = q / CPR;
+  const int pc = q % CPR;
+  cc = ((((pc >> 1) ^ (krow & 3)) << 1) | (pc & 1));
+}
+
 // Moves one operand tile (ROWS x COLS elements, COLS contiguous in memory) from global memory
-// to LDS in 16-byte chunks.  Loads are raw buffer loads: branch-free, and anything past the
-// buffer's byte range (rows of a ragged tail, k rows past the end) reads as zero in hardware.
+// straight into LDS (buffer load with LDS destination, 16 bytes per lane, no registers in
+// between).  The hardware places the 64 lanes of a wavefront at consecutive 16-byte positions,
+// so lane q loads whatever the swizzle wants at position q.  Loads are branch-free, and anything
+// past the buffer's byte range (rows of a ragged tail, k rows past the end) arrives as zeros.
 template <int ROWS, int COLS, int THREADS, bool KC>
 struct TileMover {
   static constexpr int CPR = COLS / 8;
   static constexpr int NCH = ROWS * COLS / 8 / THREADS;
   static_assert(ROWS * COLS / 8 % THREADS == 0, "tile does not divide over the block");
   __amdgpu_buffer_rsrc_t rsrc;
-  unsigned voff[NCH];   // byte offset of this thread's chunks at k tile 0
-  int lchunk[NCH];      // their LDS chunk index
+  unsigned voff[NCH];   // byte offset of this lane's chunks at k tile 0
   unsigned step;        // byte advance per k tile
+  int wave_chunk;       // first LDS chunk of this wavefront within a pass (wave-uniform)
   __device__ __forceinline__ void init(const bf16_t* base, unsigned range_bytes, long ld, unsigned step_bytes) {
     rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)range_bytes, 0x00020000);
     step = step_bytes;
+    wave_chunk = __builtin_amdgcn_readfirstlane((int)(threadIdx.x & ~63u));
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int q = i * THREADS + threadIdx.x;
-      const int row = q / CPR, cc = q % CPR;
+      int row, cc;
+      if (KC) lds_unchunk_kc<CPR>(q, row, cc);
+      else lds_unchunk_tr<CPR>(q, row, cc);
       voff[i] = (unsigned)(row * ld + cc * 8) * 2u;
-      lchunk[i] = KC ? lds_chunk_kc<CPR>(row, cc) : lds_chunk_tr<CPR>(row, cc);
     }
   }
-  __device__ __forceinline__ void load(u32x4_t* reg, unsigned tile_off) const {
+  __device__ __forceinline__ void load(uint4* lds, unsigned tile_off) const {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc cannot parse this builtin inside a template
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) reg[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[i] + tile_off, 0, 0);
-  }
-  __device__ __forceinline__ void store(const u32x4_t* reg, uint4* lds) const {
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) *(u32x4_t*)(lds + lchunk[i]) = reg[i];
+    for (int i = 0; i < NCH; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds + i * THREADS + wave_chunk), 16,
+                                               voff[i] + tile_off, 0, 0, 0);
+#else
+    (void)lds; (void)tile_off;
+#endif
   }
 };
 
 // One 32x8 operand fragment of the 32x32x16 MFMA: lane l holds k = 8*(l/32) .. +8 of row l%32.
-// `chunk` / `byte` are the lane's precomputed positions for sub-tile 0; sub-tile i of a k-contiguous
-// tile is 32 rows further (a whole number of swizzle periods), of a transposed tile 64 bytes further.
 __device__ __forceinline__ bf16x8_t frag_kc(const uint4* lds, int chunk) { return __builtin_bit_cast(bf16x8_t, lds[chunk]); }
 __device__ __forceinline__ bf16x8_t frag_tr(const uint4* lds, int byte0, int byte1) {
   // Transposing LDS read: in each group of 16 lanes, lane i gives the address of 4 consecutive
@@ -148,6 +167,9 @@ __device__ __forceinline__ bf16x8_t frag_tr(const uint4* lds, int byte0, int byt
   return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+// s_waitcnt that only waits for the vector-memory counter to drop to n (gfx9 encoding)
+#define BIGMAC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32>
 __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDesc p) {
   constexpr int THREADS = 64 * WAVES_M * WAVES_N;
@@ -155,11 +177,17 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int KS = BK / 16;
   constexpr int A_CHUNKS = BM * BK / 8, B_CHUNKS = BN * BK / 8;
-  constexpr int STAGE_CHUNKS = (EPI == EPI_ACCUM || OUTF32) ? 0 : 32 * (WN + 4) * 4 * WAVES_M * WAVES_N / 16;
-  constexpr int OPER_CHUNKS = 2 * A_CHUNKS + 2 * B_CHUNKS;
-  __shared__ uint4 lds_raw[OPER_CHUNKS > STAGE_CHUNKS ? OPER_CHUNKS : STAGE_CHUNKS];
-  auto lds_a = [&](int buf) { return lds_raw + buf * A_CHUNKS; };
-  auto lds_b = [&](int buf) { return lds_raw + 2 * A_CHUNKS + buf * B_CHUNKS; };
+  constexpr int NS = BIGMAC_TILE_STAGES;  // LDS ring: NS - 1 k tiles in flight while one is consumed
+  // bf16 results accumulate the transposed tile (operands swapped in the MFMA): a lane then owns
+  // one output row and groups of 4 consecutive columns, which pack into 8-byte pieces
+  constexpr bool SWAP = !(EPI == EPI_ACCUM || OUTF32);
+  static_assert(NS >= 2 && NS <= 4, "ring of 2 to 4 stages");
+  // one LDS object per stage: the compiler then knows which loads a fragment read depends on
+  __shared__ uint4 ring0[A_CHUNKS + B_CHUNKS];
+  __shared__ uint4 ring1[A_CHUNKS + B_CHUNKS];
+  __shared__ uint4 ring2[NS > 2 ? A_CHUNKS + B_CHUNKS : 1];
+  __shared__ uint4 ring3[NS > 3 ? A_CHUNKS + B_CHUNKS : 1];
+#define BIGMAC_RING(s) ((s) == 0 ? ring0 : (s) == 1 ? ring1 : (s) == 2 ? ring2 : ring3)
 
   TileCoord t = resolve_tile<BM, BN>(p, 2);
   if (!t.valid) return;
@@ -196,15 +224,16 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
     }
   }
   const int wrap_tiles = p.kwrap_b ? p.kwrap_b / BK : 0x7FFFFFFF;
-
-  // Register prefetch ring: the global loads of k tile j sit in slot j % PF for PF - 1 whole
-  // iterations before they are written to LDS, so PF tiles are in flight per block.
-  constexpr int PF = BIGMAC_TILE_PREFETCH;
-  u32x4_t ra[PF][MoveA::NCH], rb[PF][MoveB::NCH];
-  auto fetch = [&](int tile, u32x4_t* qa, u32x4_t* qb) {
-    ma.load(qa, (unsigned)tile * ma.step);
-    mb.load(qb, (unsigned)(tile % wrap_tiles) * mb.step);
+  // k tile `tile` -> ring stage `s`.  Tiles past the end are still requested: they lie outside
+  // the buffer range (zeros, no memory traffic) and keep the number of loads in flight constant.
+  auto fetch = [&](int tile, int s) {
+    uint4* dst = BIGMAC_RING(s);
+    if (tile < nk || !AK) ma.load(dst, (unsigned)tile * ma.step);
+    else ma.load(dst, 0xFFFF0000u);                       // k-contiguous operands do not end at a row: force out of range
+    if (tile < nk || !BKC) mb.load(dst + A_CHUNKS, (unsigned)(tile % wrap_tiles) * mb.step);
+    else mb.load(dst + A_CHUNKS, 0xFFFF0000u);
   };
+  constexpr int LOADS_PER_TILE = MoveA::NCH + MoveB::NCH;
 
   // Per-lane fragment positions for every k step of a tile.  k-contiguous tiles: chunk index of
   // sub-tile 0 (sub-tile i is 32 rows = a whole number of swizzle periods further).  Transposed
@@ -237,17 +266,17 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
     }
   }
 
-  // EPI_DGELU multiplies by act'(saved pre-activation): fetch that tile now, use it at the end
-  constexpr int LPR_E = WN / 8, RPP_E = 64 / LPR_E, NPASS_E = 32 / RPP_E;
-  uint4 aux[EPI == EPI_DGELU ? TM * NPASS_E : 1];
+  // EPI_DGELU multiplies by act'(saved pre-activation): request that tile now (row layout: 8 lanes
+  // per 64-column row, 8 rows per pass), use it in the epilogue
+  uint4 aux[EPI == EPI_DGELU ? TM * 4 : 1];
   if (EPI == EPI_DGELU) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int q = 0; q < NPASS_E; ++q) {
-        const int row = t.m0 + wm + i * 32 + q * RPP_E + lane / LPR_E, col = t.n0 + wn + (lane % LPR_E) * 8;
-        aux[i * NPASS_E + q] = (row < t.m_end && col < p.N) ? *(const uint4*)((const bf16_t*)p.aux_in + (size_t)row * p.ldc + col)
-                                                             : make_uint4(0, 0, 0, 0);
+      for (int q = 0; q < 4; ++q) {
+        const int row = t.m0 + wm + i * 32 + q * 8 + (lane >> 3), col = t.n0 + wn + (lane & 7) * 8;
+        aux[i * 4 + q] = (row < t.m_end && col < p.N) ? *(const uint4*)((const bf16_t*)p.aux_in + (size_t)row * p.ldc + col)
+                                                       : make_uint4(0, 0, 0, 0);
       }
   }
 
@@ -260,22 +289,17 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
 #pragma unroll
-  for (int s = 0; s < PF; ++s)
-    if (s < nk) fetch(s, ra[s], rb[s]);
-  if (nk > 0) {
-    ma.store(ra[0], lds_a(0));
-    mb.store(rb[0], lds_b(0));
-    if (PF < nk) fetch(PF, ra[0], rb[0]);
-  }
-  __syncthreads();
-  for (int it0 = 0; it0 < nk; it0 += PF) {
+  for (int s = 0; s < NS - 1; ++s) fetch(s, s);
+  for (int it0 = 0; it0 < nk; it0 += NS) {
 #pragma unroll
-    for (int s = 0; s < PF; ++s) {
+    for (int s = 0; s < NS; ++s) {
       const int it = it0 + s;
       if (it >= nk) break;
-      const int cur = it & 1;
-      const uint4* sa = lds_a(cur);
-      const uint4* sb = lds_b(cur);
+      BIGMAC_WAIT_VMCNT((NS - 2) * LOADS_PER_TILE);   // this wave's part of tile `it` has landed ...
+      __builtin_amdgcn_s_barrier();                    // ... and so has everyone's; stage (s - 1) is free
+      fetch(it + NS - 1, (s + NS - 1) % NS);
+      const uint4* sa = BIGMAC_RING(s);
+      const uint4* sb = BIGMAC_RING(s) + A_CHUNKS;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         bf16x8_t fa[TM], fb[TN];
@@ -288,14 +312,10 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0)
+                             : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
       }
-      if (it + 1 < nk) {
-        ma.store(ra[(s + 1) % PF], lds_a(cur ^ 1));
-        mb.store(rb[(s + 1) % PF], lds_b(cur ^ 1));
-        if (it + 1 + PF < nk) fetch(it + 1 + PF, ra[(s + 1) % PF], rb[(s + 1) % PF]);
-      }
-      __syncthreads();
     }
   }
 
@@ -319,41 +339,81 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
       }
     return;
   }
-  // bf16 results: transpose through LDS (a private strip per wave) so that every lane handles 8
-  // consecutive columns of one row: 16-byte loads and stores, whole 128-byte lines per row.
-  constexpr int SLD = WN + 4;               // floats per staged row
-  constexpr int LPR = WN / 8;               // lanes per row
-  constexpr int RPP = 64 / LPR;             // rows per pass
-  float* const stage = (float*)lds_raw + wave * (32 * SLD);
+  // bf16 results.  With the transposed accumulation lane l owns row l%32 of each 32-row sub-tile
+  // and, per accumulator quad, 4 consecutive columns: the epilogue math runs on the accumulators,
+  // quads are packed to 8 bytes and pass through an LDS strip private to the wave (32 rows x 64
+  // columns) to come out as whole rows: 16-byte stores, 128 contiguous bytes per row.
+  static_assert(WN == 64, "the strip holds 64-column wave tiles");
+  constexpr int SROW = 144;                                    // bytes per staged row (128 + 16 against conflicts)
+  constexpr int NWAVES = WAVES_M * WAVES_N;
+  constexpr int WPR = (NWAVES + NS - 1) / NS;                  // waves sharing one ring stage
+  static_assert(WPR * 32 * SROW <= (A_CHUNKS + B_CHUNKS) * 16, "staging strips do not fit a ring stage");
+  BIGMAC_WAIT_VMCNT(0);
+  __builtin_amdgcn_s_barrier();                                // all ring traffic is over
+  char* const strip = (char*)BIGMAC_RING(wave % NS) + (wave / NS) * (32 * SROW);
+  char* const quad_at = strip + (lane & 31) * SROW + (lane >> 5) * 8;   // + (j*32 + vq*8) * 2
+  char* const row_at = strip + (lane >> 3) * SROW + (lane & 7) * 16;    // + pass * 8 * SROW
+  const int out_col = t.n0 + wn + (lane & 7) * 8;
+  auto wave_sync = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  auto flush_rows = [&](bf16_t* dst, int i) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = t.m0 + wm + i * 32 + q * 8 + (lane >> 3);
+      const uint4 v = *(const uint4*)(row_at + q * 8 * SROW);
+      if (row < t.m_end && out_col < p.N) *(uint4*)(dst + (size_t)row * p.ldc + out_col) = v;
+    }
+  };
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    __syncthreads();
+    if (EPI == EPI_GELU && p.aux_out) {   // the pre-activation itself, for the backward pass
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          uint2 w;
+          w.x = f2bf_pair(acc[i][j][vq * 4 + 0], acc[i][j][vq * 4 + 1]);
+          w.y = f2bf_pair(acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]);
+          *(uint2*)(quad_at + (j * 32 + vq * 8) * 2) = w;
+        }
+      wave_sync();
+      flush_rows((bf16_t*)p.aux_out, i);
+      wave_sync();
+    }
+    if (EPI == EPI_DGELU) {               // saved pre-activation: rows in, quads out
+#pragma unroll
+      for (int q = 0; q < 4; ++q) *(uint4*)(row_at + q * 8 * SROW) = aux[i * 4 + q];
+      wave_sync();
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        stage[((v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * SLD + j * 32 + (lane & 31)] = acc[i][j][v];
-    __syncthreads();
+      for (int vq = 0; vq < 4; ++vq) {
+        float v[4];
 #pragma unroll
-    for (int r0 = 0; r0 < 32; r0 += RPP) {
-      const int r = r0 + lane / LPR, c = (lane % LPR) * 8;
-      const int row = t.m0 + wm + i * 32 + r, col = t.n0 + wn + c;
-      if (row >= t.m_end || col >= p.N) continue;
-      const float4 v0 = *(const float4*)(stage + r * SLD + c), v1 = *(const float4*)(stage + r * SLD + c + 4);
-      float a[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-      const size_t off = (size_t)row * p.ldc + col;
-      if (EPI == EPI_GELU) {
-        if (p.aux_out) *(uint4*)((bf16_t*)p.aux_out + off) = pack_bf16x8(a);
+        for (int vr = 0; vr < 4; ++vr) v[vr] = acc[i][j][vq * 4 + vr];
+        uint2* slot = (uint2*)(quad_at + (j * 32 + vq * 8) * 2);
+        if (EPI == EPI_GELU) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) a[q] = gelu_f(a[q]);
-      } else if (EPI == EPI_DGELU) {
-        float s[8];
-        unpack_bf16x8(aux[i * NPASS_E + r0 / RPP], s);
-#pragma unroll
-        for (int q = 0; q < 8; ++q) a[q] *= gelu_grad_f(s[q]);
+          for (int vr = 0; vr < 4; ++vr) v[vr] = gelu_f(v[vr]);
+        } else if (EPI == EPI_DGELU) {
+          const uint2 sv = *slot;
+          v[0] *= gelu_grad_f(__uint_as_float(sv.x << 16));
+          v[1] *= gelu_grad_f(__uint_as_float(sv.x & 0xFFFF0000u));
+          v[2] *= gelu_grad_f(__uint_as_float(sv.y << 16));
+          v[3] *= gelu_grad_f(__uint_as_float(sv.y & 0xFFFF0000u));
+        }
+        uint2 w;
+        w.x = f2bf_pair(v[0], v[1]);
+        w.y = f2bf_pair(v[2], v[3]);
+        *slot = w;
       }
-      *(uint4*)((bf16_t*)t.C + off) = pack_bf16x8(a);
-    }
+    wave_sync();
+    flush_rows((bf16_t*)t.C, i);
+    wave_sync();
   }
 }
 
