@@ -25,13 +25,20 @@ __global__ __launch_bounds__(256) void perm_count_kernel(const int32_t* __restri
   for (int e = threadIdx.x; e < N; e += 256) counts[(size_t)blockIdx.x * N + e] = cnt[e];
 }
 
-// in place: counts[c][e] -> first slot of expert e's pairs of chunk c;  offsets[e] = first slot of e
+// in place: counts[c][e] -> first slot of expert e's pairs of chunk c;  offsets[e] = first slot of e.
+// One thread per expert; chunks are read 8 at a time so that the loads overlap.
 __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ counts, int nchunks, int N, int32_t* __restrict__ offsets) {
   __shared__ int scan[1024];
   const int e = threadIdx.x;
   int total = 0;
   if (e < N)
-    for (int c = 0; c < nchunks; ++c) total += counts[(size_t)c * N + e];
+    for (int c0 = 0; c0 < nchunks; c0 += 8) {
+      int v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = c0 + u < nchunks ? counts[(size_t)(c0 + u) * N + e] : 0;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) total += v[u];
+    }
   scan[e] = total;
   __syncthreads();
   for (int off = 1; off < 1024; off <<= 1) {
@@ -43,10 +50,15 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ c
   if (e < N) {
     int run = scan[e] - total;
     offsets[e] = run;
-    for (int c = 0; c < nchunks; ++c) {
-      int v = counts[(size_t)c * N + e];
-      counts[(size_t)c * N + e] = run;
-      run += v;
+    for (int c0 = 0; c0 < nchunks; c0 += 8) {
+      int v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = c0 + u < nchunks ? counts[(size_t)(c0 + u) * N + e] : 0;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (c0 + u < nchunks) counts[(size_t)(c0 + u) * N + e] = run;
+        run += v[u];
+      }
     }
     if (e == N - 1) offsets[N] = run;
   }

@@ -97,6 +97,118 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const XT* __restrict
   }
 }
 
+// Same computation for N % 4 == 0, software-pipelined: the 32 x 256 token tile and the 256 x 16
+// router tile of the next step travel global -> LDS directly (16 bytes per lane, no registers)
+// while the current step's 512 fused multiply-adds per lane run.  Token rows past T and router
+// rows past d lie outside the buffer ranges and arrive as zeros; they are never used anyway.
+#define BIGMAC_ROUTER_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+template <typename XT>
+__global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* __restrict__ x, const float* __restrict__ wg,
+                                                                      const float* __restrict__ bias, float* __restrict__ logits,
+                                                                      int T, int d, int N) {
+  constexpr int XROW = 256 * sizeof(XT) / 16;       // 16-byte chunks per token row of a tile
+  constexpr int XCH = 32 * XROW;                    // chunks of a token tile
+  constexpr int WCH = 256 * 4;                      // chunks of a router tile (256 rows x 16 floats)
+  constexpr int XL = XCH / 256, WL = WCH / 256;     // loads per thread
+  __shared__ uint4 xs0[XCH];
+  __shared__ uint4 xs1[XCH];
+  __shared__ uint4 ws0[WCH];
+  __shared__ uint4 ws1[WCH];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int tb = blockIdx.x * 32, t0 = tb + wave * R_TB;
+  const int n0 = blockIdx.y * R_NB;
+  const int nq = d / 64, ntiles = (nq + 3) / 4;
+  const int rows = min(32, T - tb), cols = min(R_NB, N - n0);
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)(x + (size_t)tb * d), 0, (int)((size_t)rows * d * sizeof(XT)), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)(wg + n0), 0, (int)(((size_t)(d - 1) * N + cols) * 4), 0x00020000);
+  const int wave_chunk = __builtin_amdgcn_readfirstlane((int)(threadIdx.x & ~63u));
+  unsigned xoff[XL], woff[WL];
+#pragma unroll
+  for (int i = 0; i < XL; ++i) {
+    const int q = i * 256 + threadIdx.x;
+    xoff[i] = (unsigned)((q / XROW) * d * sizeof(XT) + (q % XROW) * 16);
+  }
+#pragma unroll
+  for (int i = 0; i < WL; ++i) {   // LDS position q holds column chunk (q & 3) ^ ((row >> 1) & 3) of row q >> 2
+    const int q = i * 256 + threadIdx.x, row = q >> 2;
+    woff[i] = (unsigned)((row * N + (((q & 3) ^ ((row >> 1) & 3)) << 2)) * 4);
+  }
+  auto issue = [&](int tile, uint4* xs, uint4* ws) {
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+    for (int i = 0; i < XL; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(xs + i * 256 + wave_chunk), 16,
+                                               xoff[i] + (unsigned)(tile * 256 * sizeof(XT)), 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < WL; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void*)(ws + i * 256 + wave_chunk), 16,
+                                               woff[i] + (unsigned)(tile * 256 * N * 4), 0, 0, 0);
+#else
+    (void)tile; (void)xs; (void)ws;
+#endif
+  };
+  float acc[R_TB * R_NB];
+#pragma unroll
+  for (int v = 0; v < R_TB * R_NB; ++v) acc[v] = 0.0f;
+  auto compute = [&](int tile, const uint4* xs, const uint4* ws) {
+    const XT* xt = (const XT*)xs + (wave * R_TB) * 256 + lane;
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq) {
+      if (tile * 4 + qq >= nq) break;
+      float xv[R_TB];
+#pragma unroll
+      for (int i = 0; i < R_TB; ++i) xv[i] = Elem<XT>::load(xt + i * 256 + qq * 64);
+      const int row = qq * 64 + lane;
+      float wv[R_NB];
+#pragma unroll
+      for (int c4 = 0; c4 < 4; ++c4) {
+        const uint4 w = ws[row * 4 + (c4 ^ ((row >> 1) & 3))];
+        wv[c4 * 4 + 0] = __uint_as_float(w.x); wv[c4 * 4 + 1] = __uint_as_float(w.y);
+        wv[c4 * 4 + 2] = __uint_as_float(w.z); wv[c4 * 4 + 3] = __uint_as_float(w.w);
+      }
+#pragma unroll
+      for (int i = 0; i < R_TB; ++i)
+#pragma unroll
+        for (int c = 0; c < R_NB; ++c) acc[i * R_NB + c] = fmaf(xv[i], wv[c], acc[i * R_NB + c]);
+    }
+  };
+  issue(0, xs0, ws0);
+  for (int tile = 0; tile < ntiles; tile += 2) {
+    if (tile + 1 < ntiles) { issue(tile + 1, xs1, ws1); BIGMAC_ROUTER_WAIT_VMCNT(XL + WL); }
+    else BIGMAC_ROUTER_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    compute(tile, xs0, ws0);
+    __builtin_amdgcn_s_barrier();
+    if (tile + 1 >= ntiles) break;
+    if (tile + 2 < ntiles) { issue(tile + 2, xs0, ws0); BIGMAC_ROUTER_WAIT_VMCNT(XL + WL); }
+    else BIGMAC_ROUTER_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    compute(tile + 1, xs1, ws1);
+    __builtin_amdgcn_s_barrier();
+  }
+  // halving tree as a reduce-scatter (see router_logits_kernel)
+#pragma unroll
+  for (int off = 32, half = R_TB * R_NB / 2; off >= 1; off >>= 1, half >>= 1) {
+    const bool hi = (lane & off) != 0;
+#pragma unroll
+    for (int v = 0; v < half; ++v) {
+      const float send = hi ? acc[v] : acc[v + half];
+      const float keep = hi ? acc[v + half] : acc[v];
+      acc[v] = keep + __shfl_xor(send, off, 64);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int v = 2 * lane + u;
+    const int t = t0 + v / R_NB, n = n0 + v % R_NB;
+    if (t < T && n < N) {
+      float val = acc[u];
+      if (bias) val = val + bias[n];
+      logits[(size_t)t * N + n] = val;
+    }
+  }
+}
+
 // One wavefront per token: k rounds of arg-max over the remaining logits (ties to the lowest
 // index), then the softmax over the k picked logits.  PER = logits held per lane.
 template <int PER>
@@ -202,10 +314,14 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __res
 
 int launch_router_logits(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias, float* logits, hipStream_t s) {
   const dim3 grid((D.T + 31) / 32, (D.N + R_NB - 1) / R_NB), block(256);
-  if (D.dtype == BIGMAC_BF16)
-    hipLaunchKernelGGL(router_logits_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
-  else
-    hipLaunchKernelGGL(router_logits_kernel<float>, grid, block, 0, s, (const float*)x, w_gate, bias, logits, D.T, D.d, D.N);
+  const bool pipelined = D.N % 4 == 0 && (size_t)D.d * D.N * 4 < (1ull << 31);   // 16-byte router rows, 32-bit buffer range
+  if (D.dtype == BIGMAC_BF16) {
+    if (pipelined) hipLaunchKernelGGL(router_logits_pipelined_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
+    else hipLaunchKernelGGL(router_logits_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
+  } else {
+    if (pipelined) hipLaunchKernelGGL(router_logits_pipelined_kernel<float>, grid, block, 0, s, (const float*)x, w_gate, bias, logits, D.T, D.d, D.N);
+    else hipLaunchKernelGGL(router_logits_kernel<float>, grid, block, 0, s, (const float*)x, w_gate, bias, logits, D.T, D.d, D.N);
+  }
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }
