@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--order", default="dcca", choices=["dcca", "cdac"])
     ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of the oracle timing sample (0: skip)")
     ap.add_argument("--no-stage-events", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="time eager launches instead of replays of the step captured in a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -152,6 +154,8 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    # Pass 1, eager launches: one pair of HIP events around every stage of every step, on the
+    # stream the kernels are launched on (per-stage durations for the roofline).
     tables = [] if args.no_stage_events else [B.StageEvents() for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -160,8 +164,24 @@ def main():
             tables[i].install()
         step()
     torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    eager_elapsed = time.perf_counter() - t0
     B.StageEvents.clear()
+    # Pass 2, the timed region: the same step (the library only enqueues kernels, no memsets,
+    # no synchronisation) captured once in a HIP graph and replayed K times, which removes the
+    # host's launch gaps between the ~35 kernels of a step.
+    elapsed, timed = eager_elapsed, "eager launches"
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed, timed = time.perf_counter() - t0, "replays of the step captured in a HIP graph"
 
     ms_per_step = elapsed / args.steps * 1e3
     work = stage_work(wl, cdac, training)
@@ -197,6 +217,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "order": args.order, "T": wl.T, "d": wl.d, "r": wl.r, "N": wl.N, "k": wl.k,
                    "h": wl.h, "pass": "fwd+bwd" if training else "fwd"},
+        "timed": timed,
+        "eager_ms_per_step": eager_elapsed / args.steps * 1e3,
         "roofline": roofline,
         "matrix_tflops": fwd_flops * (3 if training else 1) / (elapsed / args.steps) / 1e12,
         "permute_bytes_per_step": B.permute_bytes(dims) * (1.0 if training else 0.5),

@@ -17,6 +17,10 @@
 #define BIGMAC_TILE_WM 2
 #define BIGMAC_TILE_WN 2
 #endif
+// Phase time stamps for kernel studies; compiled out unless a harness defines the macro.
+#ifndef BIGMAC_TRACE_POINT
+#define BIGMAC_TRACE_POINT(i)
+#endif
 #ifndef BIGMAC_TILE_STAGES
 #define BIGMAC_TILE_STAGES 4     // LDS ring stages: STAGES - 1 k tiles of global loads in flight per block
 #endif
@@ -191,6 +195,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
 
   TileCoord t = resolve_tile<BM, BN>(p, 2);
   if (!t.valid) return;
+  BIGMAC_TRACE_POINT(0);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = (wave / WAVES_N) * WM, wn = (wave % WAVES_N) * WN;
   const int klen = t.kend - t.kbeg;
@@ -297,6 +302,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
       if (it >= nk) break;
       BIGMAC_WAIT_VMCNT((NS - 2) * LOADS_PER_TILE);   // this wave's part of tile `it` has landed ...
       __builtin_amdgcn_s_barrier();                    // ... and so has everyone's; stage (s - 1) is free
+      if (it == 0) BIGMAC_TRACE_POINT(1);
       fetch(it + NS - 1, (s + NS - 1) % NS);
       const uint4* sa = BIGMAC_RING(s);
       const uint4* sb = BIGMAC_RING(s) + A_CHUNKS;
@@ -319,6 +325,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
     }
   }
 
+  BIGMAC_TRACE_POINT(2);
   // epilogue: lane l of a 32x32 tile holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4
   if (EPI == EPI_ACCUM || OUTF32) {
     // fp32 results: a lane group already writes 128 contiguous bytes per row
@@ -415,6 +422,9 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
     flush_rows((bf16_t*)t.C, i);
     wave_sync();
   }
+  BIGMAC_TRACE_POINT(3);
+  BIGMAC_WAIT_VMCNT(0);
+  BIGMAC_TRACE_POINT(4);
 }
 
 // ------------------------------------------------------------------------ fp32 kernel ------
