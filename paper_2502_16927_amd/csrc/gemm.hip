@@ -273,15 +273,28 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
 
   // EPI_DGELU multiplies by act'(saved pre-activation): request that tile now (row layout: 8 lanes
   // per 64-column row, 8 rows per pass), use it in the epilogue
+  // Output rows as buffers: the range ends with the last valid row, so rows of the next group
+  // (or past M) fall outside it and their stores are dropped and their loads read as zero
+  // without a branch; columns at or beyond N get an offset that is out of range by itself.
+  const int c_rows = min(t.m_end - t.m0, BM);
+  constexpr unsigned OUT_OF_RANGE = 0x80000000u;
+  auto rows_of = [&](const void* base, int esz_out) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (size_t)t.m0 * p.ldc * esz_out), 0,
+                                             c_rows > 0 ? (int)(((size_t)(c_rows - 1) * p.ldc + p.N) * esz_out) : 0, 0x00020000);
+  };
+  // EPI_DGELU multiplies by act'(saved pre-activation): request that tile now (row layout: 8 lanes
+  // per 64-column row, 8 rows per pass), use it in the epilogue
   uint4 aux[EPI == EPI_DGELU ? TM * 4 : 1];
   if (EPI == EPI_DGELU) {
+    const __amdgpu_buffer_rsrc_t ra = rows_of(p.aux_in, 2);
+    const int col = t.n0 + wn + (lane & 7) * 8;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int row = t.m0 + wm + i * 32 + q * 8 + (lane >> 3), col = t.n0 + wn + (lane & 7) * 8;
-        aux[i * 4 + q] = (row < t.m_end && col < p.N) ? *(const uint4*)((const bf16_t*)p.aux_in + (size_t)row * p.ldc + col)
-                                                       : make_uint4(0, 0, 0, 0);
+        const int row = wm + i * 32 + q * 8 + (lane >> 3);
+        const unsigned off = col < p.N ? (unsigned)(((size_t)row * p.ldc + col) * 2) : OUT_OF_RANGE;
+        aux[i * 4 + q] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, 0));
       }
   }
 
@@ -328,22 +341,44 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
   BIGMAC_TRACE_POINT(2);
   // epilogue: lane l of a 32x32 tile holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4
   if (EPI == EPI_ACCUM || OUTF32) {
-    // fp32 results: a lane group already writes 128 contiguous bytes per row
+    // fp32 results: a lane group already writes 128 contiguous bytes per row.  Accumulation into
+    // C requests the whole old tile before the first add: one memory round trip, not one per element.
+    const __amdgpu_buffer_rsrc_t rc = rows_of(t.C, 4);
+    unsigned off[TM][TN][4];   // (i, j, v / 4): offset of the quad's first row; the 4 rows of a quad are ldc apart
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int col = t.n0 + wn + j * 32 + (lane & 31);
-        if (col >= p.N) continue;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = t.m0 + wm + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-          if (row >= t.m_end) continue;
-          float* c = (float*)t.C + (size_t)row * p.ldc + col;
-          const float a = acc[i][j][v];
-          *c = (EPI == EPI_ACCUM && p.beta) ? *c + a : a;
+        for (int vq = 0; vq < 4; ++vq) {
+          const int row = wm + i * 32 + vq * 8 + (lane >> 5) * 4;
+          off[i][j][vq] = col < p.N ? (unsigned)(((size_t)row * p.ldc + col) * 4) : OUT_OF_RANGE;
         }
       }
+    const unsigned row_step = (unsigned)(p.ldc * 4);
+    if (EPI == EPI_ACCUM && p.beta) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {   // 32 rows at a time: 32 values per lane in flight
+        float old[TN][16];
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            old[j][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rc, off[i][j][v >> 2] + (v & 3) * row_step, 0, 0));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][j][v] += old[j][v];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v]), rc, off[i][j][v >> 2] + (v & 3) * row_step, 0, 0);
     return;
   }
   // bf16 results.  With the transposed accumulation lane l owns row l%32 of each 32-row sub-tile
@@ -366,13 +401,17 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   };
-  auto flush_rows = [&](bf16_t* dst, int i) {
+  const __amdgpu_buffer_rsrc_t rc = rows_of(t.C, 2);
+  const __amdgpu_buffer_rsrc_t rx = rows_of(EPI == EPI_GELU && p.aux_out ? p.aux_out : t.C, 2);
+  const unsigned out_off = out_col < p.N ? (unsigned)(((size_t)(wm + (lane >> 3)) * p.ldc + out_col) * 2) : OUT_OF_RANGE;
+  const unsigned pass_step = (unsigned)(8 * p.ldc * 2);
+  auto flush_rows = [&](const __amdgpu_buffer_rsrc_t& dst, int i) {
+    uint4 v[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int row = t.m0 + wm + i * 32 + q * 8 + (lane >> 3);
-      const uint4 v = *(const uint4*)(row_at + q * 8 * SROW);
-      if (row < t.m_end && out_col < p.N) *(uint4*)(dst + (size_t)row * p.ldc + out_col) = v;
-    }
+    for (int q = 0; q < 4; ++q) v[q] = *(const uint4*)(row_at + q * 8 * SROW);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v[q]), dst, out_off + (unsigned)(i * 4 + q) * pass_step, 0, 0);
   };
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -387,7 +426,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
           *(uint2*)(quad_at + (j * 32 + vq * 8) * 2) = w;
         }
       wave_sync();
-      flush_rows((bf16_t*)p.aux_out, i);
+      flush_rows(rx, i);
       wave_sync();
     }
     if (EPI == EPI_DGELU) {               // saved pre-activation: rows in, quads out
@@ -419,7 +458,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
         *slot = w;
       }
     wave_sync();
-    flush_rows((bf16_t*)t.C, i);
+    flush_rows(rc, i);
     wave_sync();
   }
   BIGMAC_TRACE_POINT(3);
