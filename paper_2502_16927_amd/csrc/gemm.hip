@@ -556,11 +556,31 @@ __global__ void build_tile_map_kernel(const int* __restrict__ offsets, int group
 }
 
 __global__ void reduce_partials_kernel(const float* __restrict__ part, int nslices, size_t n, float* __restrict__ out, int beta) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  // one float4 of the output per thread; slices are summed in ascending order, eight loads in flight
+  const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (i >= n) return;
-  float s = beta ? out[i] : 0.0f;
-  for (int z = 0; z < nslices; ++z) s += part[(size_t)z * n + i];
-  out[i] = s;
+  if ((n & 3) == 0) {   // then every slice keeps the 16-byte alignment
+    float4 s = beta ? *(const float4*)(out + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+    int z = 0;
+    for (; z + 8 <= nslices; z += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *(const float4*)(part + (size_t)(z + u) * n + i);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+    for (; z < nslices; ++z) {
+      const float4 v = *(const float4*)(part + (size_t)z * n + i);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    *(float4*)(out + i) = s;
+  } else {
+    for (size_t e = i; e < n && e < i + 4; ++e) {
+      float s = beta ? out[e] : 0.0f;
+      for (int z = 0; z < nslices; ++z) s += part[(size_t)z * n + e];
+      out[e] = s;
+    }
+  }
 }
 
 int gemm_ragged_tile_rows(int dtype) { return dtype == BIGMAC_BF16 ? BIGMAC_TILE_BM : 64; }
@@ -573,7 +593,7 @@ int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* ti
 }
 
 int launch_reduce_partials(const float* part, int nslices, size_t n, float* out, int beta, hipStream_t s) {
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part, nslices, n, out, beta);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, part, nslices, n, out, beta);
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }
