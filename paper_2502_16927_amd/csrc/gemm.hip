@@ -18,8 +18,8 @@
 #define BIGMAC_TILE_WN 2
 #endif
 // Phase time stamps for kernel studies; compiled out unless a harness defines the macro.
-#ifndef BIGMAC_TRACE_POINT
-#define BIGMAC_TRACE_POINT(i)
+#ifndef BIGMAC_TRACE_AT
+#define BIGMAC_TRACE_AT(tile, i)
 #endif
 #ifndef BIGMAC_TILE_STAGES
 #define BIGMAC_TILE_STAGES 4     // LDS ring stages: STAGES - 1 k tiles of global loads in flight per block
@@ -41,26 +41,40 @@ struct TileCoord {
   bool valid;
 };
 
-// Works out which tile this block owns.  BM/BN: tile shape.
-//
-// The launch is one-dimensional.  MI355X hands consecutive workgroup ids to its 8 XCDs in turn and
-// every XCD has its own L2, so the id is first turned into (xcd, position) and each XCD is given a
-// contiguous run of logical tiles, n tile fastest: the blocks that share an A tile, and the M
-// tiles that share one expert's weights, then meet in one L2 instead of being fetched eight times.
+// Tile enumeration.  The launch is one-dimensional.  MI355X hands consecutive workgroup ids to
+// its 8 XCDs in turn and every XCD has its own L2, so a workgroup id is first turned into
+// (xcd = id % 8, slot = id / 8) and each XCD is given a contiguous run of logical tiles, n tile
+// fastest: the blocks that share an A tile, and the M tiles that share one expert's weights, then
+// meet in one L2 instead of being fetched eight times.
+struct TileSpace {
+  int gx, gy, total, per_xcd;
+};
 template <int BM, int BN>
-__device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, int esz) {
+__device__ __forceinline__ TileSpace tile_space(const GemmDesc& p) {
+  TileSpace ts;
+  ts.gx = (p.N + BN - 1) / BN;
+  ts.gy = p.mode == GEMM_RAGGED_M ? p.tile_map[0] : (p.M + BM - 1) / BM;
+  const int gz = p.mode == GEMM_RAGGED_K ? p.groups : (p.mode == GEMM_DENSE ? p.ksplit : 1);
+  ts.total = ts.gx * ts.gy * gz;
+  ts.per_xcd = (ts.total + 7) >> 3;
+  return ts;
+}
+// logical tile of position `pos` in this workgroup's XCD run, or -1
+__device__ __forceinline__ int tile_at(const TileSpace& ts, int pos) {
+  const int id = (int)(blockIdx.x & 7) * ts.per_xcd + pos;
+  return (pos < ts.per_xcd && id < ts.total) ? id : -1;
+}
+template <int BM, int BN>
+__device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, const TileSpace& ts, int id, int esz) {
   TileCoord t;
-  t.valid = false;
   t.B = p.B;
   t.C = p.C;
-  const int gx = (p.N + BN - 1) / BN;
-  const int gy = p.mode == GEMM_RAGGED_M ? p.tile_map[0] : (p.M + BM - 1) / BM;
-  const int gz = p.mode == GEMM_RAGGED_K ? p.groups : (p.mode == GEMM_DENSE ? p.ksplit : 1);
-  const int total = gx * gy * gz;
-  const int per_xcd = (total + 7) >> 3;
-  const int id = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-  if ((int)(blockIdx.x >> 3) >= per_xcd || id >= total) return t;
-  const int bx = id % gx, by = (id / gx) % gy, bz = id / (gx * gy);
+  if (id < 0) {   // no tile: empty ranges everywhere
+    t.valid = false;
+    t.m0 = t.n0 = t.m_end = t.kbeg = t.kend = 0;
+    return t;
+  }
+  const int bx = id % ts.gx, by = (id / ts.gx) % ts.gy, bz = id / (ts.gx * ts.gy);
   t.valid = true;
   t.n0 = bx * BN;
   if (p.mode == GEMM_RAGGED_M) {
@@ -132,13 +146,9 @@ struct TileMover {
   static constexpr int CPR = COLS / 8;
   static constexpr int NCH = ROWS * COLS / 8 / THREADS;
   static_assert(ROWS * COLS / 8 % THREADS == 0, "tile does not divide over the block");
-  __amdgpu_buffer_rsrc_t rsrc;
   unsigned voff[NCH];   // byte offset of this lane's chunks at k tile 0
-  unsigned step;        // byte advance per k tile
   int wave_chunk;       // first LDS chunk of this wavefront within a pass (wave-uniform)
-  __device__ __forceinline__ void init(const bf16_t* base, unsigned range_bytes, long ld, unsigned step_bytes) {
-    rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)range_bytes, 0x00020000);
-    step = step_bytes;
+  __device__ __forceinline__ void init(long ld) {
     wave_chunk = __builtin_amdgcn_readfirstlane((int)(threadIdx.x & ~63u));
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
@@ -149,31 +159,112 @@ struct TileMover {
       voff[i] = (unsigned)(row * ld + cc * 8) * 2u;
     }
   }
-  __device__ __forceinline__ void load(uint4* lds, unsigned tile_off) const {
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, uint4* lds, unsigned tile_off) const {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc cannot parse this builtin inside a template
 #pragma unroll
     for (int i = 0; i < NCH; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds + i * THREADS + wave_chunk), 16,
                                                voff[i] + tile_off, 0, 0, 0);
 #else
-    (void)lds; (void)tile_off;
+    (void)rsrc; (void)lds; (void)tile_off;
 #endif
   }
 };
 
-// One 32x8 operand fragment of the 32x32x16 MFMA: lane l holds k = 8*(l/32) .. +8 of row l%32.
-__device__ __forceinline__ bf16x8_t frag_kc(const uint4* lds, int chunk) { return __builtin_bit_cast(bf16x8_t, lds[chunk]); }
-__device__ __forceinline__ bf16x8_t frag_tr(const uint4* lds, int byte0, int byte1) {
-  // Transposing LDS read: in each group of 16 lanes, lane i gives the address of 4 consecutive
-  // elements of row (i/4) and receives column i of the resulting 4 x 16 block.
-  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)((const char*)lds + byte0));
-  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)((const char*)lds + byte1));
-  return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+// LDS accesses of the epilogue's staging strips, as assembly the compiler does not look into.
+// The compiler makes every LDS access it knows of wait for all direct-to-LDS loads in flight
+// unless it can pair the access with the loads of one particular LDS object; the strips are
+// used while the next tile's prefetch is in flight, and such a wait would undo the overlap.
+// Within a wavefront the LDS executes these in issue order, so a read issued after a write sees
+// it; lds_wait() makes the data of the reads issued so far available.
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const void*)p;
+}
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void lds_write_b64(unsigned addr, u32x2_t v) {
+  asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write_b128(unsigned addr, u32x4_t v) {
+  asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_read_b64(unsigned addr, u32x2_t& v) {
+  asm volatile("ds_read_b64 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+}
+__device__ __forceinline__ void lds_read_b128(unsigned addr, u32x4_t& v) {
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+}
+template <typename T, int N>
+__device__ __forceinline__ void lds_wait(T (&v)[N]) {   // the values become usable behind this point
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+v"(v[i]));
+}
+// The same with a 16-bit instruction offset, for the operand fragments in the ring.
+template <int OFFSET>
+__device__ __forceinline__ void lds_read_b128(unsigned addr, u32x4_t& v) {
+  static_assert(OFFSET >= 0 && OFFSET < 65536, "instruction offset");
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+}
+// Transposing read: in each group of 16 lanes, lane i gives the address of 4 consecutive 16-bit
+// elements of row (i/4) and receives column i of the resulting 4 x 16 block.
+template <int OFFSET>
+__device__ __forceinline__ void lds_read_tr_b64(unsigned addr, u32x2_t& v) {
+  static_assert(OFFSET >= 0 && OFFSET < 65536, "instruction offset");
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+}
+template <int STILL_UNDER_WAY>
+__device__ __forceinline__ void lds_wait_for() {   // all but the last STILL_UNDER_WAY LDS reads have delivered
+  static_assert(STILL_UNDER_WAY >= 0 && STILL_UNDER_WAY < 16, "counter range");
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(STILL_UNDER_WAY) : "memory");
+}
+// One 32x8 operand fragment of the 32x32x16 MFMA (lane l: k = 8*(l/32) .. +8 of row l%32), read
+// either as one 16-byte piece of a k-contiguous tile or as two transposing reads of 4 k rows.
+template <bool KCONTIG>
+struct Frag;
+template <>
+struct Frag<true> {
+  u32x4_t q;
+  __device__ __forceinline__ void settle() { asm volatile("" : "+v"(q)); }   // orders the uses behind the wait in front of this call
+  __device__ __forceinline__ bf16x8_t value() const { return __builtin_bit_cast(bf16x8_t, q); }
+};
+template <>
+struct Frag<false> {
+  u32x2_t h[2];
+  __device__ __forceinline__ void settle() {
+    asm volatile("" : "+v"(h[0]));
+    asm volatile("" : "+v"(h[1]));
+  }
+  __device__ __forceinline__ bf16x8_t value() const { return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3)); }
+};
+template <int I>
+struct StaticIndex { static constexpr int value = I; };
+template <int BEGIN, int END, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(StaticIndex<BEGIN>{});
+    static_for<BEGIN + 1, END>(f);
+  }
 }
 
 // s_waitcnt that only waits for the vector-memory counter to drop to n (gfx9 encoding)
 #define BIGMAC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
+// One tile's operands as the movers need them.
+struct TileOperands {
+  TileCoord t;
+  __amdgpu_buffer_rsrc_t ra, rb;
+  unsigned step_a, step_b;   // byte advance per k tile
+  int nk;                    // k tiles
+};
+
+// Persistent kernel: a workgroup walks the tiles of its XCD run (stride = workgroups per XCD).
+// Per tile: a ring of NS LDS stages, NS - 1 k tiles in flight while one is consumed, one barrier
+// per k tile.  When a tile's k loop ends, the first NS - 1 k tiles of the workgroup's next tile
+// are requested before the epilogue starts, so the epilogue's arithmetic and stores overlap that
+// latency.  Every vector memory instruction is issued unconditionally (accesses that must not
+// happen are pushed out of their buffer's range instead of being branched around): the number of
+// instructions in flight behind any load is then a compile-time constant, which is what the
+// counter waits below and the compiler's own ones are derived from.
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32>
 __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDesc p) {
   constexpr int THREADS = 64 * WAVES_M * WAVES_N;
@@ -185,285 +276,357 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
   // bf16 results accumulate the transposed tile (operands swapped in the MFMA): a lane then owns
   // one output row and groups of 4 consecutive columns, which pack into 8-byte pieces
   constexpr bool SWAP = !(EPI == EPI_ACCUM || OUTF32);
-  static_assert(NS >= 2 && NS <= 4, "ring of 2 to 4 stages");
-  // one LDS object per stage: the compiler then knows which loads a fragment read depends on
-  __shared__ uint4 ring0[A_CHUNKS + B_CHUNKS];
-  __shared__ uint4 ring1[A_CHUNKS + B_CHUNKS];
-  __shared__ uint4 ring2[NS > 2 ? A_CHUNKS + B_CHUNKS : 1];
-  __shared__ uint4 ring3[NS > 3 ? A_CHUNKS + B_CHUNKS : 1];
-#define BIGMAC_RING(s) ((s) == 0 ? ring0 : (s) == 1 ? ring1 : (s) == 2 ? ring2 : ring3)
+  static_assert(NS >= 3 && NS <= 4, "ring of 3 or 4 stages");
+  // The ring.  All reads of it are assembly (see lds_read_*), so the only waits on its loads are
+  // the counter waits written out below.
+  constexpr int STAGE_CHUNKS = A_CHUNKS + B_CHUNKS;
+  constexpr int STAGE_BYTES = STAGE_CHUNKS * 16;
+  static_assert(NS * STAGE_BYTES <= 65536, "fragment reads address the ring through 16-bit instruction offsets");
+  __shared__ uint4 ring[NS * STAGE_CHUNKS];
+  const unsigned ring_at = lds_address(ring);
+  constexpr unsigned OUT_OF_RANGE = 0x80000000u;
+  // Cache policy of the layer's big one-pass streams: non-temporal.  These are the results of
+  // the two activation epilogues and the saved pre-activation read back by the second (the
+  // [rows, hidden] tensors), and all fp32 results (weight gradients, y, dx).  Left at the default
+  // they fill the XCD's L2 (4 MB, about what its workgroups write per round of tiles) and push out
+  // the operand tiles that neighbouring workgroups share.  Narrow bf16 results, which the next
+  // kernel reads back, keep the default; so do all operand loads (measured: slower otherwise).
+  constexpr int NON_TEMPORAL = 2;
+  constexpr int STREAMING = (EPI == EPI_GELU || EPI == EPI_DGELU) ? NON_TEMPORAL : 0;
 
-  TileCoord t = resolve_tile<BM, BN>(p, 2);
-  if (!t.valid) return;
-  BIGMAC_TRACE_POINT(0);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = (wave / WAVES_N) * WM, wn = (wave % WAVES_N) * WN;
-  const int klen = t.kend - t.kbeg;
-  const int nk = (klen + BK - 1) / BK;
 
-  // operand movers; buffer ranges end at the last valid row so that tails read as zeros
   using MoveA = TileMover<AK ? BM : BK, AK ? BK : BM, THREADS, AK>;
   using MoveB = TileMover<BKC ? BN : BK, BKC ? BK : BN, THREADS, BKC>;
+  constexpr int LOADS_PER_TILE = MoveA::NCH + MoveB::NCH;
   MoveA ma;
   MoveB mb;
-  {
+  ma.init(p.lda);
+  mb.init(p.ldb);
+  const int wrap_tiles = p.kwrap_b ? p.kwrap_b / BK : 0x7FFFFFFF;
+
+  const TileSpace ts = tile_space<BM, BN>(p);
+  // buffers of one tile (id < 0: no tile, empty ranges); ranges end at the last valid row so that
+  // tails read as zeros
+  auto operands = [&](int id) {
+    TileOperands o;
+    o.t = resolve_tile<BM, BN>(p, ts, id, 2);
+    const TileCoord& t = o.t;
+    const int klen = t.kend - t.kbeg;
+    o.nk = (klen + BK - 1) / BK;
     const bf16_t* A = (const bf16_t*)p.A;
     if (AK) {
       const int rows = min(t.m_end - t.m0, BM);
-      ma.init(A + (size_t)t.m0 * p.lda + t.kbeg, rows > 0 ? (unsigned)(((size_t)(rows - 1) * p.lda + klen) * 2) : 0u, p.lda, BK * 2u);
+      o.ra = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (size_t)t.m0 * p.lda + t.kbeg), 0,
+                                               rows > 0 && klen > 0 ? (int)(((size_t)(rows - 1) * p.lda + klen) * 2) : 0, 0x00020000);
+      o.step_a = BK * 2u;
     } else {
-      const int cols = min(p.M - t.m0, BM);
-      ma.init(A + (size_t)t.kbeg * p.lda + t.m0, klen > 0 ? (unsigned)(((size_t)(klen - 1) * p.lda + cols) * 2) : 0u, p.lda,
-              (unsigned)(BK * p.lda * 2));
+      const int cols = t.valid ? min(p.M - t.m0, BM) : 0;
+      o.ra = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (size_t)t.kbeg * p.lda + t.m0), 0,
+                                               klen > 0 && cols > 0 ? (int)(((size_t)(klen - 1) * p.lda + cols) * 2) : 0, 0x00020000);
+      o.step_a = (unsigned)(BK * p.lda * 2);
     }
     const bf16_t* B = (const bf16_t*)t.B;
     const int kb0 = p.kwrap_b ? 0 : t.kbeg;                  // with a wrap the whole B is one k period
-    const int kblen = p.kwrap_b ? p.kwrap_b : klen;
+    const int kblen = !t.valid ? 0 : (p.kwrap_b ? p.kwrap_b : klen);
     if (BKC) {
       const int rows = min(p.N - t.n0, BN);
-      mb.init(B + (size_t)t.n0 * p.ldb + kb0, rows > 0 ? (unsigned)(((size_t)(rows - 1) * p.ldb + kblen) * 2) : 0u, p.ldb, BK * 2u);
+      o.rb = __builtin_amdgcn_make_buffer_rsrc((void*)(B + (size_t)t.n0 * p.ldb + kb0), 0,
+                                               rows > 0 && kblen > 0 ? (int)(((size_t)(rows - 1) * p.ldb + kblen) * 2) : 0, 0x00020000);
+      o.step_b = BK * 2u;
     } else {
       const int cols = min(p.N - t.n0, BN);
-      mb.init(B + (size_t)kb0 * p.ldb + t.n0, kblen > 0 ? (unsigned)(((size_t)(kblen - 1) * p.ldb + cols) * 2) : 0u, p.ldb,
-              (unsigned)(BK * p.ldb * 2));
+      o.rb = __builtin_amdgcn_make_buffer_rsrc((void*)(B + (size_t)kb0 * p.ldb + t.n0), 0,
+                                               kblen > 0 && cols > 0 ? (int)(((size_t)(kblen - 1) * p.ldb + cols) * 2) : 0, 0x00020000);
+      o.step_b = (unsigned)(BK * p.ldb * 2);
     }
-  }
-  const int wrap_tiles = p.kwrap_b ? p.kwrap_b / BK : 0x7FFFFFFF;
-  // k tile `tile` -> ring stage `s`.  Tiles past the end are still requested: they lie outside
-  // the buffer range (zeros, no memory traffic) and keep the number of loads in flight constant.
-  auto fetch = [&](int tile, int s) {
-    uint4* dst = BIGMAC_RING(s);
-    if (tile < nk || !AK) ma.load(dst, (unsigned)tile * ma.step);
-    else ma.load(dst, 0xFFFF0000u);                       // k-contiguous operands do not end at a row: force out of range
-    if (tile < nk || !BKC) mb.load(dst + A_CHUNKS, (unsigned)(tile % wrap_tiles) * mb.step);
-    else mb.load(dst + A_CHUNKS, 0xFFFF0000u);
+    return o;
   };
-  constexpr int LOADS_PER_TILE = MoveA::NCH + MoveB::NCH;
+  // k tile `tile` of tile `o` -> one ring stage.  k tiles past the end are still requested, out of
+  // range (zeros, no memory traffic): the number of loads in flight stays constant.
+  auto fetch = [&](const TileOperands& o, int tile, uint4* dst) {
+    const bool live = tile < o.nk;
+    const unsigned off_a = live ? (unsigned)tile * o.step_a : OUT_OF_RANGE;
+    const unsigned off_b = live ? (unsigned)(tile % wrap_tiles) * o.step_b : OUT_OF_RANGE;
+    ma.load(o.ra, dst, off_a);
+    mb.load(o.rb, dst + A_CHUNKS, off_b);
+  };
+  auto prefetch = [&](const TileOperands& o) {   // the first NS - 1 k tiles into stages 0 .. NS - 2
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) fetch(o, s, ring + s * STAGE_CHUNKS);
+  };
 
   // Per-lane fragment positions for every k step of a tile.  k-contiguous tiles: chunk index of
   // sub-tile 0 (sub-tile i is 32 rows = a whole number of swizzle periods further).  Transposed
   // tiles: byte offsets of the two 4-row reads for sub-tiles 0 and 1 (32 columns are half a
   // swizzle period; sub-tile i is (i / 2) * 128 bytes past sub-tile i % 2).
-  int pa[KS][2][2], pb[KS][2][2];
+  unsigned pa[KS][2][2], pb[KS][2][2];   // LDS byte addresses within stage 0
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     if (AK) {
-      pa[ks][0][0] = lds_chunk_kc<BK / 8>(wm + (lane & 31), ks * 2 + (lane >> 5));
+      pa[ks][0][0] = ring_at + lds_chunk_kc<BK / 8>(wm + (lane & 31), ks * 2 + (lane >> 5)) * 16;
     } else {
 #pragma unroll
       for (int par = 0; par < 2; ++par) {
         const int c = wm + par * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
-          pa[ks][jj][par] = lds_chunk_tr<BM / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
+          pa[ks][jj][par] = ring_at + lds_chunk_tr<BM / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
       }
     }
     if (BKC) {
-      pb[ks][0][0] = lds_chunk_kc<BK / 8>(wn + (lane & 31), ks * 2 + (lane >> 5));
+      pb[ks][0][0] = ring_at + A_CHUNKS * 16 + lds_chunk_kc<BK / 8>(wn + (lane & 31), ks * 2 + (lane >> 5)) * 16;
     } else {
 #pragma unroll
       for (int par = 0; par < 2; ++par) {
         const int c = wn + par * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
-          pb[ks][jj][par] = lds_chunk_tr<BN / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
+          pb[ks][jj][par] = ring_at + A_CHUNKS * 16 + lds_chunk_tr<BN / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
       }
     }
   }
 
-  // EPI_DGELU multiplies by act'(saved pre-activation): request that tile now (row layout: 8 lanes
-  // per 64-column row, 8 rows per pass), use it in the epilogue
   // Output rows as buffers: the range ends with the last valid row, so rows of the next group
   // (or past M) fall outside it and their stores are dropped and their loads read as zero
   // without a branch; columns at or beyond N get an offset that is out of range by itself.
-  const int c_rows = min(t.m_end - t.m0, BM);
-  constexpr unsigned OUT_OF_RANGE = 0x80000000u;
-  auto rows_of = [&](const void* base, int esz_out) {
+  auto rows_of = [&](const TileCoord& t, const void* base, int esz_out) {
+    const int c_rows = min(t.m_end - t.m0, BM);
     return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (size_t)t.m0 * p.ldc * esz_out), 0,
                                              c_rows > 0 ? (int)(((size_t)(c_rows - 1) * p.ldc + p.N) * esz_out) : 0, 0x00020000);
   };
-  // EPI_DGELU multiplies by act'(saved pre-activation): request that tile now (row layout: 8 lanes
-  // per 64-column row, 8 rows per pass), use it in the epilogue
+  // EPI_DGELU multiplies by act'(saved pre-activation): that tile is requested one tile ahead
+  // (row layout: 8 lanes per 64-column row, 8 rows per pass) and used in the epilogue
+  constexpr int AUX_LOADS = EPI == EPI_DGELU ? TM * 4 : 0;
   uint4 aux[EPI == EPI_DGELU ? TM * 4 : 1];
-  if (EPI == EPI_DGELU) {
-    const __amdgpu_buffer_rsrc_t ra = rows_of(p.aux_in, 2);
-    const int col = t.n0 + wn + (lane & 7) * 8;
+  auto request_aux = [&](const TileCoord& t) {
+    if (EPI == EPI_DGELU) {
+      const __amdgpu_buffer_rsrc_t ra = rows_of(t, p.aux_in, 2);
+      const int col = t.n0 + wn + (lane & 7) * 8;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int row = wm + i * 32 + q * 8 + (lane >> 3);
-        const unsigned off = col < p.N ? (unsigned)(((size_t)row * p.ldc + col) * 2) : OUT_OF_RANGE;
-        aux[i * 4 + q] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, 0));
-      }
-  }
-
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s) fetch(s, s);
-  for (int it0 = 0; it0 < nk; it0 += NS) {
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const int it = it0 + s;
-      if (it >= nk) break;
-      BIGMAC_WAIT_VMCNT((NS - 2) * LOADS_PER_TILE);   // this wave's part of tile `it` has landed ...
-      __builtin_amdgcn_s_barrier();                    // ... and so has everyone's; stage (s - 1) is free
-      if (it == 0) BIGMAC_TRACE_POINT(1);
-      fetch(it + NS - 1, (s + NS - 1) % NS);
-      const uint4* sa = BIGMAC_RING(s);
-      const uint4* sb = BIGMAC_RING(s) + A_CHUNKS;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8_t fa[TM], fb[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-          fa[i] = AK ? frag_kc(sa, pa[ks][0][0] + i * 32 * (BK / 8)) : frag_tr(sa, pa[ks][0][i & 1] + (i >> 1) * 128, pa[ks][1][i & 1] + (i >> 1) * 128);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          fb[j] = BKC ? frag_kc(sb, pb[ks][0][0] + j * 32 * (BK / 8)) : frag_tr(sb, pb[ks][0][j & 1] + (j >> 1) * 128, pb[ks][1][j & 1] + (j >> 1) * 128);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0)
-                             : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-      }
-    }
-  }
-
-  BIGMAC_TRACE_POINT(2);
-  // epilogue: lane l of a 32x32 tile holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4
-  if (EPI == EPI_ACCUM || OUTF32) {
-    // fp32 results: a lane group already writes 128 contiguous bytes per row.  Accumulation into
-    // C requests the whole old tile before the first add: one memory round trip, not one per element.
-    const __amdgpu_buffer_rsrc_t rc = rows_of(t.C, 4);
-    unsigned off[TM][TN][4];   // (i, j, v / 4): offset of the quad's first row; the 4 rows of a quad are ldc apart
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = t.n0 + wn + j * 32 + (lane & 31);
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          const int row = wm + i * 32 + vq * 8 + (lane >> 5) * 4;
-          off[i][j][vq] = col < p.N ? (unsigned)(((size_t)row * p.ldc + col) * 4) : OUT_OF_RANGE;
+        for (int q = 0; q < 4; ++q) {
+          const int row = wm + i * 32 + q * 8 + (lane >> 3);
+          const unsigned off = col < p.N ? (unsigned)(((size_t)row * p.ldc + col) * 2) : OUT_OF_RANGE;
+          aux[i * 4 + q] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, NON_TEMPORAL));
         }
-      }
-    const unsigned row_step = (unsigned)(p.ldc * 4);
-    if (EPI == EPI_ACCUM && p.beta) {
+    }
+  };
+  // While k tile `it` is awaited, the NS - 2 k tiles requested after it may stay in flight.  (At
+  // the start of a tile the previous epilogue's stores are in flight as well; they are younger
+  // than the whole prefetch, so this count then also waits for the rest of the prefetch, which
+  // had the length of an epilogue to arrive.)
+  constexpr int RING_AHEAD = (NS - 2) * LOADS_PER_TILE;
+
+  const int stride = (int)(gridDim.x >> 3);
+  int pos = (int)(blockIdx.x >> 3);
+  int id = tile_at(ts, pos);
+  if (id < 0) return;
+  TileOperands cur = operands(id);
+  prefetch(cur);
+  request_aux(cur.t);
+
+  while (true) {
+    const TileCoord t = cur.t;
+    const int nk = cur.nk;
+    const int cur_id = id;
+    (void)cur_id;
+    BIGMAC_TRACE_AT(cur_id, 0);
+
+    f32x16_t acc[TM][TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {   // 32 rows at a time: 32 values per lane in flight
-        float old[TN][16];
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    for (int it0 = 0; it0 < nk; it0 += NS) {
+      static_for<0, NS>([&](auto stage) {
+        constexpr int s = decltype(stage)::value;
+        const int it = it0 + s;
+        if (it >= nk) return;
+        BIGMAC_WAIT_VMCNT(RING_AHEAD);                   // this wave's part of k tile `it` has landed ...
+        __builtin_amdgcn_s_barrier();                    // ... and so has everyone's; stage (s - 1) is free
+        if (it == 0) BIGMAC_TRACE_AT(cur_id, 1);
+        fetch(cur, it + NS - 1, ring + ((s + NS - 1) % NS) * STAGE_CHUNKS);
+        // all fragments of the k tile are requested at once; the products of k step 0 start as
+        // soon as its fragments are there, while those of the later steps are still arriving
+        Frag<AK> fa[KS][TM];
+        Frag<BKC> fb[KS][TN];
+        static_for<0, KS>([&](auto kstep) {
+          constexpr int ks = decltype(kstep)::value;
+          static_for<0, TM>([&](auto sub) {
+            constexpr int i = decltype(sub)::value;
+            if constexpr (AK) lds_read_b128<s * STAGE_BYTES + i * 32 * (BK / 8) * 16>(pa[ks][0][0], fa[ks][i].q);
+            else {
+              lds_read_tr_b64<s * STAGE_BYTES + (i >> 1) * 128>(pa[ks][0][i & 1], fa[ks][i].h[0]);
+              lds_read_tr_b64<s * STAGE_BYTES + (i >> 1) * 128>(pa[ks][1][i & 1], fa[ks][i].h[1]);
+            }
+          });
+          static_for<0, TN>([&](auto sub) {
+            constexpr int j = decltype(sub)::value;
+            if constexpr (BKC) lds_read_b128<s * STAGE_BYTES + j * 32 * (BK / 8) * 16>(pb[ks][0][0], fb[ks][j].q);
+            else {
+              lds_read_tr_b64<s * STAGE_BYTES + (j >> 1) * 128>(pb[ks][0][j & 1], fb[ks][j].h[0]);
+              lds_read_tr_b64<s * STAGE_BYTES + (j >> 1) * 128>(pb[ks][1][j & 1], fb[ks][j].h[1]);
+            }
+          });
+        });
+        constexpr int READS_PER_STEP = (AK ? TM : 2 * TM) + (BKC ? TN : 2 * TN);
+        static_for<0, KS>([&](auto kstep) {
+          constexpr int ks = decltype(kstep)::value;
+          lds_wait_for<(KS - 1 - ks) * READS_PER_STEP>();   // the reads of the later k steps may still be under way
+#pragma unroll
+          for (int i = 0; i < TM; ++i) fa[ks][i].settle();
+#pragma unroll
+          for (int j = 0; j < TN; ++j) fb[ks][j].settle();
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][j].value(), fa[ks][i].value(), acc[i][j], 0, 0, 0)
+                               : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i].value(), fb[ks][j].value(), acc[i][j], 0, 0, 0);
+        });
+      });
+    }
+    BIGMAC_TRACE_AT(cur_id, 2);
+
+    // Every wave has left the k loop: the ring is free.  What is still in flight are the k tiles
+    // past the end (zeros), some of them into the last stage, which the bf16 epilogue uses as
+    // its staging strips: let them land first.
+    pos += stride;
+    id = tile_at(ts, pos);
+    const TileOperands nxt = operands(id);
+    if (SWAP) BIGMAC_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    // bf16 epilogue staging, in the ring's last stage: the prefetch below fills stages
+    // 0 .. NS - 2, and the last stage is requested again only behind the first barrier of the next
+    // k loop.  A staged row is 128 bytes = 8 chunks of 16; chunk c of row r sits at position
+    // c ^ (r % 8), which spreads both the column-wise quad accesses and the row-wise ones over
+    // all banks.  One strip (32 rows x 64 columns) per wave.
+    constexpr int SROW = 128;
+    static_assert(!SWAP || WN == 64, "the strip holds 64-column wave tiles");
+    static_assert(WAVES_M * WAVES_N * 32 * SROW <= (A_CHUNKS + B_CHUNKS) * 16, "staging strips do not fit a ring stage");
+    const unsigned strip = ring_at + (NS - 1) * STAGE_BYTES + wave * (32 * SROW);
+    const unsigned quad_row = strip + (lane & 31) * SROW + (lane >> 5) * 8;
+    const unsigned quad_swz = lane & 7;                                     // row % 8 of the quads' row
+    auto quad_at = [&](int j, int vq) { return quad_row + ((((unsigned)(j * 4 + vq)) ^ quad_swz) << 4); };
+    const unsigned row_at = strip + (lane >> 3) * SROW + (((lane & 7) ^ ((lane >> 3) & 7)) << 4);   // + pass * 8 * SROW
+    // EPI_DGELU: turn the saved pre-activation from its row layout into the accumulators' quad
+    // layout now; its registers are then free for the next tile's request, which goes out ahead
+    // of the prefetch and is therefore complete whenever a k tile of that prefetch is.
+    u32x2_t pre[EPI == EPI_DGELU ? TM * TN * 4 : 1];
+    if (EPI == EPI_DGELU) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lds_write_b128(row_at + q * 8 * SROW, __builtin_bit_cast(u32x4_t, aux[i * 4 + q]));
 #pragma unroll
         for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) lds_read_b64(quad_at(j, vq), pre[(i * TN + j) * 4 + vq]);
+      }
+      lds_wait(pre);
+      request_aux(nxt.t);
+    }
+    prefetch(nxt);
+
+    // epilogue: lane l of a 32x32 tile holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4
+    if (EPI == EPI_ACCUM || OUTF32) {
+      // fp32 results: a lane group already writes 128 contiguous bytes per row.  Accumulation into
+      // C requests 32 rows of the old tile before the first add: one memory round trip, not one
+      // per element.
+      const __amdgpu_buffer_rsrc_t rc = rows_of(t, t.C, 4);
+      const unsigned row_step = (unsigned)(p.ldc * 4);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int col = t.n0 + wn + j * 32 + (lane & 31);
+          unsigned off[4];   // offset of each quad's first row; the 4 rows of a quad are ldc apart
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const int row = wm + i * 32 + vq * 8 + (lane >> 5) * 4;
+            off[vq] = col < p.N ? (unsigned)(((size_t)row * p.ldc + col) * 4) : OUT_OF_RANGE;
+          }
+          if (EPI == EPI_ACCUM && p.beta) {
+            float old[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              old[v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rc, off[v >> 2] + (v & 3) * row_step, 0, 0));
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] += old[v];
+          }
 #pragma unroll
           for (int v = 0; v < 16; ++v)
-            old[j][v] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rc, off[i][j][v >> 2] + (v & 3) * row_step, 0, 0));
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v]), rc, off[v >> 2] + (v & 3) * row_step, 0, NON_TEMPORAL);
+        }
+    } else {
+      // bf16 results.  With the transposed accumulation lane l owns row l%32 of each 32-row sub-tile
+      // and, per accumulator quad, 4 consecutive columns: the epilogue math runs on the accumulators,
+      // quads are packed to 8 bytes and pass through the wave's LDS strip to come out as whole
+      // rows: 16-byte stores, 128 contiguous bytes per row.
+      const int out_col = t.n0 + wn + (lane & 7) * 8;
+      const __amdgpu_buffer_rsrc_t rc = rows_of(t, t.C, 2);
+      const __amdgpu_buffer_rsrc_t rx = rows_of(t, EPI == EPI_GELU && p.aux_out ? p.aux_out : t.C, 2);
+      const unsigned out_off = out_col < p.N ? (unsigned)(((size_t)(wm + (lane >> 3)) * p.ldc + out_col) * 2) : OUT_OF_RANGE;
+      const unsigned pass_step = (unsigned)(8 * p.ldc * 2);
+      auto flush_rows = [&](const __amdgpu_buffer_rsrc_t& dst, int i) {
+        u32x4_t v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lds_read_b128(row_at + q * 8 * SROW, v[q]);
+        lds_wait(v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          __builtin_amdgcn_raw_buffer_store_b128(v[q], dst, out_off + (unsigned)(i * 4 + q) * pass_step, 0, STREAMING);
+      };
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        if (EPI == EPI_GELU && p.aux_out) {   // the pre-activation itself, for the backward pass
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+              u32x2_t w;
+              w.x = f2bf_pair(acc[i][j][vq * 4 + 0], acc[i][j][vq * 4 + 1]);
+              w.y = f2bf_pair(acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]);
+              lds_write_b64(quad_at(j, vq), w);
+            }
+          flush_rows(rx, i);
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) acc[i][j][v] += old[j][v];
+          for (int vq = 0; vq < 4; ++vq) {
+            float v[4];
+#pragma unroll
+            for (int vr = 0; vr < 4; ++vr) v[vr] = acc[i][j][vq * 4 + vr];
+            if (EPI == EPI_GELU) {
+#pragma unroll
+              for (int vr = 0; vr < 4; ++vr) v[vr] = gelu_f(v[vr]);
+            } else if (EPI == EPI_DGELU) {
+              const u32x2_t sv = pre[(i * TN + j) * 4 + vq];
+              v[0] *= gelu_grad_f(__uint_as_float(sv.x << 16));
+              v[1] *= gelu_grad_f(__uint_as_float(sv.x & 0xFFFF0000u));
+              v[2] *= gelu_grad_f(__uint_as_float(sv.y << 16));
+              v[3] *= gelu_grad_f(__uint_as_float(sv.y & 0xFFFF0000u));
+            }
+            u32x2_t w;
+            w.x = f2bf_pair(v[0], v[1]);
+            w.y = f2bf_pair(v[2], v[3]);
+            lds_write_b64(quad_at(j, vq), w);
+          }
+        flush_rows(rc, i);
       }
     }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v]), rc, off[i][j][v >> 2] + (v & 3) * row_step, 0, 0);
-    return;
+    BIGMAC_TRACE_AT(cur_id, 3);
+    BIGMAC_TRACE_AT(cur_id, 4);
+    if (id < 0) break;
+    cur = nxt;
   }
-  // bf16 results.  With the transposed accumulation lane l owns row l%32 of each 32-row sub-tile
-  // and, per accumulator quad, 4 consecutive columns: the epilogue math runs on the accumulators,
-  // quads are packed to 8 bytes and pass through an LDS strip private to the wave (32 rows x 64
-  // columns) to come out as whole rows: 16-byte stores, 128 contiguous bytes per row.
-  static_assert(WN == 64, "the strip holds 64-column wave tiles");
-  constexpr int SROW = 144;                                    // bytes per staged row (128 + 16 against conflicts)
-  constexpr int NWAVES = WAVES_M * WAVES_N;
-  constexpr int WPR = (NWAVES + NS - 1) / NS;                  // waves sharing one ring stage
-  static_assert(WPR * 32 * SROW <= (A_CHUNKS + B_CHUNKS) * 16, "staging strips do not fit a ring stage");
-  BIGMAC_WAIT_VMCNT(0);
-  __builtin_amdgcn_s_barrier();                                // all ring traffic is over
-  char* const strip = (char*)BIGMAC_RING(wave % NS) + (wave / NS) * (32 * SROW);
-  char* const quad_at = strip + (lane & 31) * SROW + (lane >> 5) * 8;   // + (j*32 + vq*8) * 2
-  char* const row_at = strip + (lane >> 3) * SROW + (lane & 7) * 16;    // + pass * 8 * SROW
-  const int out_col = t.n0 + wn + (lane & 7) * 8;
-  auto wave_sync = [&]() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  };
-  const __amdgpu_buffer_rsrc_t rc = rows_of(t.C, 2);
-  const __amdgpu_buffer_rsrc_t rx = rows_of(EPI == EPI_GELU && p.aux_out ? p.aux_out : t.C, 2);
-  const unsigned out_off = out_col < p.N ? (unsigned)(((size_t)(wm + (lane >> 3)) * p.ldc + out_col) * 2) : OUT_OF_RANGE;
-  const unsigned pass_step = (unsigned)(8 * p.ldc * 2);
-  auto flush_rows = [&](const __amdgpu_buffer_rsrc_t& dst, int i) {
-    uint4 v[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) v[q] = *(const uint4*)(row_at + q * 8 * SROW);
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v[q]), dst, out_off + (unsigned)(i * 4 + q) * pass_step, 0, 0);
-  };
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    if (EPI == EPI_GELU && p.aux_out) {   // the pre-activation itself, for the backward pass
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          uint2 w;
-          w.x = f2bf_pair(acc[i][j][vq * 4 + 0], acc[i][j][vq * 4 + 1]);
-          w.y = f2bf_pair(acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]);
-          *(uint2*)(quad_at + (j * 32 + vq * 8) * 2) = w;
-        }
-      wave_sync();
-      flush_rows(rx, i);
-      wave_sync();
-    }
-    if (EPI == EPI_DGELU) {               // saved pre-activation: rows in, quads out
-#pragma unroll
-      for (int q = 0; q < 4; ++q) *(uint4*)(row_at + q * 8 * SROW) = aux[i * 4 + q];
-      wave_sync();
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        float v[4];
-#pragma unroll
-        for (int vr = 0; vr < 4; ++vr) v[vr] = acc[i][j][vq * 4 + vr];
-        uint2* slot = (uint2*)(quad_at + (j * 32 + vq * 8) * 2);
-        if (EPI == EPI_GELU) {
-#pragma unroll
-          for (int vr = 0; vr < 4; ++vr) v[vr] = gelu_f(v[vr]);
-        } else if (EPI == EPI_DGELU) {
-          const uint2 sv = *slot;
-          v[0] *= gelu_grad_f(__uint_as_float(sv.x << 16));
-          v[1] *= gelu_grad_f(__uint_as_float(sv.x & 0xFFFF0000u));
-          v[2] *= gelu_grad_f(__uint_as_float(sv.y << 16));
-          v[3] *= gelu_grad_f(__uint_as_float(sv.y & 0xFFFF0000u));
-        }
-        uint2 w;
-        w.x = f2bf_pair(v[0], v[1]);
-        w.y = f2bf_pair(v[2], v[3]);
-        *slot = w;
-      }
-    wave_sync();
-    flush_rows(rc, i);
-    wave_sync();
-  }
-  BIGMAC_TRACE_POINT(3);
-  BIGMAC_WAIT_VMCNT(0);
-  BIGMAC_TRACE_POINT(4);
 }
 
 // ------------------------------------------------------------------------ fp32 kernel ------
@@ -473,8 +636,10 @@ __global__ __launch_bounds__(256) void fma_gemm_kernel(GemmDesc p) {
   constexpr int BM = 64, BN = 64, BK = 16;
   __shared__ float sa[BK][BM + 1];
   __shared__ float sb[BK][BN + 1];
-  TileCoord t = resolve_tile<BM, BN>(p, 4);
-  if (!t.valid) return;
+  const TileSpace ts = tile_space<BM, BN>(p);
+  const int id = tile_at(ts, (int)(blockIdx.x >> 3));
+  if (id < 0) return;
+  TileCoord t = resolve_tile<BM, BN>(p, ts, id, 4);
   const float* A = (const float*)p.A;
   const float* B = (const float*)t.B;
   const int tid = threadIdx.x, ty = tid / 16, tx = tid % 16;
@@ -600,20 +765,24 @@ int launch_reduce_partials(const float* part, int nslices, size_t n, float* out,
 
 namespace {
 
+// One-dimensional launch, a multiple of the 8 XCDs.  `persistent`: at most two workgroups per CU
+// (256 CUs), each walking several tiles; otherwise one workgroup per tile (surplus ones exit).
 template <int BM, int BN>
-dim3 grid_for(const GemmDesc& g) {  // one-dimensional, a multiple of the 8 XCDs; surplus blocks exit
+dim3 grid_for(const GemmDesc& g, bool persistent) {
   long gx = (g.N + BN - 1) / BN, gy, gz = 1;
   if (g.mode == GEMM_RAGGED_M) gy = g.max_rows / BM + g.groups + 1;
   else gy = (g.M + BM - 1) / BM;
   if (g.mode == GEMM_RAGGED_K) gz = g.groups;
   if (g.mode == GEMM_DENSE) gz = g.ksplit;
-  return dim3((unsigned)((gx * gy * gz + 7) / 8 * 8), 1, 1);
+  long blocks = (gx * gy * gz + 7) / 8 * 8;
+  if (persistent && blocks > 512) blocks = 512;
+  return dim3((unsigned)blocks, 1, 1);
 }
 
 template <bool AK, bool BKC>
 int launch_mfma(const GemmDesc& g, hipStream_t s) {
   constexpr int BM = BIGMAC_TILE_BM, BN = BIGMAC_TILE_BN, BK = BIGMAC_TILE_BK, WMs = BIGMAC_TILE_WM, WNs = BIGMAC_TILE_WN;
-  dim3 grid = grid_for<BM, BN>(g), block(64 * WMs * WNs);
+  dim3 grid = grid_for<BM, BN>(g, true), block(64 * WMs * WNs);
 #define BIGMAC_MFMA(EPI, OUTF32) \
   hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI, OUTF32>), grid, block, 0, s, g)
   switch (g.epilogue) {
@@ -633,7 +802,7 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
 
 template <bool AK, bool BKC>
 int launch_fma(const GemmDesc& g, hipStream_t s) {
-  dim3 grid = grid_for<64, 64>(g), block(256);
+  dim3 grid = grid_for<64, 64>(g, false), block(256);
   switch (g.epilogue) {
     case EPI_STORE: hipLaunchKernelGGL((fma_gemm_kernel<AK, BKC, EPI_STORE>), grid, block, 0, s, g); break;
     case EPI_GELU: hipLaunchKernelGGL((fma_gemm_kernel<AK, BKC, EPI_GELU>), grid, block, 0, s, g); break;
