@@ -111,7 +111,7 @@ struct GemmDesc {
   int groups;                // ragged modes: number of groups (experts)
   int max_rows;              // ragged-M: total rows (upper bound for the tile count)
   const int* offsets;        // device [groups+1]: row ranges (ragged-M) or k ranges (ragged-K)
-  const int* tile_map;       // device, ragged-M: [0] = number of tiles, then (group, first row) pairs
+  const int* tile_map;       // device, from launch_build_tile_map: ragged-M needs it; ragged-K takes its cost-balanced schedule from it (optional)
   long gstride_b;            // ragged-M: elements between the B matrices of consecutive groups
   long gstride_c;            // ragged-K / split-K: elements between consecutive C outputs
   int ksplit;                // dense: number of K slices (each writes C + z*gstride_c); 1 = none
@@ -122,7 +122,7 @@ int gemm_ragged_tile_rows(int dtype);
 int launch_gemm(const GemmDesc& g, hipStream_t s);
 // tile_map capacity in int32 for a ragged-M problem
 inline size_t tile_map_ints(int total_rows, int groups, int tile_rows) {
-  return 1 + 2 * ((size_t)total_rows / tile_rows + groups + 1);
+  return 16 + 2 * ((size_t)total_rows / tile_rows + groups + 1);
 }
 int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* tile_map, hipStream_t s);
 // out[i] = (beta ? out[i] : 0) + sum_z part[z*n + i]

@@ -48,6 +48,7 @@ struct TileCoord {
 // meet in one L2 instead of being fetched eight times.
 struct TileSpace {
   int gx, gy, total, per_xcd;
+  int first, last;   // this workgroup's XCD owns the logical tiles [first, last)
 };
 template <int BM, int BN>
 __device__ __forceinline__ TileSpace tile_space(const GemmDesc& p) {
@@ -57,13 +58,31 @@ __device__ __forceinline__ TileSpace tile_space(const GemmDesc& p) {
   const int gz = p.mode == GEMM_RAGGED_K ? p.groups : (p.mode == GEMM_DENSE ? p.ksplit : 1);
   ts.total = ts.gx * ts.gy * gz;
   ts.per_xcd = (ts.total + 7) >> 3;
+  ts.first = (int)(blockIdx.x & 7) * ts.per_xcd;
+  ts.last = min(ts.first + ts.per_xcd, ts.total);
   return ts;
 }
 // logical tile of position `pos` in this workgroup's XCD run, or -1
 __device__ __forceinline__ int tile_at(const TileSpace& ts, int pos) {
-  const int id = (int)(blockIdx.x & 7) * ts.per_xcd + pos;
-  return (pos < ts.per_xcd && id < ts.total) ? id : -1;
+  const int id = ts.first + pos;
+  return id < ts.last ? id : -1;
 }
+// Ragged-K problems (one output matrix per group, contraction over that group's rows): a tile of
+// a group with many rows costs many k tiles, one of a small group almost none, so equal tile
+// counts per XCD can leave one XCD with a multiple of the average work (skewed routing).  The
+// tile map therefore carries nine split points that cut the group sequence into eight runs of
+// equal cost (cost of a group = its k tiles + a constant for set-up and epilogue, see
+// build_tile_map_kernel), each as group * 65536 + 16-bit fraction of that group; every group has
+// the same number of tiles, so a split point turns into a tile index for any tile shape.
+constexpr int TILE_MAP_HEADER = 16;   // ints in front of the (group, first row) pairs: [0] tile count, [1..9] split points
+__device__ __forceinline__ void balance_ragged_k(const GemmDesc& p, TileSpace& ts) {
+  const int tiles_per_group = ts.gx * ts.gy;
+  const int x = (int)(blockIdx.x & 7);
+  const int a = p.tile_map[1 + x], b = p.tile_map[2 + x];
+  ts.first = (a >> 16) * tiles_per_group + (((a & 0xFFFF) * tiles_per_group) >> 16);
+  ts.last = (b >> 16) * tiles_per_group + (((b & 0xFFFF) * tiles_per_group) >> 16);
+}
+
 template <int BM, int BN>
 __device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, const TileSpace& ts, int id, int esz) {
   TileCoord t;
@@ -78,8 +97,8 @@ __device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, const TileS
   t.valid = true;
   t.n0 = bx * BN;
   if (p.mode == GEMM_RAGGED_M) {
-    int g = p.tile_map[1 + 2 * by];
-    t.m0 = p.tile_map[2 + 2 * by];
+    int g = p.tile_map[TILE_MAP_HEADER + 2 * by];
+    t.m0 = p.tile_map[TILE_MAP_HEADER + 1 + 2 * by];
     t.m_end = p.offsets[g + 1];
     t.kbeg = 0;
     t.kend = p.K;
@@ -306,7 +325,8 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
   mb.init(p.ldb);
   const int wrap_tiles = p.kwrap_b ? p.kwrap_b / BK : 0x7FFFFFFF;
 
-  const TileSpace ts = tile_space<BM, BN>(p);
+  TileSpace ts = tile_space<BM, BN>(p);
+  if (p.mode == GEMM_RAGGED_K && p.tile_map) balance_ragged_k(p, ts);
   // buffers of one tile (id < 0: no tile, empty ranges); ranges end at the last valid row so that
   // tails read as zeros
   auto operands = [&](int id) {
@@ -695,29 +715,76 @@ __global__ __launch_bounds__(256) void fma_gemm_kernel(GemmDesc p) {
 
 // ------------------------------------------------------------------------ helpers ----------
 
-// tile_map[0] = number of M tiles; then (group, first row) per tile, groups in order.
+// tile_map[0] = number of M tiles, [1..9] = the split points of the cost-balanced ragged-K
+// schedule (see balance_ragged_k), then from TILE_MAP_HEADER on (group, first row) per M tile,
+// groups in order.  One workgroup of 1024 threads, one thread per group.
 __global__ void build_tile_map_kernel(const int* __restrict__ offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
   __shared__ int scan[1024];
   const int g = threadIdx.x;
-  int beg = 0, cnt = 0;
+  int beg = 0, rows = 0, cnt = 0;
   if (g < groups) {
     beg = offsets[g];
-    cnt = (offsets[g + 1] - beg + tile_rows - 1) / tile_rows;
+    rows = offsets[g + 1] - beg;
+    cnt = (rows + tile_rows - 1) / tile_rows;
   }
-  scan[g] = cnt;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    int v = g >= off ? scan[g - off] : 0;
+  auto inclusive_scan = [&](int v) {
     __syncthreads();
-    scan[g] += v;
+    scan[g] = v;
     __syncthreads();
-  }
-  const int first = scan[g] - cnt;
+    for (int off = 1; off < 1024; off <<= 1) {
+      const int o = g >= off ? scan[g - off] : 0;
+      __syncthreads();
+      scan[g] += o;
+      __syncthreads();
+    }
+    return scan[g];
+  };
+  const int last_tile = inclusive_scan(cnt);
+  const int first = last_tile - cnt;
   for (int i = 0; i < cnt; ++i) {
-    tile_map[1 + 2 * (first + i)] = g;
-    tile_map[2 + 2 * (first + i)] = beg + i * tile_rows;
+    tile_map[TILE_MAP_HEADER + 2 * (first + i)] = g;
+    tile_map[TILE_MAP_HEADER + 1 + 2 * (first + i)] = beg + i * tile_rows;
   }
-  if (g == 1023) tile_map[0] = scan[1023];
+  if (g == 1023) tile_map[0] = last_tile;
+  // split points: cost of a group = its k tiles + 8 (set-up and epilogue of a tile, in k tiles)
+  __shared__ int cost_of[1024];
+  __shared__ int incl[1024];
+  __shared__ long long worst_run;
+  const int cost = g < groups ? (rows + BIGMAC_TILE_BK - 1) / BIGMAC_TILE_BK + 8 : 0;
+  const int upto = inclusive_scan(cost);
+  cost_of[g] = cost;
+  incl[g] = upto;
+  if (g == 0) worst_run = 0;
+  __syncthreads();
+  const long long total = incl[1023];
+  // cost in front of position q = group * 65536 + fraction
+  auto cost_before = [&](long long q) {
+    const int gi = (int)(q >> 16);
+    if (gi >= groups) return total;
+    return (long long)(incl[gi] - cost_of[gi]) + (((q & 0xFFFF) * cost_of[gi]) >> 16);
+  };
+  // Near-uniform routing: runs of equal tile counts are as good and keep whole groups together,
+  // and the workgroups of an XCD then get equal numbers of tiles.  Use the cost-balanced cut
+  // only where the equal cut would leave an XCD more than 1/8 over its share.
+  if (g < 8) {
+    const long long q0 = ((long long)groups * g << 16) / 8, q1 = ((long long)groups * (g + 1) << 16) / 8;
+    atomicMax((unsigned long long*)&worst_run, (unsigned long long)(cost_before(q1) - cost_before(q0)));
+  }
+  __syncthreads();
+  const bool balanced = worst_run * 64 > total * 9;
+#pragma unroll 1
+  for (int x = 0; x <= 8; ++x) {
+    if (!balanced) {
+      if (g == 0) tile_map[1 + x] = (int)(((long long)groups * x << 16) / 8);
+      continue;
+    }
+    const long long target = total * x / 8;
+    if (x == 8) {
+      if (g == 0) tile_map[1 + x] = groups << 16;
+    } else if (cost > 0 && target >= upto - cost && target < upto) {
+      tile_map[1 + x] = (g << 16) | (int)(((target - (upto - cost)) << 16) / cost);
+    }
+  }
 }
 
 __global__ void reduce_partials_kernel(const float* __restrict__ part, int nslices, size_t n, float* __restrict__ out, int beta) {
