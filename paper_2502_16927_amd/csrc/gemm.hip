@@ -719,7 +719,7 @@ __global__ __launch_bounds__(256) void fma_gemm_kernel(GemmDesc p) {
 // schedule (see balance_ragged_k), then from TILE_MAP_HEADER on (group, first row) per M tile,
 // groups in order.  One workgroup of 1024 threads, one thread per group.
 __global__ void build_tile_map_kernel(const int* __restrict__ offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
-  __shared__ int scan[1024];
+  __shared__ int scan[16];
   const int g = threadIdx.x;
   int beg = 0, rows = 0, cnt = 0;
   if (g < groups) {
@@ -727,17 +727,20 @@ __global__ void build_tile_map_kernel(const int* __restrict__ offsets, int group
     rows = offsets[g + 1] - beg;
     cnt = (rows + tile_rows - 1) / tile_rows;
   }
+  // inclusive scan over the 1024 threads: shuffles inside each wavefront, the 16 wavefront totals through LDS
   auto inclusive_scan = [&](int v) {
-    __syncthreads();
-    scan[g] = v;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-      const int o = g >= off ? scan[g - off] : 0;
-      __syncthreads();
-      scan[g] += o;
-      __syncthreads();
+    const int lane = g & 63, wave = g >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(v, d, 64);
+      if (lane >= d) v += o;
     }
-    return scan[g];
+    __syncthreads();
+    if (lane == 63) scan[wave] = v;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += scan[w];
+    return v + before;
   };
   const int last_tile = inclusive_scan(cnt);
   const int first = last_tile - cnt;

@@ -25,59 +25,95 @@ __global__ __launch_bounds__(256) void perm_count_kernel(const int32_t* __restri
   for (int e = threadIdx.x; e < N; e += 256) counts[(size_t)blockIdx.x * N + e] = cnt[e];
 }
 
-// in place: counts[c][e] -> first slot of expert e's pairs of chunk c;  offsets[e] = first slot of e.
-// One thread per expert; chunks are read 8 at a time so that the loads overlap.
-__global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ counts, int nchunks, int N, int32_t* __restrict__ offsets) {
-  __shared__ int scan[1024];
-  const int e = threadIdx.x;
-  int total = 0;
-  if (e < N)
-    for (int c0 = 0; c0 < nchunks; c0 += 8) {
-      int v[8];
+// Inclusive scan over the 1024 threads of a workgroup: shuffles inside each wavefront, the 16
+// wavefront totals through LDS.
+__device__ __forceinline__ int block_scan_1024(int v, int* wave_totals) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = c0 + u < nchunks ? counts[(size_t)(c0 + u) * N + e] : 0;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) total += v[u];
-    }
-  scan[e] = total;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    int v = e >= off ? scan[e - off] : 0;
-    __syncthreads();
-    scan[e] += v;
-    __syncthreads();
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
   }
-  if (e < N) {
-    int run = scan[e] - total;
-    offsets[e] = run;
-    for (int c0 = 0; c0 < nchunks; c0 += 8) {
+  __syncthreads();                 // wave_totals may still be read from a previous call
+  if (lane == 63) wave_totals[wave] = v;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += wave_totals[w];
+  return v + before;
+}
+
+// in place: counts[c][e] -> first slot of expert e's pairs of chunk c;  offsets[e] = first slot of e.
+// The 1024 threads are G groups x NP experts (NP = N rounded up to a power of two, G = 1024 / NP);
+// group g owns a contiguous range of chunks, so all chunk rows are read by many threads at once.
+__global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ counts, int nchunks, int N, int NP, int32_t* __restrict__ offsets) {
+  __shared__ int part[1024];        // [g][e]: pairs of expert e in the chunks of group g
+  __shared__ int wave_totals[16];
+  const int G = 1024 / NP;
+  const int e = threadIdx.x % NP, g = threadIdx.x / NP;
+  const int per = (nchunks + G - 1) / G;
+  const int c_beg = min(g * per, nchunks), c_end = min(c_beg + per, nchunks);
+  int mine = 0;
+  if (e < N)
+    for (int c0 = c_beg; c0 < c_end; c0 += 8) {
       int v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = c0 + u < nchunks ? counts[(size_t)(c0 + u) * N + e] : 0;
+      for (int u = 0; u < 8; ++u) v[u] = c0 + u < c_end ? counts[(size_t)(c0 + u) * N + e] : 0;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) mine += v[u];
+    }
+  part[g * NP + e] = mine;
+  __syncthreads();
+  int total = 0, before_me = 0;      // expert e: all pairs, and those in the groups in front of g
+  for (int h = 0; h < G; ++h) {
+    const int v = part[h * NP + e];
+    total += v;
+    if (h < g) before_me += v;
+  }
+  // exclusive scan over the experts (threads of group 0 carry the totals, the others zero)
+  const int incl = block_scan_1024(g == 0 && e < N ? total : 0, wave_totals);
+  __syncthreads();
+  if (g == 0) part[e] = incl - total;   // first slot of expert e (part[0 .. NP) is free to reuse: every thread has read it)
+  __syncthreads();
+  if (e < N) {
+    int run = part[e] + before_me;
+    if (g == 0) offsets[e] = part[e];
+    if (g == 0 && e == N - 1) offsets[N] = part[e] + total;
+    for (int c0 = c_beg; c0 < c_end; c0 += 8) {
+      int v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = c0 + u < c_end ? counts[(size_t)(c0 + u) * N + e] : 0;
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        if (c0 + u < nchunks) counts[(size_t)(c0 + u) * N + e] = run;
+        if (c0 + u < c_end) counts[(size_t)(c0 + u) * N + e] = run;
         run += v[u];
       }
     }
-    if (e == N - 1) offsets[N] = run;
   }
 }
 
-// One wavefront per chunk walks its pairs in flat order, 64 at a time.  A pair's slot is the
-// running first-free slot of its expert plus the number of earlier lanes with the same expert.
+// One wavefront per chunk walks its pairs in flat order, 64 at a time (all read up front).  A
+// pair's slot is the running first-free slot of its expert plus the number of earlier lanes with
+// the same expert.
 __global__ __launch_bounds__(64) void perm_rank_kernel(const int32_t* __restrict__ idx, int Tk, int N, int nbits,
                                                        const int32_t* __restrict__ base, int32_t* __restrict__ slot_of,
                                                        int32_t* __restrict__ src_of) {
   extern __shared__ int run[];
   const int lane = threadIdx.x;
+  constexpr int ROUNDS = P_CHUNK / 64;
+  int mine[ROUNDS];
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int f = blockIdx.x * P_CHUNK + r * 64 + lane;
+    mine[r] = f < Tk ? idx[f] : -1;
+  }
   for (int e = lane; e < N; e += 64) run[e] = base[(size_t)blockIdx.x * N + e];
   __syncthreads();
   const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-  for (int i = 0; i < P_CHUNK; i += 64) {
-    const int f = blockIdx.x * P_CHUNK + i + lane;
-    const bool live = f < Tk;
-    const int e = live ? idx[f] : 0;
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int f = blockIdx.x * P_CHUNK + r * 64 + lane;
+    const bool live = mine[r] >= 0;
+    const int e = live ? mine[r] : 0;
     unsigned long long same = __ballot(live);
     for (int b = 0; b < nbits; ++b) {
       const unsigned long long bal = __ballot((e >> b) & 1);
@@ -199,7 +235,9 @@ int launch_build_permutation(int T, int k, int N, const int32_t* topk_idx, int32
   int32_t* counts = (int32_t*)ws;
   hipLaunchKernelGGL(perm_count_kernel, dim3(nchunks), dim3(256), N * sizeof(int), s, topk_idx, Tk, N, counts);
   BIGMAC_CHECK_LAUNCH();
-  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, counts, nchunks, N, expert_offsets);
+  int NP = 1;
+  while (NP < N) NP <<= 1;
+  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, counts, nchunks, N, NP, expert_offsets);
   BIGMAC_CHECK_LAUNCH();
   hipLaunchKernelGGL(perm_rank_kernel, dim3(nchunks), dim3(64), N * sizeof(int), s, topk_idx, Tk, N, nbits, counts, slot_of, src_of);
   BIGMAC_CHECK_LAUNCH();
