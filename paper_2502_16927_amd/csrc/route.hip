@@ -209,8 +209,11 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
   }
 }
 
-// One wavefront per token: k rounds of arg-max over the remaining logits (ties to the lowest
-// index), then the softmax over the k picked logits.  PER = logits held per lane.
+// One wavefront per token.  Every lane ranks its logits against all N by broadcast (rank = how
+// many logits come first: greater, or equal with a lower index, which is the order k rounds of
+// arg-max with ties to the lowest index would pick them in); ranks below k are the selection, in
+// pick order.  Then the softmax over the k picked logits, summed in pick order.  PER = logits
+// held per lane.
 template <int PER>
 __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict__ logits, int T, int N, int k,
                                                         int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
@@ -218,31 +221,36 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict_
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
   float v[PER];
-  bool taken[PER];
+  int rank[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
     const int n = i * 64 + lane;
     v[i] = n < N ? logits[(size_t)t * N + n] : -INFINITY;
-    taken[i] = n >= N;
+    rank[i] = 0;
   }
+#pragma unroll
+  for (int io = 0; io < PER; ++io) {
+    const int live = min(64, N - io * 64);        // lanes of this register that hold a logit
+    for (int l = 0; l < live; ++l) {
+      const float o = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v[io]), l));
+      const int on = io * 64 + l;
+#pragma unroll
+      for (int i = 0; i < PER; ++i) rank[i] += (o > v[i] || (o == v[i] && on < i * 64 + lane)) ? 1 : 0;
+    }
+  }
+  // lane j < k collects the j-th pick: its index and logit
   float selv = 0.0f;
   int seli = 0;
   for (int j = 0; j < k; ++j) {
-    float bv = -INFINITY;
-    int bi = 0x7FFFFFFF;
 #pragma unroll
-    for (int i = 0; i < PER; ++i)
-      if (!taken[i] && (bi == 0x7FFFFFFF || v[i] > bv)) { bv = v[i]; bi = i * 64 + lane; }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      const float ov = __shfl_xor(bv, off, 64);
-      const int oi = __shfl_xor(bi, off, 64);
-      if (oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+    for (int i = 0; i < PER; ++i) {
+      const unsigned long long hit = __ballot(rank[i] == j && i * 64 + lane < N);
+      if (hit) {                                  // wave-uniform: exactly one (i, lane) has rank j
+        const int src = __ffsll((long long)hit) - 1;
+        const float pv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v[i]), src));
+        if (lane == j) { selv = pv; seli = i * 64 + src; }
+      }
     }
-#pragma unroll
-    for (int i = 0; i < PER; ++i)
-      if (bi == i * 64 + lane) taken[i] = true;
-    if (lane == j) { selv = bv; seli = bi; }
   }
   const float m = __shfl(selv, 0, 64);
   const float e = lane < k ? expf(selv - m) : 0.0f;
