@@ -274,6 +274,7 @@ struct TileOperands {
   __amdgpu_buffer_rsrc_t ra, rb;
   unsigned step_a, step_b;   // byte advance per k tile
   int nk;                    // k tiles
+  int wrap_first;            // with a wrapped B: k tile index (within the wrap period) of this tile's first k tile
 };
 
 // Persistent kernel: a workgroup walks the tiles of its XCD run (stride = workgroups per XCD).
@@ -335,6 +336,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
     const TileCoord& t = o.t;
     const int klen = t.kend - t.kbeg;
     o.nk = (klen + BK - 1) / BK;
+    o.wrap_first = p.kwrap_b ? (t.kbeg / BK) % (p.kwrap_b / BK) : 0;
     const bf16_t* A = (const bf16_t*)p.A;
     if (AK) {
       const int rows = min(t.m_end - t.m0, BM);
@@ -368,7 +370,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
   auto fetch = [&](const TileOperands& o, int tile, uint4* dst) {
     const bool live = tile < o.nk;
     const unsigned off_a = live ? (unsigned)tile * o.step_a : OUT_OF_RANGE;
-    const unsigned off_b = live ? (unsigned)(tile % wrap_tiles) * o.step_b : OUT_OF_RANGE;
+    const unsigned off_b = live ? (unsigned)((tile + o.wrap_first) % wrap_tiles) * o.step_b : OUT_OF_RANGE;
     ma.load(o.ra, dst, off_a);
     mb.load(o.rb, dst + A_CHUNKS, off_b);
   };
@@ -823,6 +825,26 @@ int gemm_ragged_tile_rows(int dtype) { return dtype == BIGMAC_BF16 ? BIGMAC_TILE
 int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* tile_map, hipStream_t s) {
   if (groups > 1024) return BIGMAC_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(build_tile_map_kernel, dim3(1), dim3(1024), 0, s, offsets, groups, tile_rows, tile_map);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+// out[i] = bf16(sum_z part[z*n + i]), slices summed in ascending order; n a multiple of 8
+__global__ void reduce_partials_bf16_kernel(const float* __restrict__ part, int nslices, size_t n, bf16_t* __restrict__ out) {
+  const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (i >= n) return;
+  float acc[8] = {};
+  for (int z = 0; z < nslices; ++z) {
+    const float4 a = *(const float4*)(part + (size_t)z * n + i), b = *(const float4*)(part + (size_t)z * n + i + 4);
+    acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+    acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
+  }
+  *(uint4*)(out + i) = pack_bf16x8(acc);
+}
+
+int launch_reduce_partials_bf16(const float* part, int nslices, size_t n, void* out, hipStream_t s) {
+  if (n % 8) return BIGMAC_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(reduce_partials_bf16_kernel, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, s, part, nslices, n, (bf16_t*)out);
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }

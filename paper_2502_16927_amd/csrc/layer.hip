@@ -48,7 +48,7 @@ struct SavedPlan {
   size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, x_perm, act, hact, o_perm, y_low, total;
 };
 struct FwdPlan {
-  size_t logits, perm, x_low, total;
+  size_t logits, perm, x_low, partials, total;
 };
 struct BwdPlan {
   size_t dy_low, dgate, do_perm, dact, dx_low, dL, route, dx_f32, partials, tmp_f32, total;
@@ -86,12 +86,32 @@ SavedPlan plan_saved(const bigmac_dims& D) {
   return p;
 }
 
+// Split of K for a dense forward product [M,K] x [K,N] with few output tiles and a long K (the
+// shared projections at decode sizes: a handful of tiles would otherwise walk K alone on a
+// handful of CUs).  fp32 partials, reduced in slice order.  1 = no split.
+int forward_ksplit(const bigmac_dims& D, int M, int N, int K) {
+  if (!bf(D)) return 1;
+  const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
+  if (tiles >= 128 && K <= 2048) return 1;
+  int ks = K / 256;
+  if (ks > 512 / tiles) ks = 512 / tiles;
+  if (ks > 32) ks = 32;
+  return ks < 1 ? 1 : ks;
+}
+size_t forward_partials_bytes(const bigmac_dims& D) {
+  if (D.order != BIGMAC_ORDER_DCCA) return 0;
+  const int ka = forward_ksplit(D, D.T, D.r, D.d), kb = forward_ksplit(D, D.T, D.d, low_ld(D));
+  const size_t a = ka > 1 ? (size_t)ka * D.T * D.r * 4 : 0, b = kb > 1 ? (size_t)kb * D.T * D.d * 4 : 0;
+  return a > b ? a : b;
+}
+
 FwdPlan plan_fwd(const bigmac_dims& D) {
   Carver c;
   FwdPlan p;
   p.logits = c.take((size_t)D.T * D.N * 4);
   p.perm = c.take(permutation_ws_bytes(D.T, D.k, D.N));
   p.x_low = c.take(D.order == BIGMAC_ORDER_DCCA ? (size_t)D.T * D.r * esize(D.dtype) : 0);
+  p.partials = c.take(forward_partials_bytes(D));
   p.total = c.off;
   return p;
 }
@@ -373,7 +393,15 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     g.B = P->w_down; g.ldb = D->r; g.N = D->r;
     g.C = wsb + F.x_low; g.ldc = D->r;
     BIGMAC_STAGE(BIGMAC_STAGE_DESCEND);
-    rc = launch_gemm(g, s);
+    g.ksplit = forward_ksplit(*D, D->T, D->r, D->d);
+    if (g.ksplit > 1) {   // fp32 partials, then one rounding to bf16
+      g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->r;
+      rc = launch_gemm(g, s);
+      if (rc) return rc;
+      rc = launch_reduce_partials_bf16((const float*)(wsb + F.partials), g.ksplit, (size_t)D->T * D->r, wsb + F.x_low, s);
+    } else {
+      rc = launch_gemm(g, s);
+    }
     if (rc) return rc;
     x_low = wsb + F.x_low;
   }
@@ -407,7 +435,16 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     g.B = P->w_up; g.ldb = D->d; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
     g.C = y; g.ldc = D->d;
     BIGMAC_STAGE(BIGMAC_STAGE_ASCEND);
-    rc = launch_gemm(g, s);
+    g.ksplit = forward_ksplit(*D, D->T, D->d, low_ld(*D));
+    if (g.ksplit > 1) {
+      g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->d;
+      rc = launch_gemm(g, s);
+      if (rc) return rc;
+      if (out_bf16) rc = launch_reduce_partials_bf16((const float*)(wsb + F.partials), g.ksplit, (size_t)D->T * D->d, y, s);
+      else rc = launch_reduce_partials((const float*)(wsb + F.partials), g.ksplit, (size_t)D->T * D->d, (float*)y, 0, s);
+    } else {
+      rc = launch_gemm(g, s);
+    }
   }
   return rc;
 }
