@@ -102,23 +102,26 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const XT* __restrict
 // while the current step's 512 fused multiply-adds per lane run.  Token rows past T and router
 // rows past d lie outside the buffer ranges and arrive as zeros; they are never used anyway.
 #define BIGMAC_ROUTER_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
-template <typename XT>
+// TB = tokens per wavefront (8 for large T; 1 or 2 when T is small, so that the few tokens still
+// spread over many CUs).  The summation order does not depend on it.
+template <typename XT, int TB>
 __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* __restrict__ x, const float* __restrict__ wg,
                                                                       const float* __restrict__ bias, float* __restrict__ logits,
                                                                       int T, int d, int N) {
   constexpr int XROW = 256 * sizeof(XT) / 16;       // 16-byte chunks per token row of a tile
-  constexpr int XCH = 32 * XROW;                    // chunks of a token tile
+  constexpr int TOKENS = 4 * TB;                    // tokens per workgroup
+  constexpr int XCH = TOKENS * XROW;                // chunks of a token tile
   constexpr int WCH = 256 * 4;                      // chunks of a router tile (256 rows x 16 floats)
-  constexpr int XL = XCH / 256, WL = WCH / 256;     // loads per thread
-  __shared__ uint4 xs0[XCH];
-  __shared__ uint4 xs1[XCH];
+  constexpr int XL = (XCH + 255) / 256, WL = WCH / 256;   // loads per thread
+  __shared__ uint4 xs0[XL * 256];                   // (a tile of fewer than 256 chunks is padded: the surplus lanes load out of range)
+  __shared__ uint4 xs1[XL * 256];
   __shared__ uint4 ws0[WCH];
   __shared__ uint4 ws1[WCH];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int tb = blockIdx.x * 32, t0 = tb + wave * R_TB;
+  const int tb = blockIdx.x * TOKENS, t0 = tb + wave * TB;
   const int n0 = blockIdx.y * R_NB;
   const int nq = d / 64, ntiles = (nq + 3) / 4;
-  const int rows = min(32, T - tb), cols = min(R_NB, N - n0);
+  const int rows = min(TOKENS, T - tb), cols = min(R_NB, N - n0);
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)(x + (size_t)tb * d), 0, (int)((size_t)rows * d * sizeof(XT)), 0x00020000);
   const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)(wg + n0), 0, (int)(((size_t)(d - 1) * N + cols) * 4), 0x00020000);
   const int wave_chunk = __builtin_amdgcn_readfirstlane((int)(threadIdx.x & ~63u));
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
 #pragma unroll
   for (int i = 0; i < XL; ++i) {
     const int q = i * 256 + threadIdx.x;
-    xoff[i] = (unsigned)((q / XROW) * d * sizeof(XT) + (q % XROW) * 16);
+    xoff[i] = q < XCH ? (unsigned)((q / XROW) * d * sizeof(XT) + (q % XROW) * 16) : 0x80000000u;
   }
 #pragma unroll
   for (int i = 0; i < WL; ++i) {   // LDS position q holds column chunk (q & 3) ^ ((row >> 1) & 3) of row q >> 2
@@ -147,17 +150,18 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
     (void)tile; (void)xs; (void)ws;
 #endif
   };
-  float acc[R_TB * R_NB];
+  constexpr int ACCS = TB * R_NB;
+  float acc[ACCS];
 #pragma unroll
-  for (int v = 0; v < R_TB * R_NB; ++v) acc[v] = 0.0f;
+  for (int v = 0; v < ACCS; ++v) acc[v] = 0.0f;
   auto compute = [&](int tile, const uint4* xs, const uint4* ws) {
-    const XT* xt = (const XT*)xs + (wave * R_TB) * 256 + lane;
+    const XT* xt = (const XT*)xs + (wave * TB) * 256 + lane;
 #pragma unroll
     for (int qq = 0; qq < 4; ++qq) {
       if (tile * 4 + qq >= nq) break;
-      float xv[R_TB];
+      float xv[TB];
 #pragma unroll
-      for (int i = 0; i < R_TB; ++i) xv[i] = Elem<XT>::load(xt + i * 256 + qq * 64);
+      for (int i = 0; i < TB; ++i) xv[i] = Elem<XT>::load(xt + i * 256 + qq * 64);
       const int row = qq * 64 + lane;
       float wv[R_NB];
 #pragma unroll
@@ -167,7 +171,7 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
         wv[c4 * 4 + 2] = __uint_as_float(w.z); wv[c4 * 4 + 3] = __uint_as_float(w.w);
       }
 #pragma unroll
-      for (int i = 0; i < R_TB; ++i)
+      for (int i = 0; i < TB; ++i)
 #pragma unroll
         for (int c = 0; c < R_NB; ++c) acc[i * R_NB + c] = fmaf(xv[i], wv[c], acc[i * R_NB + c]);
     }
@@ -186,25 +190,41 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
     compute(tile + 1, xs1, ws1);
     __builtin_amdgcn_s_barrier();
   }
-  // halving tree as a reduce-scatter (see router_logits_kernel)
+  // Halving tree (lane l with lane l ^ off, off = 32 .. 1).  While a lane still holds two or more
+  // sums the step is a reduce-scatter: each half of the pair keeps one half of the sums (see
+  // router_logits_kernel); once a lane is down to one sum, both lanes of a pair add the other's
+  // (the same addition, a + b, in both).  The sum of accumulator v ends on the lanes whose top
+  // bits spell v.
+  constexpr int SCATTER_STEPS = ACCS >= 64 ? 6 : (ACCS == 32 ? 5 : 4);
+  static_assert(ACCS == 128 || ACCS == 32 || ACCS == 16, "1, 2 or 8 tokens per wavefront");
 #pragma unroll
-  for (int off = 32, half = R_TB * R_NB / 2; off >= 1; off >>= 1, half >>= 1) {
-    const bool hi = (lane & off) != 0;
+  for (int step = 0; step < 6; ++step) {
+    const int off = 32 >> step;
+    if (step < SCATTER_STEPS) {
+      const int half = ACCS >> (step + 1);
+      const bool hi = (lane & off) != 0;
 #pragma unroll
-    for (int v = 0; v < half; ++v) {
-      const float send = hi ? acc[v] : acc[v + half];
-      const float keep = hi ? acc[v + half] : acc[v];
-      acc[v] = keep + __shfl_xor(send, off, 64);
+      for (int v = 0; v < half; ++v) {
+        const float send = hi ? acc[v] : acc[v + half];
+        const float keep = hi ? acc[v + half] : acc[v];
+        acc[v] = keep + __shfl_xor(send, off, 64);
+      }
+    } else {
+      acc[0] = acc[0] + __shfl_xor(acc[0], off, 64);
     }
   }
+  constexpr int LEFT = ACCS >> SCATTER_STEPS;          // sums per lane at the end: 2 (ACCS = 128) or 1
+  constexpr int SHARE = 6 - SCATTER_STEPS;             // low lane bits that hold copies of the same sum
+  if ((lane & ((1 << SHARE) - 1)) == 0) {
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int v = 2 * lane + u;
-    const int t = t0 + v / R_NB, n = n0 + v % R_NB;
-    if (t < T && n < N) {
-      float val = acc[u];
-      if (bias) val = val + bias[n];
-      logits[(size_t)t * N + n] = val;
+    for (int u = 0; u < LEFT; ++u) {
+      const int v = LEFT * (lane >> SHARE) + u;
+      const int t = t0 + v / R_NB, n = n0 + v % R_NB;
+      if (t < T && n < N) {
+        float val = acc[u];
+        if (bias) val = val + bias[n];
+        logits[(size_t)t * N + n] = val;
+      }
     }
   }
 }
@@ -321,15 +341,32 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __res
 }  // namespace
 
 int launch_router_logits(const bigmac_dims& D, const void* x, const float* w_gate, const float* bias, float* logits, hipStream_t s) {
-  const dim3 grid((D.T + 31) / 32, (D.N + R_NB - 1) / R_NB), block(256);
   const bool pipelined = D.N % 4 == 0 && (size_t)D.d * D.N * 4 < (1ull << 31);   // 16-byte router rows, 32-bit buffer range
-  if (D.dtype == BIGMAC_BF16) {
-    if (pipelined) hipLaunchKernelGGL(router_logits_pipelined_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
-    else hipLaunchKernelGGL(router_logits_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
-  } else {
-    if (pipelined) hipLaunchKernelGGL(router_logits_pipelined_kernel<float>, grid, block, 0, s, (const float*)x, w_gate, bias, logits, D.T, D.d, D.N);
+  const dim3 block(256);
+  const unsigned gy = (unsigned)((D.N + R_NB - 1) / R_NB);
+  if (!pipelined) {
+    const dim3 grid((D.T + 31) / 32, gy);
+    if (D.dtype == BIGMAC_BF16) hipLaunchKernelGGL(router_logits_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)x, w_gate, bias, logits, D.T, D.d, D.N);
     else hipLaunchKernelGGL(router_logits_kernel<float>, grid, block, 0, s, (const float*)x, w_gate, bias, logits, D.T, D.d, D.N);
+    BIGMAC_CHECK_LAUNCH();
+    return BIGMAC_OK;
   }
+  // tokens per wavefront: 8 unless that leaves most CUs without a workgroup
+  const long groups8 = (long)((D.T + 31) / 32) * gy;
+  const int tb = groups8 >= 1024 ? 8 : (groups8 * 4 >= 512 ? 2 : 1);
+#define BIGMAC_ROUTER(XT, TBV)                                                                                       \
+  hipLaunchKernelGGL((router_logits_pipelined_kernel<XT, TBV>), dim3((D.T + 4 * TBV - 1) / (4 * TBV), gy), block, 0, s, \
+                     (const XT*)x, w_gate, bias, logits, D.T, D.d, D.N)
+  if (D.dtype == BIGMAC_BF16) {
+    if (tb == 8) BIGMAC_ROUTER(bf16_t, 8);
+    else if (tb == 2) BIGMAC_ROUTER(bf16_t, 2);
+    else BIGMAC_ROUTER(bf16_t, 1);
+  } else {
+    if (tb == 8) BIGMAC_ROUTER(float, 8);
+    else if (tb == 2) BIGMAC_ROUTER(float, 2);
+    else BIGMAC_ROUTER(float, 1);
+  }
+#undef BIGMAC_ROUTER
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }
