@@ -127,6 +127,14 @@ inline size_t tile_map_ints(int total_rows, int groups, int tile_rows) {
 int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* tile_map, hipStream_t s);
 // out[i] = (beta ? out[i] : 0) + sum_z part[z*n + i]
 int launch_reduce_partials(const float* part, int nslices, size_t n, float* out, int beta, hipStream_t s);
+// the same for up to 3 independent reductions in one launch
+struct ReduceJob {
+  const float* part;
+  float* out;
+  size_t n;
+  int nslices;
+};
+int launch_reduce_partials_multi(const ReduceJob* jobs, int count, int beta, hipStream_t s);
 // out[i] = bf16(sum_z part[z*n + i]); n a multiple of 8
 int launch_reduce_partials_bf16(const float* part, int nslices, size_t n, void* out, hipStream_t s);
 

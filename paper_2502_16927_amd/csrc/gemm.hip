@@ -792,9 +792,9 @@ __global__ void build_tile_map_kernel(const int* __restrict__ offsets, int group
   }
 }
 
-__global__ void reduce_partials_kernel(const float* __restrict__ part, int nslices, size_t n, float* __restrict__ out, int beta) {
-  // one float4 of the output per thread; slices are summed in ascending order, eight loads in flight
-  const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+// out[i .. i+4) = (beta ? out : 0) + sum_z part[z*n + i ..]: one float4 of the output per thread;
+// slices are summed in ascending order, eight loads in flight
+__device__ __forceinline__ void reduce_slices(const float* __restrict__ part, int nslices, size_t n, float* __restrict__ out, int beta, size_t i) {
   if (i >= n) return;
   if ((n & 3) == 0) {   // then every slice keeps the 16-byte alignment
     float4 s = beta ? *(const float4*)(out + i) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -818,6 +818,16 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, int nslic
       out[e] = s;
     }
   }
+}
+__global__ void reduce_partials_kernel(const float* __restrict__ part, int nslices, size_t n, float* __restrict__ out, int beta) {
+  reduce_slices(part, nslices, n, out, beta, ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4);
+}
+struct ReduceJobs {
+  ReduceJob job[3];
+};
+__global__ void reduce_partials_multi_kernel(ReduceJobs jobs, int beta) {
+  const ReduceJob j = jobs.job[blockIdx.y];
+  reduce_slices(j.part, j.nslices, j.n, j.out, beta, ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4);
 }
 
 int gemm_ragged_tile_rows(int dtype) { return dtype == BIGMAC_BF16 ? BIGMAC_TILE_BM : 64; }
@@ -851,6 +861,19 @@ int launch_reduce_partials_bf16(const float* part, int nslices, size_t n, void* 
 
 int launch_reduce_partials(const float* part, int nslices, size_t n, float* out, int beta, hipStream_t s) {
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, part, nslices, n, out, beta);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+int launch_reduce_partials_multi(const ReduceJob* jobs, int count, int beta, hipStream_t s) {
+  if (count < 1 || count > 3) return BIGMAC_ERR_INVALID_ARG;
+  ReduceJobs all = {};
+  size_t longest = 0;
+  for (int i = 0; i < count; ++i) {
+    all.job[i] = jobs[i];
+    if (jobs[i].n > longest) longest = jobs[i].n;
+  }
+  hipLaunchKernelGGL(reduce_partials_multi_kernel, dim3((unsigned)((longest + 1023) / 1024), count), dim3(256), 0, s, all, beta);
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }

@@ -51,7 +51,7 @@ struct FwdPlan {
   size_t logits, perm, x_low, partials, total;
 };
 struct BwdPlan {
-  size_t dy_low, dgate, do_perm, dact, dx_low, dL, route, dx_f32, partials, tmp_f32, total;
+  size_t dy_low, dgate, do_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, total;
 };
 
 inline bool bf(const bigmac_dims& D) { return D.dtype == BIGMAC_BF16; }
@@ -138,14 +138,11 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
   p.dL = c.take((size_t)D.T * D.N * es);
   p.route = c.take(route_backward_ws_bytes(D));
   p.dx_f32 = c.take((bf(D) && (D.flags & BIGMAC_FLAG_OUT_BF16)) ? (size_t)D.T * D.d * 4 : 0);
-  size_t part = (size_t)choose_ksplit(D.d, D.N, D.T) * D.d * D.N;
-  if (dcca) {
-    const size_t a = (size_t)choose_ksplit(D.r, D.d, D.T) * D.r * D.d;
-    const size_t b = (size_t)choose_ksplit(D.d, D.r, D.T) * D.d * D.r;
-    part = part > a ? part : a;
-    part = part > b ? part : b;
-  }
-  p.partials = c.take(part * 4);
+  // split-K partials of the three weight gradients over the token index: one region each, so
+  // that one launch at the end can reduce all three
+  p.part_gate = c.take((size_t)choose_ksplit(D.d, D.N, D.T) * D.d * D.N * 4);
+  p.part_up = c.take(dcca ? (size_t)choose_ksplit(D.r, D.d, D.T) * D.r * D.d * 4 : 0);
+  p.part_down = c.take(dcca ? (size_t)choose_ksplit(D.d, D.r, D.T) * D.d * D.r * 4 : 0);
   p.tmp_f32 = 0;
   p.total = c.off;
   return p;
@@ -209,18 +206,18 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   return launch_gemm(g, s);
 }
 
-// dense fp32 C (+)= A^T-style product over the token index, split over K and reduced in a fixed order
+// dense fp32 C (+)= A^T-style product over the token index, split over K into fp32 partials; the
+// reduction (fixed slice order) is left to the caller as a job for launch_reduce_partials_multi
 int run_token_wgrad(const bigmac_dims& D, const void* A, long lda, int M, const void* B, long ldb, int N,
-                    float* out, float* partials, hipStream_t s) {
+                    float* out, float* partials, ReduceJob* job, hipStream_t s) {
   GemmDesc g = base_desc(D);
   g.a_kcontig = 0; g.b_kcontig = 0;
   g.epilogue = EPI_ACCUM; g.beta = 0;
   g.A = A; g.lda = lda; g.M = M; g.B = B; g.ldb = ldb; g.N = N; g.K = D.T;
   g.ksplit = choose_ksplit(M, N, D.T);
   g.C = partials; g.ldc = N; g.gstride_c = (long)M * N;
-  int rc = launch_gemm(g, s);
-  if (rc) return rc;
-  return launch_reduce_partials(partials, g.ksplit, (size_t)M * N, out, (D.flags & BIGMAC_FLAG_ACCUMULATE) ? 1 : 0, s);
+  job->part = partials; job->out = out; job->n = (size_t)M * N; job->nslices = g.ksplit;
+  return launch_gemm(g, s);
 }
 
 }  // namespace
@@ -483,7 +480,8 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   void* dx_perm = do_perm;  // do_perm is dead once the second expert matrix's gradients are done
   void* dx_low = wsb + B.dx_low;
   void* dL = wsb + B.dL;
-  float* partials = (float*)(wsb + B.partials);
+  ReduceJob jobs[3];
+  int njobs = 0;
   const bool out_bf16 = bf(*D) && (D->flags & BIGMAC_FLAG_OUT_BF16);
   float* dx_f32 = out_bf16 ? (float*)(wsb + B.dx_f32) : (float*)dx;
   const int accumulate = (D->flags & BIGMAC_FLAG_ACCUMULATE) ? 1 : 0;
@@ -504,7 +502,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     if (rc) return rc;
     // dW_up (+)= y'^T dy
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_ASCEND_WGRAD);
-    rc = run_token_wgrad(*D, y_low, low_ld(*D), D->r, dy, D->d, D->d, d_w_up, partials, s);
+    rc = run_token_wgrad(*D, y_low, low_ld(*D), D->r, dy, D->d, D->d, d_w_up, (float*)(wsb + B.part_up), &jobs[njobs++], s);
     if (rc) return rc;
   } else {
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_ASCEND_DGRAD);
@@ -575,29 +573,32 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   if (rc) return rc;
   {  // dW_g (+)= x^T dL
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_ROUTER_WGRAD);
-    rc = run_token_wgrad(*D, x, D->d, D->d, dL, D->N, D->N, d_w_gate, partials, s);
+    rc = run_token_wgrad(*D, x, D->d, D->d, dL, D->N, D->N, d_w_gate, (float*)(wsb + B.part_gate), &jobs[njobs++], s);
   }
   if (rc) return rc;
   if (dcca) {
-    // dW_down (+)= x^T dx'
-    {
-      BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_WGRAD);
-      rc = run_token_wgrad(*D, x, D->d, D->d, dx_low, low_ld(*D), D->r, d_w_down, partials, s);
+    {  // dx += dx' W_down^T
+      GemmDesc g = base_desc(*D);
+      g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ACCUM; g.beta = 1;
+      g.A = dx_low; g.lda = low_ld(*D); g.M = D->T; g.K = low_ld(*D);
+      g.B = P->w_down; g.ldb = D->r; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
+      g.C = dx_f32; g.ldc = D->d;
+      BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_DGRAD);
+      rc = launch_gemm(g, s);
+      if (rc) return rc;
     }
+    // dW_down (+)= x^T dx', and the reduction of all three token-index weight gradients
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_WGRAD);
+    rc = run_token_wgrad(*D, x, D->d, D->d, dx_low, low_ld(*D), D->r, d_w_down, (float*)(wsb + B.part_down), &jobs[njobs++], s);
     if (rc) return rc;
-    // dx += dx' W_down^T
-    GemmDesc g = base_desc(*D);
-    g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ACCUM; g.beta = 1;
-    g.A = dx_low; g.lda = low_ld(*D); g.M = D->T; g.K = low_ld(*D);
-    g.B = P->w_down; g.ldb = D->r; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
-    g.C = dx_f32; g.ldc = D->d;
-    BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_DGRAD);
-    rc = launch_gemm(g, s);
+    rc = launch_reduce_partials_multi(jobs, njobs, (D->flags & BIGMAC_FLAG_ACCUMULATE) ? 1 : 0, s);
     if (rc) return rc;
   } else {
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_OUTPUT_CAST);
     hipLaunchKernelGGL(add_f32_kernel, grid1d(Td), dim3(256), 0, s, dx_f32, (const float*)dx_low, Td);
     BIGMAC_CHECK_LAUNCH();
+    rc = launch_reduce_partials_multi(jobs, njobs, (D->flags & BIGMAC_FLAG_ACCUMULATE) ? 1 : 0, s);
+    if (rc) return rc;
   }
   if (out_bf16) {
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_OUTPUT_CAST);
