@@ -135,7 +135,9 @@ def main():
     from paper_2502_16927_amd import binding as B
     from paper_2502_16927_amd import synth
 
-    wl = synth.WORKLOADS[args.workload]
+    wl = synth.WORKLOADS.get(args.workload) or synth.NEXT_WORKLOADS[args.workload]
+    if args.workload in synth.NEXT_WORKLOADS:
+        args.order = "cdac"   # the vanilla layer is a CDAC-order layer with a wide hidden dimension
     if args.tokens:
         wl = wl.with_T(args.tokens)
     cdac = args.order == "cdac"

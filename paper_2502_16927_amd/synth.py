@@ -49,6 +49,14 @@ WORKLOADS = {
     "zipf_stress": Workload("zipf_stress", T=32768, d=4096, r=1024, N=128, k=8, h=2048,
                             dtype=BF16, x_std=1.0, backward=True, zipf_s=1.2, index=4),
 }
+# A further structure built from the same kernels: the vanilla MoE layer (Fig. 2a: few experts,
+# each a full-width d -> 4d -> d FFN, top-2, no shared projections).  It runs in the CDAC order
+# with the expert hidden width in `r` (and h = d, so that the expert matrices can be drawn as
+# the swapped BigMac ones).
+NEXT_WORKLOADS = {
+    "vanilla_moe": Workload("vanilla_moe", T=8192, d=1024, r=4096, N=8, k=2, h=1024, dtype=BF16,
+                            x_std=1.0, backward=True, index=5),
+}
 DECODE_T_SWEEP = (32, 128, 512, 2048)
 W_STD = 0.02
 BASE_SEED = 1234  # the seed the paper's pre-training setup lists (Table 5)

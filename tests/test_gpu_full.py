@@ -138,6 +138,33 @@ def test_gpt_medium_fine_grained_same_parameters(oracle):
     assert B.permute_bytes(B.dims_of(wl)) / B.permute_bytes(B.dims_of(wl, B.ORDER_CDAC)) == wl.r / wl.d == 0.25
 
 
+def test_vanilla_moe_structure(oracle):
+    """The vanilla MoE layer (Fig. 2a: 8 full-width experts d -> 4d -> d, top-2) from the same
+    kernels: CDAC order with the hidden width 4d."""
+    wl = synth.NEXT_WORKLOADS["vanilla_moe"]
+    data = add_cdac_weights(synth.generate(wl))
+    layer = DeviceLayer(wl, data, order=B.ORDER_CDAC)
+    y = layer.forward(training=True)
+    torch.cuda.synchronize()
+    idx = routing_in_full(oracle, layer, data)
+    sel = sample_tokens(wl.T, 128, 1)
+    ref_y = oracle.cdac_forward(data["x"], data["w_gate"], None, data["cdac_w1"], data["cdac_w2"], wl.k, sel=sel)
+    err = np.abs(host(y)[sel] - ref_y).max() / np.sqrt(np.mean(ref_y ** 2))
+    print(f"vanilla_moe: forward max-abs/rms = {err:.4f}", flush=True)
+    assert err < TOL
+    sel2 = sample_tokens(wl.T, 1024, 3)
+    dy = np.zeros_like(data["dy"])
+    dy[sel2] = data["dy"][sel2]
+    layer.dy = B.to_device(dy, wl.dtype)
+    layer.alloc_grads()
+    layer.backward()
+    torch.cuda.synchronize()
+    ref = oracle.cdac_backward(data["x"], data["dy"], data["w_gate"], None, data["cdac_w1"], data["cdac_w2"], wl.k, sel=sel2)
+    check_dx(host(layer.dx)[sel2], ref["dx"][sel2])
+    grads = {n: host(layer.grads[n]) for n in ("d_w_gate", "d_w1", "d_w2")}
+    print(check_weight_grads(grads, ref, np.bincount(idx[sel2].ravel(), minlength=wl.N), len(sel2), TOL, dcca=False, scale=1.5), flush=True)
+
+
 def test_gpt_xl_accumulating_gradients(oracle):
     run_training_workload(oracle, "gpt_xl", n_fwd=256, n_sel=4096, experts_dense=lambda c: [int(np.argmin(c)), int(np.argmax(c))],
                           flags=B.FLAG_ACCUMULATE)
