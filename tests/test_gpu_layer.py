@@ -22,6 +22,7 @@ SMALL = [
     dict(T=257, d=192, r=64, N=24, k=8, h=192, dtype=B.BF16, zipf_s=1.2),
     dict(T=64, d=64, r=64, N=8, k=8, h=64, dtype=B.BF16),
     dict(T=1, d=64, r=64, N=8, k=1, h=64, dtype=B.BF16),
+    dict(T=200, d=768, r=256, N=8, k=2, h=128, dtype=B.BF16),   # few tiles, long K: the shared projections split K
     dict(T=130, d=128, r=64, N=8, k=3, h=192, dtype=B.F32, x_std=0.5),
 ]
 
