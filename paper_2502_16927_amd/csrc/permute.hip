@@ -219,6 +219,55 @@ __global__ __launch_bounds__(256) void combine_backward_kernel(const float* __re
   }
 }
 
+// The same for bf16 rows and k <= 16: the token's dy' row is read once (column chunk outermost,
+// the k destinations inside), 16-byte accesses of 8 columns per lane.
+__global__ __launch_bounds__(256) void combine_backward_bf16_kernel(const float* __restrict__ dy_low, const bf16_t* __restrict__ o_perm,
+                                                                    const int32_t* __restrict__ slot_of, const float* __restrict__ w,
+                                                                    float* __restrict__ dgate, bf16_t* __restrict__ do_perm, int T, int k, int width) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  // lane j holds destination j
+  const int my_slot = lane < k ? slot_of[(size_t)t * k + lane] : 0;
+  const float my_w = lane < k ? w[(size_t)t * k + lane] : 0.0f;
+  float dot[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) dot[j] = 0.0f;
+  for (int c0 = 0; c0 < width; c0 += 512) {       // uniform trip count: the shuffles below need every lane
+    const int c = c0 + lane * 8;
+    const bool live = c < width;
+    float g[8] = {};
+    if (live) {
+      const float4 g0 = *(const float4*)(dy_low + (size_t)t * width + c), g1 = *(const float4*)(dy_low + (size_t)t * width + c + 4);
+      g[0] = g0.x; g[1] = g0.y; g[2] = g0.z; g[3] = g0.w; g[4] = g1.x; g[5] = g1.y; g[6] = g1.z; g[7] = g1.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (j >= k) break;
+      const size_t row = (size_t)__shfl(my_slot, j, 64) * width + c;
+      const float wj = __shfl(my_w, j, 64);
+      if (live) {
+        float o[8], q[8];
+        unpack_bf16x8(*(const uint4*)(o_perm + row), o);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          dot[j] = fmaf(g[i], o[i], dot[j]);
+          q[i] = wj * g[i];
+        }
+        *(uint4*)(do_perm + row) = pack_bf16x8(q);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    if (j >= k) break;
+    float d = dot[j];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) d += __shfl_xor(d, off, 64);
+    if (lane == 0) dgate[(size_t)t * k + j] = d;
+  }
+}
+
 }  // namespace
 
 size_t permutation_ws_bytes(int T, int k, int N) {
@@ -276,7 +325,10 @@ int launch_combine_rows(int dtype, int T, int k, int width, const void* o_perm, 
 int launch_combine_backward(int dtype, int T, int k, int width, const float* dy_low, const void* o_perm,
                             const int32_t* slot_of, const float* topk_w, float* dgate, void* do_perm, hipStream_t s) {
   const dim3 grid((T + 3) / 4), block(256);
-  if (dtype == BIGMAC_BF16)
+  if (dtype == BIGMAC_BF16 && k <= 16 && width % 8 == 0 && width >= 512)   // narrower rows would leave lanes idle
+    hipLaunchKernelGGL(combine_backward_bf16_kernel, grid, block, 0, s, dy_low, (const bf16_t*)o_perm, slot_of, topk_w, dgate,
+                       (bf16_t*)do_perm, T, k, width);
+  else if (dtype == BIGMAC_BF16)
     hipLaunchKernelGGL(combine_backward_kernel<bf16_t>, grid, block, 0, s, dy_low, (const bf16_t*)o_perm, slot_of, topk_w, dgate,
                        (bf16_t*)do_perm, T, k, width);
   else
