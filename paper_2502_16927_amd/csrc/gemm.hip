@@ -22,8 +22,10 @@
 #define BIGMAC_TRACE_AT(tile, i)
 #endif
 #ifndef BIGMAC_TILE_STAGES
-#define BIGMAC_TILE_STAGES 4     // LDS ring stages: STAGES - 1 k tiles of global loads in flight per block
+#define BIGMAC_TILE_STAGES 3     // LDS ring stages: STAGES - 1 k tiles of global loads in flight per block
 #endif
+// Workgroups resident per CU: what the ring's LDS (16 KB a stage) leaves room for, out of 160 KB.
+#define BIGMAC_BLOCKS_PER_CU (BIGMAC_TILE_STAGES <= 3 ? 3 : 2)
 
 namespace bigmac {
 
@@ -286,7 +288,8 @@ struct TileOperands {
 // instructions in flight behind any load is then a compile-time constant, which is what the
 // counter waits below and the compiler's own ones are derived from.
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32>
-__global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDesc p) {
+__global__ __launch_bounds__(64 * WAVES_M* WAVES_N) __attribute__((amdgpu_waves_per_eu(BIGMAC_BLOCKS_PER_CU)))
+void mfma_gemm_kernel(GemmDesc p) {
   constexpr int THREADS = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -413,10 +416,16 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
   // Output rows as buffers: the range ends with the last valid row, so rows of the next group
   // (or past M) fall outside it and their stores are dropped and their loads read as zero
   // without a branch; columns at or beyond N get an offset that is out of range by itself.
+  // (Tile coordinates are the same in every lane; saying so keeps the descriptor in scalar
+  // registers where the compiler has lost track of it: a descriptor in vector registers costs
+  // a loop over its distinct values around every access.)
   auto rows_of = [&](const TileCoord& t, const void* base, int esz_out) {
     const int c_rows = min(t.m_end - t.m0, BM);
-    return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)base + (size_t)t.m0 * p.ldc * esz_out), 0,
-                                             c_rows > 0 ? (int)(((size_t)(c_rows - 1) * p.ldc + p.N) * esz_out) : 0, 0x00020000);
+    const size_t first = (size_t)base + (size_t)t.m0 * p.ldc * esz_out;
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)first);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(first >> 32));
+    const int bytes = __builtin_amdgcn_readfirstlane(c_rows > 0 ? (int)(((size_t)(c_rows - 1) * p.ldc + p.N) * esz_out) : 0);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(((size_t)hi << 32) | lo), 0, bytes, 0x00020000);
   };
   // EPI_DGELU multiplies by act'(saved pre-activation): that tile is requested one tile ahead
   // (row layout: 8 lanes per 64-column row, 8 rows per pass) and used in the epilogue
@@ -426,12 +435,15 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
     if (EPI == EPI_DGELU) {
       const __amdgpu_buffer_rsrc_t ra = rows_of(t, p.aux_in, 2);
       const int col = t.n0 + wn + (lane & 7) * 8;
+      // columns past N get the out-of-range bit by arithmetic: written as a selection, the
+      // compiler turns it into two guarded loads per access, and waits between them
+      const unsigned past_n = ((unsigned)(p.N - 1 - col) >> 31) * OUT_OF_RANGE;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int row = wm + i * 32 + q * 8 + (lane >> 3);
-          const unsigned off = col < p.N ? (unsigned)(((size_t)row * p.ldc + col) * 2) : OUT_OF_RANGE;
+          const unsigned off = (unsigned)(((size_t)row * p.ldc + col) * 2) | past_n;
           aux[i * 4 + q] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, NON_TEMPORAL));
         }
     }
@@ -572,7 +584,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
 #pragma unroll
           for (int vq = 0; vq < 4; ++vq) {
             const int row = wm + i * 32 + vq * 8 + (lane >> 5) * 4;
-            off[vq] = col < p.N ? (unsigned)(((size_t)row * p.ldc + col) * 4) : OUT_OF_RANGE;
+            off[vq] = (unsigned)(((size_t)row * p.ldc + col) * 4) | ((unsigned)(p.N - 1 - col) >> 31) * OUT_OF_RANGE;
           }
           if (EPI == EPI_ACCUM && p.beta) {
             float old[16];
@@ -594,7 +606,7 @@ __global__ __launch_bounds__(64 * WAVES_M* WAVES_N) void mfma_gemm_kernel(GemmDe
       const int out_col = t.n0 + wn + (lane & 7) * 8;
       const __amdgpu_buffer_rsrc_t rc = rows_of(t, t.C, 2);
       const __amdgpu_buffer_rsrc_t rx = rows_of(t, EPI == EPI_GELU && p.aux_out ? p.aux_out : t.C, 2);
-      const unsigned out_off = out_col < p.N ? (unsigned)(((size_t)(wm + (lane >> 3)) * p.ldc + out_col) * 2) : OUT_OF_RANGE;
+      const unsigned out_off = (unsigned)(((size_t)(wm + (lane >> 3)) * p.ldc + out_col) * 2) | ((unsigned)(p.N - 1 - out_col) >> 31) * OUT_OF_RANGE;
       const unsigned pass_step = (unsigned)(8 * p.ldc * 2);
       auto flush_rows = [&](const __amdgpu_buffer_rsrc_t& dst, int i) {
         u32x4_t v[4];
@@ -890,7 +902,7 @@ dim3 grid_for(const GemmDesc& g, bool persistent) {
   if (g.mode == GEMM_RAGGED_K) gz = g.groups;
   if (g.mode == GEMM_DENSE) gz = g.ksplit;
   long blocks = (gx * gy * gz + 7) / 8 * 8;
-  if (persistent && blocks > 512) blocks = 512;
+  if (persistent && blocks > 256 * BIGMAC_BLOCKS_PER_CU) blocks = 256 * BIGMAC_BLOCKS_PER_CU;
   return dim3((unsigned)blocks, 1, 1);
 }
 
