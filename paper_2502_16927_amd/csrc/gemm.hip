@@ -368,8 +368,8 @@ void mfma_gemm_kernel(GemmDesc p) {
     }
     return o;
   };
-  // k tile `tile` of tile `o` -> one ring stage.  k tiles past the end are still requested, out of
-  // range (zeros, no memory traffic): the number of loads in flight stays constant.
+  // k tile `tile` of tile `o` -> one ring stage.  (The prefetch requests k tiles past the end of a
+  // very short K too, out of range: zeros, no memory traffic.)
   auto fetch = [&](const TileOperands& o, int tile, uint4* dst) {
     const bool live = tile < o.nk;
     const unsigned off_a = live ? (unsigned)tile * o.step_a : OUT_OF_RANGE;
@@ -482,10 +482,15 @@ void mfma_gemm_kernel(GemmDesc p) {
         constexpr int s = decltype(stage)::value;
         const int it = it0 + s;
         if (it >= nk) return;
-        BIGMAC_WAIT_VMCNT(RING_AHEAD);                   // this wave's part of k tile `it` has landed ...
+        // This wave's part of k tile `it` has landed once only the k tiles requested after it are
+        // in flight: NS - 2 of them, fewer over the last steps (nothing is requested past the end).
+        const int younger = min(NS - 2, max(nk, NS - 1) - 1 - it);
+        if (younger == NS - 2) BIGMAC_WAIT_VMCNT(RING_AHEAD);
+        else if (NS > 3 && younger > 0) BIGMAC_WAIT_VMCNT(LOADS_PER_TILE);
+        else BIGMAC_WAIT_VMCNT(0);
         __builtin_amdgcn_s_barrier();                    // ... and so has everyone's; stage (s - 1) is free
         if (it == 0) BIGMAC_TRACE_AT(cur_id, 1);
-        fetch(cur, it + NS - 1, ring + ((s + NS - 1) % NS) * STAGE_CHUNKS);
+        if (it + NS - 1 < nk) fetch(cur, it + NS - 1, ring + ((s + NS - 1) % NS) * STAGE_CHUNKS);
         // all fragments of the k tile are requested at once; the products of k step 0 start as
         // soon as its fragments are there, while those of the later steps are still arriving
         Frag<AK> fa[KS][TM];
@@ -528,13 +533,11 @@ void mfma_gemm_kernel(GemmDesc p) {
     }
     BIGMAC_TRACE_AT(cur_id, 2);
 
-    // Every wave has left the k loop: the ring is free.  What is still in flight are the k tiles
-    // past the end (zeros), some of them into the last stage, which the bf16 epilogue uses as
-    // its staging strips: let them land first.
+    // Once every wave has left the k loop the ring is free, and nothing is in flight into its
+    // last stage (the last k step waited for everything that was requested into it).
     pos += stride;
     id = tile_at(ts, pos);
     const TileOperands nxt = operands(id);
-    if (SWAP) BIGMAC_WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
     // bf16 epilogue staging, in the ring's last stage: the prefetch below fills stages
     // 0 .. NS - 2, and the last stage is requested again only behind the first barrier of the next
