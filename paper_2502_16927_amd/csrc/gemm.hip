@@ -34,6 +34,13 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
+// The schedule tables (tile map, group offsets) are written before the kernel starts and only
+// read by it.  Read through the constant address space they come in by scalar loads, one per
+// workgroup; as plain global reads the compiler, which cannot rule out that the kernel's own
+// stores change them, would issue vector loads and wait on the vector-memory counter for them.
+typedef const int __attribute__((address_space(4))) * table_ptr_t;
+__device__ __forceinline__ int table_at(const int* table, int i) { return ((table_ptr_t)(unsigned long long)table)[i]; }
+
 struct TileCoord {
   int m0, n0;        // first row / column of the C tile (absolute)
   int m_end;         // rows of A and C at or beyond this are not touched
@@ -56,7 +63,7 @@ template <int BM, int BN>
 __device__ __forceinline__ TileSpace tile_space(const GemmDesc& p) {
   TileSpace ts;
   ts.gx = (p.N + BN - 1) / BN;
-  ts.gy = p.mode == GEMM_RAGGED_M ? p.tile_map[0] : (p.M + BM - 1) / BM;
+  ts.gy = p.mode == GEMM_RAGGED_M ? table_at(p.tile_map, 0) : (p.M + BM - 1) / BM;
   const int gz = p.mode == GEMM_RAGGED_K ? p.groups : (p.mode == GEMM_DENSE ? p.ksplit : 1);
   ts.total = ts.gx * ts.gy * gz;
   ts.per_xcd = (ts.total + 7) >> 3;
@@ -80,7 +87,7 @@ constexpr int TILE_MAP_HEADER = 16;   // ints in front of the (group, first row)
 __device__ __forceinline__ void balance_ragged_k(const GemmDesc& p, TileSpace& ts) {
   const int tiles_per_group = ts.gx * ts.gy;
   const int x = (int)(blockIdx.x & 7);
-  const int a = p.tile_map[1 + x], b = p.tile_map[2 + x];
+  const int a = table_at(p.tile_map, 1 + x), b = table_at(p.tile_map, 2 + x);
   ts.first = (a >> 16) * tiles_per_group + (((a & 0xFFFF) * tiles_per_group) >> 16);
   ts.last = (b >> 16) * tiles_per_group + (((b & 0xFFFF) * tiles_per_group) >> 16);
 }
@@ -99,17 +106,17 @@ __device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, const TileS
   t.valid = true;
   t.n0 = bx * BN;
   if (p.mode == GEMM_RAGGED_M) {
-    int g = p.tile_map[TILE_MAP_HEADER + 2 * by];
-    t.m0 = p.tile_map[TILE_MAP_HEADER + 1 + 2 * by];
-    t.m_end = p.offsets[g + 1];
+    int g = table_at(p.tile_map, TILE_MAP_HEADER + 2 * by);
+    t.m0 = table_at(p.tile_map, TILE_MAP_HEADER + 1 + 2 * by);
+    t.m_end = table_at(p.offsets, g + 1);
     t.kbeg = 0;
     t.kend = p.K;
     t.B = (const char*)p.B + (size_t)g * p.gstride_b * esz;
   } else if (p.mode == GEMM_RAGGED_K) {
     t.m0 = by * BM;
     t.m_end = p.M;
-    t.kbeg = p.offsets[bz];
-    t.kend = p.offsets[bz + 1];
+    t.kbeg = table_at(p.offsets, bz);
+    t.kend = table_at(p.offsets, bz + 1);
     t.C = (char*)p.C + (size_t)bz * p.gstride_c * sizeof(float);
   } else {
     t.m0 = by * BM;
@@ -438,14 +445,14 @@ void mfma_gemm_kernel(GemmDesc p) {
       // columns past N get the out-of-range bit by arithmetic: written as a selection, the
       // compiler turns it into two guarded loads per access, and waits between them
       const unsigned past_n = ((unsigned)(p.N - 1 - col) >> 31) * OUT_OF_RANGE;
+      // One offset register, the passes 8 rows apart added per load: the empty statement keeps
+      // the compiler from carrying all the per-pass offsets across tiles in registers of their own.
+      unsigned first = (unsigned)(((size_t)(wm + (lane >> 3)) * p.ldc + col) * 2) | past_n;
+      asm volatile("" : "+v"(first));
+      const unsigned pass_step = (unsigned)(8 * p.ldc * 2);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int row = wm + i * 32 + q * 8 + (lane >> 3);
-          const unsigned off = (unsigned)(((size_t)row * p.ldc + col) * 2) | past_n;
-          aux[i * 4 + q] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, NON_TEMPORAL));
-        }
+      for (int c = 0; c < TM * 4; ++c)
+        aux[c] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(ra, first + (unsigned)c * pass_step, 0, NON_TEMPORAL));
     }
   };
   // While k tile `it` is awaited, the NS - 2 k tiles requested after it may stay in flight.  (At
