@@ -114,6 +114,10 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 512 MiB device copy three times: the kernel of known size that the "
                          "HBM counters (FETCH_SIZE, WRITE_SIZE) of a rocprofv3 --pmc run are scaled by")
+    ap.add_argument("--capacity-factor", type=float, default=0.0,
+                    help="fixed expert capacity ceil(f T k / N) instead of dropless routing (the paper's training runs: 1.2)")
+    ap.add_argument("--aux-alpha", type=float, default=0.0,
+                    help="coefficient of the load-balance loss (the paper's training runs: 0.001); 0 = off")
     ap.add_argument("--no-graph", action="store_true",
                     help="time eager launches instead of replays of the step captured in a HIP graph")
     args = ap.parse_args()
@@ -145,7 +149,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     data = synth.generate(wl)
-    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA)
+    capacity = B.expert_capacity(wl.T, wl.k, wl.N, args.capacity_factor) if args.capacity_factor > 0 else 0
+    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA, capacity=capacity, aux_alpha=args.aux_alpha)
+    variant = capacity > 0 or args.aux_alpha > 0      # not the headline configuration
     x = B.to_device(data["x"], wl.dtype, dev)
     dy = B.to_device(data.get("dy"), wl.dtype, dev)
     wg = B.to_device(data["w_gate"], B.F32, dev)
@@ -220,11 +226,11 @@ def main():
             for s, ms in tb.elapsed_ms(set(live)).items():
                 stage_ms[names[s]] = stage_ms.get(names[s], 0.0) + ms / args.steps
     roofline = None
-    if stage_ms:
+    if stage_ms and not capacity:   # with dropped rows the algorithmic work is not the closed form below
         dom = max(stage_ms, key=stage_ms.get)
         kind, flops, nbytes = work[dom]
         roofline = roofline_of(dom, kind, flops, nbytes, stage_ms[dom] * 1e-3)
-        if not args.tokens:
+        if not args.tokens and not variant:
             roofline["traffic"] = MEASURED_TRAFFIC.get((wl.name, args.order), {}).get(dom)
     fwd_flops = B.forward_matrix_flops(dims)
     out = {
@@ -241,7 +247,9 @@ def main():
         "dtype": "bf16" if wl.dtype == B.BF16 else "f32",
         "data": "synthetic",
         "config": {"workload": wl.name, "order": args.order, "T": wl.T, "d": wl.d, "r": wl.r, "N": wl.N, "k": wl.k,
-                   "h": wl.h, "pass": "fwd+bwd" if training else "fwd"},
+                   "h": wl.h, "pass": "fwd+bwd" if training else "fwd",
+                   **({"capacity_factor": args.capacity_factor, "capacity": capacity} if capacity else {}),
+                   **({"aux_alpha": args.aux_alpha} if args.aux_alpha > 0 else {})},
         "timed": timed,
         "eager_ms_per_step": eager_elapsed / args.steps * 1e3,
         "roofline": roofline,
@@ -250,7 +258,7 @@ def main():
         "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
         "stage_sum_ms": round(sum(stage_ms.values()), 4),
     }
-    if args.cpu_sample > 0 and not cdac:
+    if args.cpu_sample > 0 and not cdac and not variant:
         out["cpu_baseline"] = cpu_baseline(wl, data, args.cpu_sample, training)
     else:
         out["cpu_baseline"] = None

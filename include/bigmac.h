@@ -27,8 +27,15 @@
  *    failing step: BIGMAC_ERR_INVALID_ARG (NULL required pointer, bad dimension or enum),
  *    BIGMAC_ERR_WORKSPACE (workspace too small), BIGMAC_ERR_UNSUPPORTED, BIGMAC_ERR_HIP (a
  *    launch failed).  Inputs are assumed finite; NaN/Inf logits give unspecified routing.
- *  - Routing is dropless (Section 3.3): every (token, choice) pair keeps a row, the rows of an
- *    expert are contiguous and ordered by token, expert_offsets[N] = T*k.
+ *  - Routing is dropless (Section 3.3) unless dims.capacity > 0: every (token, choice) pair
+ *    keeps a row, the rows of an expert are contiguous and ordered by token,
+ *    expert_offsets[N] = T*k.
+ *  - Fixed expert capacity (the setting of the paper's training runs, Table 5: capacity factor
+ *    f = 1.2, i.e. capacity = ceil(f T k / N); the paper gives no rule, this is the usual one):
+ *    with dims.capacity = C > 0 an expert keeps the first C of its pairs in flat order
+ *    f = t*k + j and drops the rest.  A dropped pair has slot_of = -1, no row, and contributes
+ *    nothing to y (its gate value is not redistributed) nor to any gradient;
+ *    expert_offsets[N] = number of kept pairs <= T*k, and rows at or beyond it are not touched.
  */
 #ifndef BIGMAC_H
 #define BIGMAC_H
@@ -61,6 +68,8 @@ typedef struct {
   int32_t T, d, r, N, k, h; /* tokens, model width, low width, experts, top_k, expert hidden width */
   int32_t dtype, act, order;
   int32_t flags;
+  int32_t capacity;         /* 0: dropless.  C > 0: at most C pairs per expert (see above)         */
+  float aux_alpha;          /* 0: none.  > 0: coefficient of the load-balance loss (bigmac_aux_loss) */
 } bigmac_dims;
 
 typedef struct {          /* parameters: caller-owned, never written                              */
@@ -78,7 +87,8 @@ typedef enum {
   BIGMAC_WS_GROUPED_FFN = 2,
   BIGMAC_WS_LAYER_FORWARD = 3,   /* inference (saved == NULL)                                      */
   BIGMAC_WS_LAYER_TRAIN = 4,     /* forward with a saved block, and backward                       */
-  BIGMAC_WS_SAVED = 5            /* size of the saved-activation block of a training forward       */
+  BIGMAC_WS_SAVED = 5,           /* size of the saved-activation block of a training forward       */
+  BIGMAC_WS_AUX_LOSS = 6
 } bigmac_ws_kind;
 
 /* Host only, touches no GPU.  Bytes of workspace the given call needs for these dims
@@ -103,6 +113,20 @@ double bigmac_permute_bytes(const bigmac_dims *dims);
 int bigmac_route(const bigmac_dims *dims, const void *x /*[T,d] dtype*/, const float *w_gate,
                  const float *gate_bias, int32_t *topk_idx /*[T,k]*/, float *topk_w /*[T,k]*/,
                  float *logits_out, void *ws, size_t ws_bytes, void *stream);
+
+/* Load-balance auxiliary loss.  The paper trains with "aux_loss" balancing at coefficient 0.001
+ * (Table 5) and gives no formula; this is the common one, stated here as this library's choice:
+ *     loss = aux_alpha * N * sum_e f_e * P_e
+ * f_e = share of the T*k (token, choice) pairs routed to expert e, counted before any capacity
+ * drop; P_e = mean over the T tokens of softmax(logits[t, :])[e] over all N experts.  fp32; the
+ * sums run in a fixed order, so equal inputs give equal bits.  Outputs: loss [1], share [N] (the
+ * f_e) and, unless NULL, dlogits [T, N]: the gradient with f held fixed,
+ *     dlogits[t, n] = aux_alpha * N / T * p[t, n] * (f_n - sum_e f_e p[t, e]).
+ * With dims.aux_alpha > 0 bigmac_layer_forward (training form) evaluates the loss into the saved
+ * block (bigmac_saved_aux_layout) and bigmac_layer_backward adds this gradient, scaled by an
+ * upstream gradient of 1, to the router logits' gradient: it reaches d_w_gate and dx. */
+int bigmac_aux_loss(const bigmac_dims *dims, const float *logits /*[T,N]*/, const int32_t *topk_idx /*[T,k]*/,
+                    float *loss, float *share, float *dlogits, void *ws, size_t ws_bytes, void *stream);
 
 /* First All-to-All of Section 3.1 on one device.  Builds the stable counting-sort permutation
  * of the flat pairs f = t*k + j by expert (expert_offsets [N+1], slot_of [T,k], src_of [T*k]
@@ -145,6 +169,10 @@ int bigmac_layer_backward(const bigmac_dims *dims, const bigmac_params *params, 
  * [T,k] fp32, expert_offsets [N+1] int32 and slot_of [T,k] int32 inside it.  Host only. */
 int bigmac_saved_layout(const bigmac_dims *dims, size_t *off_topk_idx, size_t *off_topk_w,
                         size_t *off_expert_offsets, size_t *off_slot_of);
+
+/* With dims.aux_alpha > 0: byte offsets inside a saved block of the loss (one float) and of the
+ * pair shares f_e ([N] floats) that the training forward wrote.  Host only. */
+int bigmac_saved_aux_layout(const bigmac_dims *dims, size_t *off_aux_loss, size_t *off_aux_share);
 
 /* Profiling aid for callers that cannot allocate or want per-kernel times (benchmarks).  The
  * layer calls launch one kernel per stage below (a stage that a configuration skips records

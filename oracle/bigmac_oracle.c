@@ -108,16 +108,29 @@ void oracle_topk_gate(int T, int N, int k, const float *logits, int32_t *idx, do
 
 /* The dispatch permutation: the flat (token, choice) pairs f = t*k + j, stably sorted by expert.
  * src_of[s] = f at sorted position s; slot_of[f] = s; offsets[e] = first slot of expert e,
- * offsets[N] = T*k (dropless: every pair keeps a slot). */
-void oracle_permutation(int T, int k, int N, const int32_t *idx, int32_t *offsets,
-                        int32_t *slot_of, int32_t *src_of)
+ * offsets[N] = T*k (dropless, Section 3.3: every pair keeps a slot).
+ * capacity > 0 is the fixed expert capacity of the paper's training set-up (Table 5 names a
+ * capacity factor; the rule itself is the usual one, not the paper's): an expert keeps the first
+ * `capacity` of its pairs in flat order, the others get slot_of = -1 and no slot, and
+ * offsets[N] = number of kept pairs.  keep ([T*k], may be NULL) receives 1 / 0 per pair. */
+void oracle_permutation(int T, int k, int N, int capacity, const int32_t *idx, int32_t *offsets,
+                        int32_t *slot_of, int32_t *src_of, int32_t *keep)
 {
     int64_t Tk = (int64_t)T * k;
     int32_t s = 0;
     for (int e = 0; e < N; ++e) {          /* a stable sort by expert, written as N passes */
+        int32_t held = 0;
         offsets[e] = s;
-        for (int64_t f = 0; f < Tk; ++f)
-            if (idx[f] == e) { src_of[s] = (int32_t)f; slot_of[f] = s; ++s; }
+        for (int64_t f = 0; f < Tk; ++f) {
+            if (idx[f] != e) continue;
+            if (capacity > 0 && held >= capacity) {
+                slot_of[f] = -1;
+                if (keep) keep[f] = 0;
+                continue;
+            }
+            src_of[s] = (int32_t)f; slot_of[f] = s; ++s; ++held;
+            if (keep) keep[f] = 1;
+        }
     }
     offsets[N] = s;
 }
@@ -166,9 +179,11 @@ void oracle_dispatch(int T, int k, int width, const float *x_low, const int32_t 
                      float *x_perm)
 {
     for (int t = 0; t < T; ++t)
-        for (int j = 0; j < k; ++j)
+        for (int j = 0; j < k; ++j) {
+            if (slot_of[(size_t)t * k + j] < 0) continue;                 /* dropped pair: no row */
             memcpy(x_perm + (size_t)slot_of[(size_t)t * k + j] * width,
                    x_low + (size_t)t * width, sizeof(float) * (size_t)width);
+        }
 }
 
 /* The expert of Eq. 4 (or Eq. 3 with the widths swapped) applied to permuted rows: rows
@@ -203,6 +218,7 @@ void oracle_combine(int T, int k, int width, const double *o_perm, const int32_t
         for (int c = 0; c < width; ++c) y[c] = 0.0;
         for (int j = 0; j < k; ++j) {
             double g = gate ? gate[(size_t)t * k + j] : 1.0;
+            if (slot_of[(size_t)t * k + j] < 0) continue;                 /* dropped pair */
             const double *o = o_perm + (size_t)slot_of[(size_t)t * k + j] * width;
             for (int c = 0; c < width; ++c) y[c] += g * o[c];
         }
@@ -213,11 +229,13 @@ void oracle_combine(int T, int k, int width, const double *o_perm, const int32_t
 
 /* BigMac layer forward, Eq. 2 with the expert of Eq. 4, token by token, no permutation.
  * sel == NULL: all T tokens (nsel = T); otherwise only tokens sel[0..nsel) are evaluated and
- * row s of y (and y_low) is token sel[s].  y is [nsel, d]; y_low ([nsel, r]) may be NULL. */
+ * row s of y (and y_low) is token sel[s].  y is [nsel, d]; y_low ([nsel, r]) may be NULL.
+ * keep ([T, k], NULL = every pair) marks the pairs that survived the expert capacity (from
+ * oracle_permutation); a dropped pair adds nothing, and the gate values stay as they are. */
 void oracle_bigmac_forward(int T, int d, int r, int N, int k, int h,
                            const float *x, const float *w_gate, const float *bias,
                            const float *w_down, const float *w_up, const float *w1, const float *w2,
-                           int nsel, const int32_t *sel, double *y, double *y_low)
+                           int nsel, const int32_t *sel, const int32_t *keep, double *y, double *y_low)
 {
     (void)T;
 #pragma omp parallel for schedule(dynamic, 4)
@@ -239,6 +257,7 @@ void oracle_bigmac_forward(int T, int d, int r, int N, int k, int h,
         for (int c = 0; c < r; ++c) yl[c] = 0.0;
         for (int j = 0; j < k; ++j) {
             int e = idx[j];
+            if (keep && !keep[(size_t)t * k + j]) continue;
             vec_mat(xl, w1 + (size_t)e * r * h, r, h, a);               /* x' W1[e]            */
             for (int c = 0; c < h; ++c) a[c] = gelu(a[c]);
             vec_mat(a, w2 + (size_t)e * h * r, h, r, o);                /* E_e(x')             */
@@ -254,7 +273,7 @@ void oracle_bigmac_forward(int T, int d, int r, int N, int k, int h,
 void oracle_cdac_forward(int T, int d, int r, int N, int k,
                          const float *x, const float *w_gate, const float *bias,
                          const float *wdn, const float *wup,
-                         int nsel, const int32_t *sel, double *y)
+                         int nsel, const int32_t *sel, const int32_t *keep, double *y)
 {
     (void)T;
 #pragma omp parallel for schedule(dynamic, 4)
@@ -274,6 +293,7 @@ void oracle_cdac_forward(int T, int d, int r, int N, int k,
         for (int c = 0; c < d; ++c) yt[c] = 0.0;
         for (int j = 0; j < k; ++j) {
             int e = idx[j];
+            if (keep && !keep[(size_t)t * k + j]) continue;
             vec_mat(xd, wdn + (size_t)e * d * r, d, r, a);
             for (int c = 0; c < r; ++c) a[c] = gelu(a[c]);
             vec_mat(a, wup + (size_t)e * r * d, r, d, o);
@@ -299,12 +319,14 @@ void oracle_cdac_forward(int T, int d, int r, int N, int k,
  *   dlogit_j = gate_j (dgate_j - sum_m gate_m dgate_m)   (softmax over the selected logits)
  *   dW_g[:, e_j] += x^T dlogit_j ;  dx = dx' W_down^T + sum_j dlogit_j W_g[:, e_j]^T
  *   dW_down += x^T dx'
+ * keep ([T, k], NULL = every pair): pairs dropped by the expert capacity have no output, so
+ * o_j = 0, dgate_j = 0 and they reach no expert; the gate values are those of the full top-k.
  */
 static void layer_backward(int shared, int T, int d, int win, int hid, int N, int k,
                            const float *x, const float *dy,
                            const float *w_gate, const float *bias,
                            const float *w_down, const float *w_up, const float *w1, const float *w2,
-                           int nsel, const int32_t *sel,
+                           int nsel, const int32_t *sel, const int32_t *keep,
                            double *dx, double *d_w_down, double *d_w_up, double *d_w_gate,
                            double *d_w1, double *d_w2)
 {
@@ -314,9 +336,9 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
     double *gate = (double *)malloc(sizeof(double) * ns * k);
     double *xlow = (double *)malloc(sizeof(double) * ns * win);     /* x' (or x)                 */
     double *dyl = (double *)malloc(sizeof(double) * ns * win);      /* dy' (or dy)               */
-    double *opair = (double *)malloc(sizeof(double) * ns * k * win);/* o_j                       */
-    double *dxp = (double *)malloc(sizeof(double) * ns * k * win);  /* da_j W1^T                 */
-    double *dgt = (double *)malloc(sizeof(double) * ns * k);        /* dgate_j                   */
+    double *opair = (double *)calloc(ns * k * win, sizeof(double)); /* o_j (0 for a dropped pair) */
+    double *dxp = (double *)calloc(ns * k * win, sizeof(double));   /* da_j W1^T (0 if dropped)  */
+    double *dgt = (double *)calloc(ns * k, sizeof(double));         /* dgate_j (0 if dropped)    */
     double *ylow = (double *)malloc(sizeof(double) * ns * win);     /* y'                        */
     double *dxl = (double *)malloc(sizeof(double) * ns * win);      /* dx'                       */
     double *dlg = (double *)malloc(sizeof(double) * ns * k);        /* dlogit_j                  */
@@ -353,6 +375,7 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
         for (int s = 0; s < nsel; ++s)
             for (int j = 0; j < k; ++j) {
                 if (idx[(size_t)s * k + j] != e) continue;
+                if (keep && !keep[(size_t)(sel ? sel[s] : s) * k + j]) continue;   /* dropped by the capacity */
                 size_t p = (size_t)s * k + j;
                 const double *xl = xlow + (size_t)s * win, *dl = dyl + (size_t)s * win;
                 double *o = opair + p * win;
@@ -435,11 +458,11 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
 void oracle_bigmac_backward(int T, int d, int r, int N, int k, int h,
                             const float *x, const float *dy, const float *w_gate, const float *bias,
                             const float *w_down, const float *w_up, const float *w1, const float *w2,
-                            int nsel, const int32_t *sel,
+                            int nsel, const int32_t *sel, const int32_t *keep,
                             double *dx, double *d_w_down, double *d_w_up, double *d_w_gate,
                             double *d_w1, double *d_w2)
 {
-    layer_backward(1, T, d, r, h, N, k, x, dy, w_gate, bias, w_down, w_up, w1, w2, nsel, sel,
+    layer_backward(1, T, d, r, h, N, k, x, dy, w_gate, bias, w_down, w_up, w1, w2, nsel, sel, keep,
                    dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2);
 }
 
@@ -447,9 +470,10 @@ void oracle_bigmac_backward(int T, int d, int r, int N, int k, int h,
 void oracle_cdac_backward(int T, int d, int r, int N, int k,
                           const float *x, const float *dy, const float *w_gate, const float *bias,
                           const float *wdn, const float *wup, int nsel, const int32_t *sel,
+                          const int32_t *keep,
                           double *dx, double *d_w_gate, double *d_wdn, double *d_wup)
 {
-    layer_backward(0, T, d, d, r, N, k, x, dy, w_gate, bias, NULL, NULL, wdn, wup, nsel, sel,
+    layer_backward(0, T, d, d, r, N, k, x, dy, w_gate, bias, NULL, NULL, wdn, wup, nsel, sel, keep,
                    dx, NULL, NULL, d_w_gate, d_wdn, d_wup);
 }
 

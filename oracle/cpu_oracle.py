@@ -82,21 +82,23 @@ def route(x, w_gate, bias, k):
     return idx, gate, logits
 
 
-def permutation(idx, N):
+def permutation(idx, N, capacity=0, want_keep=False):
+    """offsets, slot_of, src_of (entries past offsets[N] are -1) and, on request, the keep mask."""
     idx = _i32(idx)
     T, k = idx.shape
     offsets = np.empty(N + 1, np.int32)
     slot_of = np.empty((T, k), np.int32)
-    src_of = np.empty(T * k, np.int32)
-    lib().oracle_permutation(T, k, N, _p(idx), _p(offsets), _p(slot_of), _p(src_of))
-    return offsets, slot_of, src_of
+    src_of = np.full(T * k, -1, np.int32)
+    keep = np.empty((T, k), np.int32)
+    lib().oracle_permutation(T, k, N, int(capacity), _p(idx), _p(offsets), _p(slot_of), _p(src_of), _p(keep))
+    return (offsets, slot_of, src_of, keep) if want_keep else (offsets, slot_of, src_of)
 
 
 def dispatch(x_low, slot_of):
     x_low, slot_of = _f32(x_low), _i32(slot_of)
     T, width = x_low.shape
     k = slot_of.shape[1]
-    out = np.empty((T * k, width), np.float32)
+    out = np.zeros((T * k, width), np.float32)      # rows no pair maps to (capacity drops) stay zero
     lib().oracle_dispatch(T, k, width, _p(x_low), _p(slot_of), _p(out))
     return out
 
@@ -121,7 +123,7 @@ def combine(o_perm, slot_of, gate=None):
     return y
 
 
-def bigmac_forward(x, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, want_y_low=False):
+def bigmac_forward(x, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, want_y_low=False, keep=None):
     x, w_gate, bias, w_down, w_up, w1, w2 = map(_f32, (x, w_gate, bias, w_down, w_up, w1, w2))
     T, d = x.shape
     r = w_down.shape[1]
@@ -132,11 +134,11 @@ def bigmac_forward(x, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, want_y_lo
     y = np.empty((nsel, d), np.float64)
     y_low = np.empty((nsel, r), np.float64) if want_y_low else None
     lib().oracle_bigmac_forward(T, d, r, N, k, h, _p(x), _p(w_gate), _p(bias), _p(w_down), _p(w_up),
-                                _p(w1), _p(w2), nsel, _p(sel), _p(y), _p(y_low))
+                                _p(w1), _p(w2), nsel, _p(sel), _p(_i32(keep)), _p(y), _p(y_low))
     return (y, y_low) if want_y_low else y
 
 
-def cdac_forward(x, w_gate, bias, wdn, wup, k, sel=None):
+def cdac_forward(x, w_gate, bias, wdn, wup, k, sel=None, keep=None):
     x, w_gate, bias, wdn, wup = map(_f32, (x, w_gate, bias, wdn, wup))
     T, d = x.shape
     N, _, r = wdn.shape
@@ -145,11 +147,11 @@ def cdac_forward(x, w_gate, bias, wdn, wup, k, sel=None):
     nsel = T if sel is None else sel.shape[0]
     y = np.empty((nsel, d), np.float64)
     lib().oracle_cdac_forward(T, d, r, N, k, _p(x), _p(w_gate), _p(bias), _p(wdn), _p(wup),
-                              nsel, _p(sel), _p(y))
+                              nsel, _p(sel), _p(_i32(keep)), _p(y))
     return y
 
 
-def bigmac_backward(x, dy, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, init=None):
+def bigmac_backward(x, dy, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, init=None, keep=None):
     """Returns dict(dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2).  init: optional dict of starting
     values the weight gradients are added to (default zeros)."""
     x, dy, w_gate, bias, w_down, w_up, w1, w2 = map(_f32, (x, dy, w_gate, bias, w_down, w_up, w1, w2))
@@ -168,13 +170,13 @@ def bigmac_backward(x, dy, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, init
         "d_w2": _f64(init.get("d_w2", np.zeros((N, h, r)))).copy(),
     }
     lib().oracle_bigmac_backward(T, d, r, N, k, h, _p(x), _p(dy), _p(w_gate), _p(bias), _p(w_down),
-                                 _p(w_up), _p(w1), _p(w2), nsel, _p(sel), _p(g["dx"]),
+                                 _p(w_up), _p(w1), _p(w2), nsel, _p(sel), _p(_i32(keep)), _p(g["dx"]),
                                  _p(g["d_w_down"]), _p(g["d_w_up"]), _p(g["d_w_gate"]),
                                  _p(g["d_w1"]), _p(g["d_w2"]))
     return g
 
 
-def cdac_backward(x, dy, w_gate, bias, wdn, wup, k, sel=None):
+def cdac_backward(x, dy, w_gate, bias, wdn, wup, k, sel=None, keep=None):
     x, dy, w_gate, bias, wdn, wup = map(_f32, (x, dy, w_gate, bias, wdn, wup))
     T, d = x.shape
     N, _, r = wdn.shape
@@ -183,8 +185,32 @@ def cdac_backward(x, dy, w_gate, bias, wdn, wup, k, sel=None):
     g = {"dx": np.zeros((T, d), np.float64), "d_w_gate": np.zeros((d, N), np.float64),
          "d_w1": np.zeros((N, d, r), np.float64), "d_w2": np.zeros((N, r, d), np.float64)}
     lib().oracle_cdac_backward(T, d, r, N, k, _p(x), _p(dy), _p(w_gate), _p(bias), _p(wdn), _p(wup),
-                               nsel, _p(sel), _p(g["dx"]), _p(g["d_w_gate"]), _p(g["d_w1"]), _p(g["d_w2"]))
+                               nsel, _p(sel), _p(_i32(keep)), _p(g["dx"]), _p(g["d_w_gate"]), _p(g["d_w1"]), _p(g["d_w2"]))
     return g
+
+
+def aux_loss(logits, idx, alpha):
+    """Load-balance loss.  The paper names the type and the coefficient (Table 5: aux_loss, 0.001)
+    but prints no formula; this is the usual one, written out:  alpha * N * sum_e f_e * P_e  with
+    f_e the share of the T*k routed pairs that chose expert e (before any capacity drop) and P_e
+    the mean over tokens of softmax(logits[t])[e] over all N experts.  Plain numpy, fp64.
+    Returns loss, f [N] and dlogits [T, N], the gradient with f held fixed."""
+    z = np.asarray(logits, np.float64)
+    idx = np.asarray(idx)
+    T, N = z.shape
+    p = np.exp(z - z.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    f = np.bincount(idx.ravel(), minlength=N).astype(np.float64) / idx.size
+    P = p.sum(axis=0) / T
+    loss = float(alpha * N * np.dot(f, P))
+    dlogits = alpha * N / T * p * (f[None, :] - (p @ f)[:, None])
+    return loss, f, dlogits
+
+
+def aux_loss_layer_terms(x, w_gate, dlogits):
+    """What the loss adds to the layer's gradients: d_w_gate += x^T dlogits, dx += dlogits w_gate^T."""
+    x, w_gate = np.asarray(x, np.float64), np.asarray(w_gate, np.float64)
+    return {"d_w_gate": x.T @ dlogits, "dx": dlogits @ w_gate.T}
 
 
 def moe_flops_per_token(d, r, k, bigmac):

@@ -13,14 +13,15 @@ import torch
 F32, BF16 = 0, 1
 ORDER_DCCA, ORDER_CDAC = 0, 1
 FLAG_ACCUMULATE, FLAG_OUT_BF16 = 1, 2
-WS_ROUTE, WS_DISPATCH, WS_GROUPED_FFN, WS_LAYER_FORWARD, WS_LAYER_TRAIN, WS_SAVED = range(6)
+WS_ROUTE, WS_DISPATCH, WS_GROUPED_FFN, WS_LAYER_FORWARD, WS_LAYER_TRAIN, WS_SAVED, WS_AUX_LOSS = range(7)
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbigmac.so")
 _lib = None
 
 
 class Dims(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "r", "N", "k", "h", "dtype", "act", "order", "flags")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "r", "N", "k", "h", "dtype", "act", "order", "flags", "capacity")] + [
+        ("aux_alpha", ctypes.c_float)]
 
 
 class Params(ctypes.Structure):
@@ -51,6 +52,10 @@ def lib() -> ctypes.CDLL:
         L.bigmac_permute_bytes.argtypes = [dp]
         L.bigmac_saved_layout.restype = ci
         L.bigmac_saved_layout.argtypes = [dp] + [ctypes.POINTER(sz)] * 4
+        L.bigmac_saved_aux_layout.restype = ci
+        L.bigmac_saved_aux_layout.argtypes = [dp] + [ctypes.POINTER(sz)] * 2
+        L.bigmac_aux_loss.restype = ci
+        L.bigmac_aux_loss.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.bigmac_route.restype = ci
         L.bigmac_route.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.bigmac_dispatch.restype = ci
@@ -72,17 +77,22 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("bigmac_workspace_bytes", "bigmac_status_string", "bigmac_forward_matrix_flops", "bigmac_permute_bytes",
-           "bigmac_saved_layout", "bigmac_route", "bigmac_dispatch", "bigmac_grouped_ffn", "bigmac_combine",
+           "bigmac_saved_layout", "bigmac_saved_aux_layout", "bigmac_aux_loss", "bigmac_route", "bigmac_dispatch", "bigmac_grouped_ffn", "bigmac_combine",
            "bigmac_layer_forward", "bigmac_layer_backward", "bigmac_set_stage_events", "bigmac_stage_name")
 STAGE_COUNT = 22
 
 
-def make_dims(T, d, r, N, k, h, dtype=BF16, order=ORDER_DCCA, flags=0, act=0) -> Dims:
-    return Dims(T, d, r, N, k, h, dtype, act, order, flags)
+def make_dims(T, d, r, N, k, h, dtype=BF16, order=ORDER_DCCA, flags=0, act=0, capacity=0, aux_alpha=0.0) -> Dims:
+    return Dims(T, d, r, N, k, h, dtype, act, order, flags, capacity, aux_alpha)
 
 
-def dims_of(wl, order=ORDER_DCCA, flags=0) -> Dims:
-    return make_dims(wl.T, wl.d, wl.r, wl.N, wl.k, wl.h, wl.dtype, order, flags)
+def dims_of(wl, order=ORDER_DCCA, flags=0, capacity=0, aux_alpha=0.0) -> Dims:
+    return make_dims(wl.T, wl.d, wl.r, wl.N, wl.k, wl.h, wl.dtype, order, flags, capacity=capacity, aux_alpha=aux_alpha)
+
+
+def expert_capacity(T: int, k: int, N: int, factor: float) -> int:
+    """Rows an expert keeps at capacity factor `factor`: ceil(factor * T * k / N)."""
+    return -(-int(round(factor * 1e6)) * T * k // (N * 1000000))
 
 
 def status_string(status: int) -> str:
@@ -105,6 +115,12 @@ def saved_layout(dims: Dims) -> dict:
     offs = [ctypes.c_size_t() for _ in range(4)]
     _check(lib().bigmac_saved_layout(ctypes.byref(dims), *[ctypes.byref(o) for o in offs]), "bigmac_saved_layout")
     return dict(zip(("topk_idx", "topk_w", "expert_offsets", "slot_of"), (o.value for o in offs)))
+
+
+def saved_aux_layout(dims: Dims) -> dict:
+    offs = [ctypes.c_size_t() for _ in range(2)]
+    _check(lib().bigmac_saved_aux_layout(ctypes.byref(dims), *[ctypes.byref(o) for o in offs]), "bigmac_saved_aux_layout")
+    return dict(zip(("aux_loss", "aux_share"), (o.value for o in offs)))
 
 
 def _ptr(t):
@@ -133,6 +149,11 @@ def _check(rc: int, where: str):
 
 def make_params(w_down, w_up, w_gate, gate_bias, w1, w2) -> Params:
     return Params(_ptr(w_down), _ptr(w_up), _ptr(w_gate), _ptr(gate_bias), _ptr(w1), _ptr(w2))
+
+
+def bigmac_aux_loss(dims, logits, topk_idx, loss, share, dlogits=None, ws=None, stream=None):
+    _check(lib().bigmac_aux_loss(ctypes.byref(dims), _ptr(logits), _ptr(topk_idx), _ptr(loss), _ptr(share), _ptr(dlogits),
+                                 _ptr(ws), _nbytes(ws), _stream(stream)), "bigmac_aux_loss")
 
 
 def bigmac_route(dims, x, w_gate, gate_bias, topk_idx, topk_w, logits_out=None, ws=None, stream=None):

@@ -148,13 +148,22 @@ int launch_topk_gate(const bigmac_dims& D, const float* logits, int32_t* topk_id
 //   dx_f32[t,:] = sum_j dlogit[t,j] * w_gate[:, idx[t,j]]      (overwritten)
 // ws: route_backward_ws_bytes (a transposed copy of w_gate).
 size_t route_backward_ws_bytes(const bigmac_dims& D);
+// With logits and share (the load-balance loss is on) the loss's gradient
+//   D.aux_alpha N / T * p[t,n] (share[n] - sum_e share[e] p[t,e]),  p = softmax(logits[t,:]),
+// is added to every entry of dL_out and takes part in dx_f32.
 int launch_route_backward(const bigmac_dims& D, const float* w_gate, const int32_t* topk_idx,
-                          const float* topk_w, const float* dgate, float* dx_f32, void* dL_out,
-                          void* ws, hipStream_t s);
+                          const float* topk_w, const float* dgate, const float* logits, const float* share,
+                          float* dx_f32, void* dL_out, void* ws, hipStream_t s);
+// Load-balance loss  D.aux_alpha N sum_e f_e P_e:  f_e = share of the T k pairs routed to e (before
+// any capacity drop), P_e = mean over tokens of softmax(logits)[e].  share [N] and loss [1] are
+// written; dlogits ([T,N], may be NULL) receives the gradient with f held fixed.
+size_t aux_loss_ws_bytes(const bigmac_dims& D);
+int launch_aux_loss(const bigmac_dims& D, const float* logits, const int32_t* topk_idx, float* share, float* loss,
+                    float* dlogits, void* ws, hipStream_t s);
 
 // ----------------------------------------------------------------------------- permute --
 size_t permutation_ws_bytes(int T, int k, int N);
-int launch_build_permutation(int T, int k, int N, const int32_t* topk_idx, int32_t* expert_offsets,
+int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* topk_idx, int32_t* expert_offsets,
                              int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s);
 int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, const int32_t* slot_of,
                          void* x_perm, hipStream_t s);

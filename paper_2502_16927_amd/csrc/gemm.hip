@@ -959,7 +959,9 @@ int launch_gemm(const GemmDesc& g, hipStream_t s) {
   if (g.mode != GEMM_DENSE && (!g.offsets || g.groups <= 0)) return BIGMAC_ERR_INVALID_ARG;
   if (g.mode == GEMM_RAGGED_M && !g.tile_map) return BIGMAC_ERR_INVALID_ARG;
   if (g.dtype == BIGMAC_BF16) {
-    if (g.lda % 8 || g.ldb % 8 || g.N % 8 || ((g.a_kcontig || g.b_kcontig) && g.K % 8) ||
+    // (a k-contiguous operand is moved in whole k tiles: past a K that is no multiple of the
+    // tile the next row's elements would follow, not zeros)
+    if (g.lda % 8 || g.ldb % 8 || g.N % 8 || ((g.a_kcontig || g.b_kcontig) && g.K % BIGMAC_TILE_BK) ||
         (g.mode != GEMM_RAGGED_M && !g.a_kcontig && g.M % 8) || g.kwrap_b % 64)
       return BIGMAC_ERR_INVALID_ARG;
     if ((g.a_kcontig || g.b_kcontig) && g.mode == GEMM_RAGGED_K) return BIGMAC_ERR_UNSUPPORTED;  // k ranges start anywhere

@@ -15,6 +15,7 @@ int check_dims(const bigmac_dims* D) {
   if (D->dtype != BIGMAC_F32 && D->dtype != BIGMAC_BF16) return BIGMAC_ERR_INVALID_ARG;
   if (D->act != BIGMAC_ACT_GELU_ERF) return BIGMAC_ERR_INVALID_ARG;
   if (D->flags & ~(BIGMAC_FLAG_ACCUMULATE | BIGMAC_FLAG_OUT_BF16)) return BIGMAC_ERR_INVALID_ARG;
+  if (D->capacity < 0 || !(D->aux_alpha >= 0.0f) || D->aux_alpha > 1e30f) return BIGMAC_ERR_INVALID_ARG;
   if (D->order == BIGMAC_ORDER_CDAC && D->dtype == BIGMAC_BF16 && (D->flags & BIGMAC_FLAG_OUT_BF16)) return BIGMAC_ERR_UNSUPPORTED;
   return BIGMAC_OK;
 }
@@ -45,10 +46,10 @@ struct Carver {  // hands out 256-byte aligned pieces of one buffer
 };
 
 struct SavedPlan {
-  size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, x_perm, act, hact, o_perm, y_low, total;
+  size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, x_perm, act, hact, o_perm, y_low, logits, aux, total;
 };
 struct FwdPlan {
-  size_t logits, perm, x_low, partials, total;
+  size_t logits, perm, x_low, partials, aux, total;
 };
 struct BwdPlan {
   size_t dy_low, dgate, do_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, total;
@@ -82,6 +83,10 @@ SavedPlan plan_saved(const bigmac_dims& D) {
   p.hact = c.take(Tk * wide_ld(D) * es);
   p.o_perm = c.take(Tk * W.win * es);
   p.y_low = c.take(D.order == BIGMAC_ORDER_DCCA ? low_bytes(D) : 0);
+  // load-balance loss: the backward pass needs the logits and the experts' pair shares; aux holds
+  // the loss (one float) followed, 256 bytes on, by share[N]
+  p.logits = c.take(D.aux_alpha > 0.0f ? (size_t)D.T * D.N * 4 : 0);
+  p.aux = c.take(D.aux_alpha > 0.0f ? 256 + (size_t)D.N * 4 : 0);
   p.total = c.off;
   return p;
 }
@@ -112,6 +117,7 @@ FwdPlan plan_fwd(const bigmac_dims& D) {
   p.perm = c.take(permutation_ws_bytes(D.T, D.k, D.N));
   p.x_low = c.take(D.order == BIGMAC_ORDER_DCCA ? (size_t)D.T * D.r * esize(D.dtype) : 0);
   p.partials = c.take(forward_partials_bytes(D));
+  p.aux = c.take(D.aux_alpha > 0.0f ? aux_loss_ws_bytes(D) : 0);
   p.total = c.off;
   return p;
 }
@@ -239,6 +245,7 @@ size_t bigmac_workspace_bytes(const bigmac_dims* D, int kind) {
       return f > b ? f : b;
     }
     case BIGMAC_WS_SAVED: return plan_saved(*D).total;
+    case BIGMAC_WS_AUX_LOSS: return aux_loss_ws_bytes(*D);
     default: return 0;
   }
 }
@@ -293,6 +300,25 @@ int bigmac_saved_layout(const bigmac_dims* D, size_t* off_topk_idx, size_t* off_
   return BIGMAC_OK;
 }
 
+int bigmac_saved_aux_layout(const bigmac_dims* D, size_t* off_aux_loss, size_t* off_aux_share) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  if (!(D->aux_alpha > 0.0f)) return BIGMAC_ERR_INVALID_ARG;
+  const SavedPlan p = plan_saved(*D);
+  if (off_aux_loss) *off_aux_loss = p.aux;
+  if (off_aux_share) *off_aux_share = p.aux + 256;
+  return BIGMAC_OK;
+}
+
+int bigmac_aux_loss(const bigmac_dims* D, const float* logits, const int32_t* topk_idx, float* loss, float* share,
+                    float* dlogits, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_dims(D);
+  if (rc) return rc;
+  if (!logits || !topk_idx || !loss || !share || !ws) return BIGMAC_ERR_INVALID_ARG;
+  if (ws_bytes < aux_loss_ws_bytes(*D)) return BIGMAC_ERR_WORKSPACE;
+  return launch_aux_loss(*D, logits, topk_idx, share, loss, dlogits, ws, (hipStream_t)stream);
+}
+
 int bigmac_route(const bigmac_dims* D, const void* x, const float* w_gate, const float* gate_bias, int32_t* topk_idx,
                  float* topk_w, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_dims(D);
@@ -317,7 +343,7 @@ int bigmac_dispatch(const bigmac_dims* D, const void* x_low, const int32_t* topk
   if ((x_low == nullptr) != (x_perm == nullptr)) return BIGMAC_ERR_INVALID_ARG;
   if (ws_bytes < bigmac_workspace_bytes(D, BIGMAC_WS_DISPATCH)) return BIGMAC_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
-  rc = launch_build_permutation(D->T, D->k, D->N, topk_idx, expert_offsets, slot_of, src_of, ws, s);
+  rc = launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, expert_offsets, slot_of, src_of, ws, s);
   if (rc || !x_low) return rc;
   return launch_dispatch_rows(D->dtype, D->T, D->k, widths(*D).win, x_low, slot_of, x_perm, s);
 }
@@ -371,15 +397,19 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   void* o_perm = sv + S.o_perm;
   void* y_low = sv + S.y_low;
   const bool out_bf16 = bf(*D) && (D->flags & BIGMAC_FLAG_OUT_BF16);
+  const bool aux = D->aux_alpha > 0.0f;                       // the loss lives in the saved block
+  float* logits = aux ? (float*)(sv + S.logits) : (float*)(wsb + F.logits);
 
   {
     BIGMAC_STAGE(BIGMAC_STAGE_ROUTER_LOGITS);
-    rc = launch_router_logits(*D, x, P->w_gate, P->gate_bias, (float*)(wsb + F.logits), s);
+    rc = launch_router_logits(*D, x, P->w_gate, P->gate_bias, logits, s);
   }
   if (rc) return rc;
   {
     BIGMAC_STAGE(BIGMAC_STAGE_TOPK_GATE);
-    rc = launch_topk_gate(*D, (const float*)(wsb + F.logits), topk_idx, topk_w, s);
+    rc = launch_topk_gate(*D, logits, topk_idx, topk_w, s);
+    if (!rc && aux)
+      rc = launch_aux_loss(*D, logits, topk_idx, (float*)(sv + S.aux + 256), (float*)(sv + S.aux), nullptr, wsb + F.aux, s);
   }
   if (rc) return rc;
   const void* x_low = x;
@@ -404,7 +434,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   }
   {
     BIGMAC_STAGE(BIGMAC_STAGE_PERMUTATION);
-    rc = launch_build_permutation(D->T, D->k, D->N, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s);
+    rc = launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s);
     if (rc) return rc;
     rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype), tile_map, s);
     if (rc) return rc;
@@ -568,7 +598,9 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   // gate backward; the router's share of dx is written to dx_f32
   {
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_GATE);
-    rc = launch_route_backward(*D, P->w_gate, topk_idx, topk_w, dgate, dx_f32, dL, wsb + B.route, s);
+    const bool aux = D->aux_alpha > 0.0f;
+    rc = launch_route_backward(*D, P->w_gate, topk_idx, topk_w, dgate, aux ? (const float*)(sv + S.logits) : nullptr,
+                               aux ? (const float*)(sv + S.aux + 256) : nullptr, dx_f32, dL, wsb + B.route, s);
   }
   if (rc) return rc;
   {  // dW_g (+)= x^T dL

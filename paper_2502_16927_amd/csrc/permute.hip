@@ -43,9 +43,13 @@ __device__ __forceinline__ int block_scan_1024(int v, int* wave_totals) {
 }
 
 // in place: counts[c][e] -> first slot of expert e's pairs of chunk c;  offsets[e] = first slot of e.
+// With a capacity (> 0) an expert's range holds at most that many slots; the per-chunk first
+// slots still count every pair in front, so a pair is past its expert's range exactly when its
+// slot reaches offsets[e] + capacity.
 // The 1024 threads are G groups x NP experts (NP = N rounded up to a power of two, G = 1024 / NP);
 // group g owns a contiguous range of chunks, so all chunk rows are read by many threads at once.
-__global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ counts, int nchunks, int N, int NP, int32_t* __restrict__ offsets) {
+__global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ counts, int nchunks, int N, int NP, int capacity,
+                                                         int32_t* __restrict__ offsets) {
   __shared__ int part[1024];        // [g][e]: pairs of expert e in the chunks of group g
   __shared__ int wave_totals[16];
   const int G = 1024 / NP;
@@ -70,14 +74,15 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ c
     if (h < g) before_me += v;
   }
   // exclusive scan over the experts (threads of group 0 carry the totals, the others zero)
-  const int incl = block_scan_1024(g == 0 && e < N ? total : 0, wave_totals);
+  const int held = capacity > 0 ? min(total, capacity) : total;   // slots of expert e
+  const int incl = block_scan_1024(g == 0 && e < N ? held : 0, wave_totals);
   __syncthreads();
-  if (g == 0) part[e] = incl - total;   // first slot of expert e (part[0 .. NP) is free to reuse: every thread has read it)
+  if (g == 0) part[e] = incl - held;    // first slot of expert e (part[0 .. NP) is free to reuse: every thread has read it)
   __syncthreads();
   if (e < N) {
     int run = part[e] + before_me;
     if (g == 0) offsets[e] = part[e];
-    if (g == 0 && e == N - 1) offsets[N] = part[e] + total;
+    if (g == 0 && e == N - 1) offsets[N] = part[e] + held;
     for (int c0 = c_beg; c0 < c_end; c0 += 8) {
       int v[8];
 #pragma unroll
@@ -93,11 +98,12 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ c
 
 // One wavefront per chunk walks its pairs in flat order, 64 at a time (all read up front).  A
 // pair's slot is the running first-free slot of its expert plus the number of earlier lanes with
-// the same expert.
-__global__ __launch_bounds__(64) void perm_rank_kernel(const int32_t* __restrict__ idx, int Tk, int N, int nbits,
-                                                       const int32_t* __restrict__ base, int32_t* __restrict__ slot_of,
-                                                       int32_t* __restrict__ src_of) {
-  extern __shared__ int run[];
+// the same expert.  With a capacity, a pair whose slot falls past its expert's range is dropped:
+// slot_of = -1, no src_of entry.
+__global__ __launch_bounds__(64) void perm_rank_kernel(const int32_t* __restrict__ idx, int Tk, int N, int nbits, int capacity,
+                                                       const int32_t* __restrict__ base, const int32_t* __restrict__ offsets,
+                                                       int32_t* __restrict__ slot_of, int32_t* __restrict__ src_of) {
+  extern __shared__ int run[];      // [N] running first-free slot, [N] end of the expert's range
   const int lane = threadIdx.x;
   constexpr int ROUNDS = P_CHUNK / 64;
   int mine[ROUNDS];
@@ -106,7 +112,11 @@ __global__ __launch_bounds__(64) void perm_rank_kernel(const int32_t* __restrict
     const int f = blockIdx.x * P_CHUNK + r * 64 + lane;
     mine[r] = f < Tk ? idx[f] : -1;
   }
-  for (int e = lane; e < N; e += 64) run[e] = base[(size_t)blockIdx.x * N + e];
+  int* range_end = run + N;
+  for (int e = lane; e < N; e += 64) {
+    run[e] = base[(size_t)blockIdx.x * N + e];
+    range_end[e] = capacity > 0 ? offsets[e] + capacity : 0x7fffffff;
+  }
   __syncthreads();
   const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
@@ -121,8 +131,12 @@ __global__ __launch_bounds__(64) void perm_rank_kernel(const int32_t* __restrict
     }
     if (live) {
       const int slot = run[e] + __popcll(same & below);
-      slot_of[f] = slot;
-      src_of[slot] = f;
+      if (slot < range_end[e]) {
+        slot_of[f] = slot;
+        src_of[slot] = f;
+      } else {
+        slot_of[f] = -1;
+      }
     }
     __syncthreads();
     if (live && (same >> lane) == 1ull) run[e] += __popcll(same);  // highest lane of each expert group
@@ -137,7 +151,10 @@ __global__ __launch_bounds__(256) void dispatch_rows_kernel(const uint4* __restr
   if (g >= (size_t)T * cpr) return;
   const int t = (int)(g / cpr), c = (int)(g % cpr);
   const uint4 v = x_low[g];
-  for (int j = 0; j < k; ++j) x_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c] = v;
+  for (int j = 0; j < k; ++j) {
+    const int slot = slot_of[(size_t)t * k + j];
+    if (slot >= 0) x_perm[(size_t)slot * cpr + c] = v;   // a dropped pair has no row
+  }
 }
 
 // y_low[t] = sum_j w[t,j] * o_perm[slot_of[t,j]], j ascending, fp32.  Thread = (token, 8 columns).
@@ -151,8 +168,10 @@ __global__ __launch_bounds__(256) void combine_rows_bf16_kernel(const uint4* __r
   float acc[8] = {};
   for (int j = 0; j < k; ++j) {
     const float wj = w ? w[(size_t)t * k + j] : 1.0f;
+    const int slot = slot_of[(size_t)t * k + j];
+    if (slot < 0) continue;                     // dropped pair
     float o[8];
-    unpack_bf16x8(o_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c], o);
+    unpack_bf16x8(o_perm[(size_t)slot * cpr + c], o);
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = fmaf(wj, o[i], acc[i]);
   }
@@ -182,7 +201,9 @@ __global__ __launch_bounds__(256) void combine_rows_f32_kernel(const float4* __r
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int j = 0; j < k; ++j) {
     const float wj = w ? w[(size_t)t * k + j] : 1.0f;
-    const float4 o = o_perm[(size_t)slot_of[(size_t)t * k + j] * cpr + c];
+    const int slot = slot_of[(size_t)t * k + j];
+    if (slot < 0) continue;                     // dropped pair
+    const float4 o = o_perm[(size_t)slot * cpr + c];
     acc.x = fmaf(wj, o.x, acc.x); acc.y = fmaf(wj, o.y, acc.y);
     acc.z = fmaf(wj, o.z, acc.z); acc.w = fmaf(wj, o.w, acc.w);
   }
@@ -198,7 +219,12 @@ __global__ __launch_bounds__(256) void combine_backward_kernel(const float* __re
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
   for (int j = 0; j < k; ++j) {
-    const size_t slot = (size_t)slot_of[(size_t)t * k + j];
+    const int slot_j = slot_of[(size_t)t * k + j];
+    if (slot_j < 0) {                           // dropped pair (the same in every lane): no row, no gate gradient
+      if (lane == 0) dgate[(size_t)t * k + j] = 0.0f;
+      continue;
+    }
+    const size_t slot = (size_t)slot_j;
     const float wj = w[(size_t)t * k + j];
     float dot = 0.0f;
     for (int c0 = 0; c0 < width; c0 += 256) {
@@ -244,9 +270,10 @@ __global__ __launch_bounds__(256) void combine_backward_bf16_kernel(const float*
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       if (j >= k) break;
-      const size_t row = (size_t)__shfl(my_slot, j, 64) * width + c;
+      const int slot_j = __shfl(my_slot, j, 64);
+      const size_t row = (size_t)slot_j * width + c;
       const float wj = __shfl(my_w, j, 64);
-      if (live) {
+      if (live && slot_j >= 0) {                // a dropped pair has no row; its dot stays 0
         float o[8], q[8];
         unpack_bf16x8(*(const uint4*)(o_perm + row), o);
 #pragma unroll
@@ -275,7 +302,7 @@ size_t permutation_ws_bytes(int T, int k, int N) {
   return align_up(nchunks * N * sizeof(int32_t));
 }
 
-int launch_build_permutation(int T, int k, int N, const int32_t* topk_idx, int32_t* expert_offsets,
+int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* topk_idx, int32_t* expert_offsets,
                              int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s) {
   const int Tk = T * k;
   const int nchunks = (Tk + P_CHUNK - 1) / P_CHUNK;
@@ -286,9 +313,10 @@ int launch_build_permutation(int T, int k, int N, const int32_t* topk_idx, int32
   BIGMAC_CHECK_LAUNCH();
   int NP = 1;
   while (NP < N) NP <<= 1;
-  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, counts, nchunks, N, NP, expert_offsets);
+  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, counts, nchunks, N, NP, capacity, expert_offsets);
   BIGMAC_CHECK_LAUNCH();
-  hipLaunchKernelGGL(perm_rank_kernel, dim3(nchunks), dim3(64), N * sizeof(int), s, topk_idx, Tk, N, nbits, counts, slot_of, src_of);
+  hipLaunchKernelGGL(perm_rank_kernel, dim3(nchunks), dim3(64), 2 * N * sizeof(int), s, topk_idx, Tk, N, nbits, capacity, counts, expert_offsets,
+                     slot_of, src_of);
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }

@@ -293,15 +293,150 @@ __global__ void transpose_f32_kernel(const float* __restrict__ in, float* __rest
     if (c0 + i < cols && r < rows) out[(size_t)(c0 + i) * rows + r] = tile[threadIdx.x][i];
 }
 
+// softmax over all N logits of one token by one wavefront: lane l holds experts l, l + 64, ...
+template <int PER>
+__device__ __forceinline__ void softmax_row(const float* __restrict__ row, int N, int lane, float (&p)[PER]) {
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int n = i * 64 + lane;
+    p[i] = n < N ? row[n] : -INFINITY;
+    m = fmaxf(m, p[i]);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  float sum = 0.0f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    p[i] = i * 64 + lane < N ? expf(p[i] - m) : 0.0f;
+    sum += p[i];
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) p[i] *= inv;
+}
+
+// Gradient of the load-balance loss  alpha N sum_e f_e P_e  with respect to one token's logits,
+// the pair shares f held fixed:  scale p_n (f_n - sum_e f_e p_e),  scale = alpha N / T.
+template <int PER>
+__device__ __forceinline__ void aux_grad_row(const float* __restrict__ row, const float* __restrict__ share, int N, int lane,
+                                             float scale, float (&g)[PER]) {
+  float f[PER];
+  softmax_row<PER>(row, N, lane, g);
+  float mix = 0.0f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int n = i * 64 + lane;
+    f[i] = n < N ? share[n] : 0.0f;
+    mix = fmaf(f[i], g[i], mix);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mix += __shfl_xor(mix, off, 64);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) g[i] = scale * g[i] * (f[i] - mix);
+}
+
+// Column sums of softmax(logits) over a strided share of the tokens: workgroup b, wavefront w
+// takes tokens (b * 4 + w) + i * 4 * gridDim.x.  partial[b][n], the four wavefronts added in order.
+template <int PER>
+__global__ __launch_bounds__(256) void aux_colsum_kernel(const float* __restrict__ logits, int T, int N, float* __restrict__ partial) {
+  __shared__ float sums[4][1024];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float col[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) col[i] = 0.0f;
+  for (int t = blockIdx.x * 4 + wave; t < T; t += 4 * gridDim.x) {
+    float p[PER];
+    softmax_row<PER>(logits + (size_t)t * N, N, lane, p);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) col[i] += p[i];
+  }
+#pragma unroll
+  for (int i = 0; i < PER; ++i)
+    if (i * 64 + lane < N) sums[wave][i * 64 + lane] = col[i];
+  __syncthreads();
+  for (int n = threadIdx.x; n < N; n += 256)
+    partial[(size_t)blockIdx.x * N + n] = ((sums[0][n] + sums[1][n]) + sums[2][n]) + sums[3][n];
+}
+
+// One workgroup: pair counts per expert (integer, order-free), P_e from the partial column sums,
+// share[e] = f_e, and the loss  alpha N sum_e f_e P_e.  Every sum has a fixed order: the 1024
+// threads are G groups x NP experts (NP = N rounded up to a power of two); group g adds its
+// contiguous range of partials in order, the G group sums are added in group order, and the N
+// terms f_e P_e go through a fixed tree.
+__global__ __launch_bounds__(1024) void aux_finish_kernel(const int32_t* __restrict__ topk_idx, const float* __restrict__ partial,
+                                                          int nparts, int T, int N, int NP, int k, float alpha,
+                                                          float* __restrict__ share, float* __restrict__ loss) {
+  __shared__ int cnt[1024];
+  __shared__ float psum[1024];
+  cnt[threadIdx.x] = 0;
+  __syncthreads();
+  const int Tk = T * k;
+  const int quads = Tk / 4;                        // 16-byte reads; the base pointer is 16-byte aligned
+  for (int q = threadIdx.x; q < quads; q += 1024) {
+    const int4 v = ((const int4*)topk_idx)[q];
+    atomicAdd(&cnt[v.x], 1); atomicAdd(&cnt[v.y], 1); atomicAdd(&cnt[v.z], 1); atomicAdd(&cnt[v.w], 1);
+  }
+  for (int f = quads * 4 + threadIdx.x; f < Tk; f += 1024) atomicAdd(&cnt[topk_idx[f]], 1);
+  const int G = 1024 / NP, e = threadIdx.x % NP, g = threadIdx.x / NP;
+  const int per = (nparts + G - 1) / G;
+  const int b_beg = min(g * per, nparts), b_end = min(b_beg + per, nparts);
+  float mine = 0.0f;
+  if (e < N)
+    for (int b = b_beg; b < b_end; ++b) mine += partial[(size_t)b * N + e];
+  psum[g * NP + e] = mine;
+  __syncthreads();
+  float term = 0.0f;
+  if ((int)threadIdx.x < N) {
+    float P = 0.0f;
+    for (int h = 0; h < G; ++h) P += psum[h * NP + threadIdx.x];
+    const float f = (float)cnt[threadIdx.x] / (float)Tk;
+    share[threadIdx.x] = f;
+    term = f * (P / (float)T);
+  }
+  __syncthreads();
+  psum[threadIdx.x] = term;
+  __syncthreads();
+  for (int half = 512; half >= 1; half >>= 1) {
+    if ((int)threadIdx.x < half) psum[threadIdx.x] += psum[threadIdx.x + half];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = alpha * (float)N * psum[0];
+}
+
+// dlogits[t, :] of the load-balance loss, one wavefront per token
+template <int PER>
+__global__ __launch_bounds__(256) void aux_grad_kernel(const float* __restrict__ logits, const float* __restrict__ share, int T, int N,
+                                                       float scale, float* __restrict__ dlogits) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  float g[PER];
+  aux_grad_row<PER>(logits + (size_t)t * N, share, N, lane, scale, g);
+#pragma unroll
+  for (int i = 0; i < PER; ++i)
+    if (i * 64 + lane < N) dlogits[(size_t)t * N + i * 64 + lane] = g[i];
+}
+
 // Backward of the gate (softmax over the k picked logits) and the router's share of dx.
 // One wavefront per token.  dL (dense [T, N], storage type DT) feeds d_w_gate = x^T dL.
-template <typename DT>
+// With the load-balance loss (logits != NULL) its gradient joins every entry of the row and the
+// router's share of dx runs over all N experts instead of the k picked ones (dx == NULL: left to
+// the caller).
+template <typename DT, int PER>
 __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
                                                             const float* __restrict__ dgate, const float* __restrict__ wg_t /*[N,d]*/,
+                                                            const float* __restrict__ logits, const float* __restrict__ share, float aux_scale,
                                                             DT* __restrict__ dL, float* __restrict__ dx, int T, int d, int N, int k) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
+  float aux[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) aux[i] = 0.0f;
+  if (logits) aux_grad_row<PER>(logits + (size_t)t * N, share, N, lane, aux_scale, aux);
   float w = 0.0f, g = 0.0f;
   int e = 0;
   if (lane < k) {
@@ -313,25 +448,45 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __res
   for (int j = 0; j < k; ++j) mix = fmaf(__shfl(w, j, 64), __shfl(g, j, 64), mix);
   const float dl = w * (g - mix);
   // every lane takes part in the shuffles (uniform trip counts); only loads and stores are guarded
-  for (int n0 = 0; n0 < N; n0 += 64) {   // dense row of dL: the k picked experts, zeros elsewhere
-    const int n = n0 + lane;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {        // dense row of dL: the k picked experts, zeros (or the loss term) elsewhere
+    if (i * 64 >= N) break;
+    const int n = i * 64 + lane;
     float val = 0.0f;
     for (int j = 0; j < k; ++j) {
       const float dj = __shfl(dl, j, 64);
       if (__shfl(e, j, 64) == n) val = dj;
     }
-    if (n < N) Elem<DT>::store(dL + (size_t)t * N + n, val);
+    aux[i] += val;                       // the whole dlogits entry from here on
+    if (n < N) Elem<DT>::store(dL + (size_t)t * N + n, logits ? aux[i] : val);
   }
+  if (!dx) return;                        // the caller forms the router's share of dx as a product with dL
   for (int c0 = 0; c0 < d; c0 += 256) {
     const int c = c0 + lane * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j = 0; j < k; ++j) {
-      const float dj = __shfl(dl, j, 64);
-      const int ej = __shfl(e, j, 64);
-      if (c < d) {
-        const float4 wv = *(const float4*)(wg_t + (size_t)ej * d + c);
-        acc.x = fmaf(dj, wv.x, acc.x); acc.y = fmaf(dj, wv.y, acc.y);
-        acc.z = fmaf(dj, wv.z, acc.z); acc.w = fmaf(dj, wv.w, acc.w);
+    if (!logits) {
+      for (int j = 0; j < k; ++j) {
+        const float dj = __shfl(dl, j, 64);
+        const int ej = __shfl(e, j, 64);
+        if (c < d) {
+          const float4 wv = *(const float4*)(wg_t + (size_t)ej * d + c);
+          acc.x = fmaf(dj, wv.x, acc.x); acc.y = fmaf(dj, wv.y, acc.y);
+          acc.z = fmaf(dj, wv.z, acc.z); acc.w = fmaf(dj, wv.w, acc.w);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        if (i * 64 >= N) break;
+        const int live = min(64, N - i * 64);
+        for (int l = 0; l < live; ++l) {
+          const float dn = __shfl(aux[i], l, 64);
+          if (c < d) {
+            const float4 wv = *(const float4*)(wg_t + (size_t)(i * 64 + l) * d + c);
+            acc.x = fmaf(dn, wv.x, acc.x); acc.y = fmaf(dn, wv.y, acc.y);
+            acc.z = fmaf(dn, wv.z, acc.z); acc.w = fmaf(dn, wv.w, acc.w);
+          }
+        }
       }
     }
     if (c < d) *(float4*)(dx + (size_t)t * d + c) = acc;
@@ -389,18 +544,89 @@ size_t route_backward_ws_bytes(const bigmac_dims& D) {
   return align_up((size_t)D.N * D.d * sizeof(float));  // transposed router weights
 }
 
+__global__ void router_to_bf16_kernel(const float* __restrict__ in, bf16_t* __restrict__ out, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = f2bf(in[i]);
+}
+
 int launch_route_backward(const bigmac_dims& D, const float* w_gate, const int32_t* topk_idx,
-                          const float* topk_w, const float* dgate, float* dx_f32, void* dL_out,
-                          void* ws, hipStream_t s) {
+                          const float* topk_w, const float* dgate, const float* logits, const float* share,
+                          float* dx_f32, void* dL_out, void* ws, hipStream_t s) {
+  // With the loss every entry of a dL row is non-zero, and the router's share of dx is the dense
+  // product dL w_gate^T: on bf16 runs it goes to the matrix cores (dL is stored in bf16 anyway,
+  // w_gate is rounded to bf16 for this product only); otherwise the kernel walks all N rows.
+  const bool by_product = logits && D.dtype == BIGMAC_BF16 && D.N % 32 == 0;   // N is the product's K: whole k tiles
   float* wg_t = (float*)ws;
-  hipLaunchKernelGGL(transpose_f32_kernel, dim3((D.N + 31) / 32, (D.d + 31) / 32), dim3(32, 8), 0, s, w_gate, wg_t, D.d, D.N);
+  if (by_product) {
+    const size_t n = (size_t)D.d * D.N;
+    hipLaunchKernelGGL(router_to_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w_gate, (bf16_t*)ws, n);
+  } else {
+    hipLaunchKernelGGL(transpose_f32_kernel, dim3((D.N + 31) / 32, (D.d + 31) / 32), dim3(32, 8), 0, s, w_gate, wg_t, D.d, D.N);
+  }
   BIGMAC_CHECK_LAUNCH();
   const dim3 grid((D.T + 3) / 4), block(256);
-  if (D.dtype == BIGMAC_BF16)
-    hipLaunchKernelGGL(gate_backward_kernel<bf16_t>, grid, block, 0, s, topk_idx, topk_w, dgate, wg_t, (bf16_t*)dL_out, dx_f32, D.T, D.d, D.N, D.k);
-  else
-    hipLaunchKernelGGL(gate_backward_kernel<float>, grid, block, 0, s, topk_idx, topk_w, dgate, wg_t, (float*)dL_out, dx_f32, D.T, D.d, D.N, D.k);
+  const float aux_scale = logits ? D.aux_alpha * (float)D.N / (float)D.T : 0.0f;
+  const int per = (D.N + 63) / 64;
+  float* dx_kernel = by_product ? nullptr : dx_f32;
+#define BIGMAC_GATE_BWD(DT, P)                                                                                          \
+  hipLaunchKernelGGL((gate_backward_kernel<DT, P>), grid, block, 0, s, topk_idx, topk_w, dgate, wg_t, logits, share, aux_scale, \
+                     (DT*)dL_out, dx_kernel, D.T, D.d, D.N, D.k)
+#define BIGMAC_GATE_BWD_PER(DT)          \
+  if (per <= 1) BIGMAC_GATE_BWD(DT, 1);  \
+  else if (per <= 2) BIGMAC_GATE_BWD(DT, 2); \
+  else if (per <= 4) BIGMAC_GATE_BWD(DT, 4); \
+  else if (per <= 8) BIGMAC_GATE_BWD(DT, 8); \
+  else BIGMAC_GATE_BWD(DT, 16)
+  if (D.dtype == BIGMAC_BF16) {
+    BIGMAC_GATE_BWD_PER(bf16_t);
+  } else {
+    BIGMAC_GATE_BWD_PER(float);
+  }
+#undef BIGMAC_GATE_BWD_PER
+#undef BIGMAC_GATE_BWD
   BIGMAC_CHECK_LAUNCH();
+  if (by_product) {   // dx_f32[T, d] = dL[T, N] . w_gate[d, N]^T
+    GemmDesc g = {};
+    g.dtype = BIGMAC_BF16; g.mode = GEMM_DENSE; g.ksplit = 1;
+    g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE; g.out_f32 = 1;
+    g.A = dL_out; g.lda = D.N; g.M = D.T; g.K = D.N;
+    g.B = ws; g.ldb = D.N; g.N = D.d;
+    g.C = dx_f32; g.ldc = D.d;
+    return launch_gemm(g, s);
+  }
+  return BIGMAC_OK;
+}
+
+// Workgroups of the column-sum pass: a fixed function of T, so that the order of the sums is too.
+static int aux_parts(int T) {
+  const int groups = (T + 3) / 4;
+  return groups < 256 ? groups : 256;
+}
+
+size_t aux_loss_ws_bytes(const bigmac_dims& D) { return align_up((size_t)aux_parts(D.T) * D.N * sizeof(float)); }
+
+int launch_aux_loss(const bigmac_dims& D, const float* logits, const int32_t* topk_idx, float* share, float* loss,
+                    float* dlogits, void* ws, hipStream_t s) {
+  float* partial = (float*)ws;
+  const int parts = aux_parts(D.T), per = (D.N + 63) / 64;
+#define BIGMAC_AUX_PER(KERNEL, GRID, ...)                                                         \
+  if (per <= 1) hipLaunchKernelGGL(KERNEL<1>, GRID, dim3(256), 0, s, __VA_ARGS__);                \
+  else if (per <= 2) hipLaunchKernelGGL(KERNEL<2>, GRID, dim3(256), 0, s, __VA_ARGS__);           \
+  else if (per <= 4) hipLaunchKernelGGL(KERNEL<4>, GRID, dim3(256), 0, s, __VA_ARGS__);           \
+  else if (per <= 8) hipLaunchKernelGGL(KERNEL<8>, GRID, dim3(256), 0, s, __VA_ARGS__);           \
+  else hipLaunchKernelGGL(KERNEL<16>, GRID, dim3(256), 0, s, __VA_ARGS__)
+  BIGMAC_AUX_PER(aux_colsum_kernel, dim3(parts), logits, D.T, D.N, partial);
+  BIGMAC_CHECK_LAUNCH();
+  int NP = 1;
+  while (NP < D.N) NP <<= 1;
+  hipLaunchKernelGGL(aux_finish_kernel, dim3(1), dim3(1024), 0, s, topk_idx, partial, parts, D.T, D.N, NP, D.k, D.aux_alpha, share, loss);
+  BIGMAC_CHECK_LAUNCH();
+  if (dlogits) {
+    const float scale = D.aux_alpha * (float)D.N / (float)D.T;
+    BIGMAC_AUX_PER(aux_grad_kernel, dim3((D.T + 3) / 4), logits, share, D.T, D.N, scale, dlogits);
+    BIGMAC_CHECK_LAUNCH();
+  }
+#undef BIGMAC_AUX_PER
   return BIGMAC_OK;
 }
 

@@ -89,9 +89,9 @@ def host(t: torch.Tensor) -> np.ndarray:
 class DeviceLayer:
     """All device buffers of one layer call for a workload (allocation and marshalling only)."""
 
-    def __init__(self, wl: synth.Workload, data: dict, order=B.ORDER_DCCA, flags=0, device="cuda:0"):
+    def __init__(self, wl: synth.Workload, data: dict, order=B.ORDER_DCCA, flags=0, device="cuda:0", capacity=0, aux_alpha=0.0):
         self.wl, self.order, self.flags, self.device = wl, order, flags, device
-        self.dims = B.dims_of(wl, order, flags)
+        self.dims = B.dims_of(wl, order, flags, capacity=capacity, aux_alpha=aux_alpha)
         dt = wl.dtype
         self.x = B.to_device(data["x"], dt, device)
         self.dy = B.to_device(data.get("dy"), dt, device)
@@ -157,6 +157,14 @@ class DeviceLayer:
                 "topk_w": f(lay["topk_w"], Tk, np.float32).reshape(wl.T, wl.k),
                 "expert_offsets": f(lay["expert_offsets"], wl.N + 1, np.int32),
                 "slot_of": f(lay["slot_of"], Tk, np.int32).reshape(wl.T, wl.k)}
+
+    def saved_aux(self):
+        """(loss, share[N]) the training forward left in the saved block (dims.aux_alpha > 0)."""
+        lay = B.saved_aux_layout(self.dims)
+        raw = self.saved.cpu().numpy()
+        loss = raw[lay["aux_loss"]:lay["aux_loss"] + 4].view(np.float32)[0]
+        share = raw[lay["aux_share"]:lay["aux_share"] + 4 * self.wl.N].view(np.float32).copy()
+        return float(loss), share
 
 
 def add_cdac_weights(data: dict) -> dict:
