@@ -140,7 +140,7 @@ def main():
     from paper_2502_16927_amd import synth
 
     wl = synth.WORKLOADS.get(args.workload) or synth.NEXT_WORKLOADS[args.workload]
-    if args.workload in synth.NEXT_WORKLOADS:
+    if args.workload == "vanilla_moe":
         args.order = "cdac"   # the vanilla layer is a CDAC-order layer with a wide hidden dimension
     if args.tokens:
         wl = wl.with_T(args.tokens)

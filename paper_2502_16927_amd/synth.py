@@ -56,6 +56,12 @@ WORKLOADS = {
 NEXT_WORKLOADS = {
     "vanilla_moe": Workload("vanilla_moe", T=8192, d=1024, r=4096, N=8, k=2, h=1024, dtype=BF16,
                             x_std=1.0, backward=True, index=5),
+    # The two larger base models of the paper's training comparison (Fig. 3: GPT3-2.7B and
+    # GPT3-6.7B widths), as BigMac layers with the same expert count, top-8 and r/d = 1/4.
+    "gpt_2p7b": Workload("gpt_2p7b", T=8192, d=2560, r=640, N=64, k=8, h=2560, dtype=BF16,
+                         x_std=1.0, backward=True, index=6),
+    "gpt_6p7b": Workload("gpt_6p7b", T=8192, d=4096, r=1024, N=64, k=8, h=4096, dtype=BF16,
+                         x_std=1.0, backward=True, index=7),
 }
 DECODE_T_SWEEP = (32, 128, 512, 2048)
 W_STD = 0.02
