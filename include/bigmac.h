@@ -132,7 +132,8 @@ int bigmac_aux_loss(const bigmac_dims *dims, const float *logits /*[T,N]*/, cons
  * of the flat pairs f = t*k + j by expert (expert_offsets [N+1], slot_of [T,k], src_of [T*k]
  * with src_of[slot_of[f]] = f) and copies x_low[t, :] to x_perm[slot_of[t, j], :] for every j.
  * x_low is [T, win], x_perm is [T*k, win], both dtype.  x_low == NULL (with x_perm == NULL)
- * builds the permutation only. */
+ * builds the permutation only.  With dims.capacity > 0 the dropped pairs get slot_of = -1, and
+ * x_perm rows and src_of entries at or beyond expert_offsets[N] are left as they were. */
 int bigmac_dispatch(const bigmac_dims *dims, const void *x_low, const int32_t *topk_idx,
                     void *x_perm, int32_t *expert_offsets, int32_t *slot_of, int32_t *src_of,
                     void *ws, size_t ws_bytes, void *stream);
@@ -146,7 +147,8 @@ int bigmac_grouped_ffn(const bigmac_dims *dims, const void *x_perm, const int32_
 
 /* Second All-to-All plus the weighted sum of Eq. 2: y_low[t, :] = sum_j topk_w[t, j] *
  * o_perm[slot_of[t, j], :], added in j order in fp32.  topk_w == NULL means unit weights (the
- * backward of dispatch).  y_low is [T, win] fp32. */
+ * backward of dispatch).  A pair with slot_of < 0 (dropped by the capacity) is skipped.  y_low is
+ * [T, win] fp32. */
 int bigmac_combine(const bigmac_dims *dims, const void *o_perm, const int32_t *slot_of,
                    const float *topk_w, float *y_low, void *stream);
 
