@@ -25,7 +25,14 @@
 #define BIGMAC_TILE_STAGES 3     // LDS ring stages: STAGES - 1 k tiles of global loads in flight per block
 #endif
 // Workgroups resident per CU: what the ring's LDS (16 KB a stage) leaves room for, out of 160 KB.
+#ifndef BIGMAC_BLOCKS_PER_CU
 #define BIGMAC_BLOCKS_PER_CU (BIGMAC_TILE_STAGES <= 3 ? 3 : 2)
+#endif
+// The tall tile (GemmDesc::tall_tile): twice the rows per workgroup, each wavefront a 128 x 64
+// sub-tile (128 accumulator registers), two workgroups per CU.  A third fewer operand bytes per
+// flop: what products with many tiles and a long K are short of.
+#define BIGMAC_TALL_BM (2 * BIGMAC_TILE_BM)
+#define BIGMAC_TALL_BLOCKS_PER_CU 2
 
 namespace bigmac {
 
@@ -295,7 +302,8 @@ struct TileOperands {
 // instructions in flight behind any load is then a compile-time constant, which is what the
 // counter waits below and the compiler's own ones are derived from.
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32>
-__global__ __launch_bounds__(64 * WAVES_M* WAVES_N) __attribute__((amdgpu_waves_per_eu(BIGMAC_BLOCKS_PER_CU)))
+__global__ __launch_bounds__(64 * WAVES_M* WAVES_N)
+    __attribute__((amdgpu_waves_per_eu(BM > BIGMAC_TILE_BM ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU)))
 void mfma_gemm_kernel(GemmDesc p) {
   constexpr int THREADS = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -311,7 +319,7 @@ void mfma_gemm_kernel(GemmDesc p) {
   // the counter waits written out below.
   constexpr int STAGE_CHUNKS = A_CHUNKS + B_CHUNKS;
   constexpr int STAGE_BYTES = STAGE_CHUNKS * 16;
-  static_assert(NS * STAGE_BYTES <= 65536, "fragment reads address the ring through 16-bit instruction offsets");
+  static_assert((NS - 1) * STAGE_BYTES + 8192 <= 65536, "fragment reads address the ring through 16-bit instruction offsets");
   __shared__ uint4 ring[NS * STAGE_CHUNKS];
   const unsigned ring_at = lds_address(ring);
   constexpr unsigned OUT_OF_RANGE = 0x80000000u;
@@ -852,7 +860,7 @@ __global__ void reduce_partials_multi_kernel(ReduceJobs jobs, int beta) {
   reduce_slices(j.part, j.nslices, j.n, j.out, beta, ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4);
 }
 
-int gemm_ragged_tile_rows(int dtype) { return dtype == BIGMAC_BF16 ? BIGMAC_TILE_BM : 64; }
+int gemm_ragged_tile_rows(int dtype, int tall_tile) { return dtype == BIGMAC_BF16 ? (tall_tile ? BIGMAC_TALL_BM : BIGMAC_TILE_BM) : 64; }
 
 int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* tile_map, hipStream_t s) {
   if (groups > 1024) return BIGMAC_ERR_UNSUPPORTED;
@@ -912,13 +920,14 @@ dim3 grid_for(const GemmDesc& g, bool persistent) {
   if (g.mode == GEMM_RAGGED_K) gz = g.groups;
   if (g.mode == GEMM_DENSE) gz = g.ksplit;
   long blocks = (gx * gy * gz + 7) / 8 * 8;
-  if (persistent && blocks > 256 * BIGMAC_BLOCKS_PER_CU) blocks = 256 * BIGMAC_BLOCKS_PER_CU;
+  const long resident = 256 * (BM > BIGMAC_TILE_BM ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU);
+  if (persistent && blocks > resident) blocks = resident;
   return dim3((unsigned)blocks, 1, 1);
 }
 
-template <bool AK, bool BKC>
+template <int BM, bool AK, bool BKC>
 int launch_mfma(const GemmDesc& g, hipStream_t s) {
-  constexpr int BM = BIGMAC_TILE_BM, BN = BIGMAC_TILE_BN, BK = BIGMAC_TILE_BK, WMs = BIGMAC_TILE_WM, WNs = BIGMAC_TILE_WN;
+  constexpr int BN = BIGMAC_TILE_BN, BK = BIGMAC_TILE_BK, WMs = BIGMAC_TILE_WM, WNs = BIGMAC_TILE_WN;
   dim3 grid = grid_for<BM, BN>(g, true), block(64 * WMs * WNs);
 #define BIGMAC_MFMA(EPI, OUTF32) \
   hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI, OUTF32>), grid, block, 0, s, g)
@@ -928,7 +937,10 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
       else BIGMAC_MFMA(EPI_STORE, false);
       break;
     case EPI_GELU: BIGMAC_MFMA(EPI_GELU, false); break;
-    case EPI_DGELU: BIGMAC_MFMA(EPI_DGELU, false); break;
+    case EPI_DGELU:   // (its saved-activation registers do not fit beside 128 accumulators)
+      if constexpr (BM > BIGMAC_TILE_BM) return BIGMAC_ERR_UNSUPPORTED;
+      else BIGMAC_MFMA(EPI_DGELU, false);
+      break;
     case EPI_ACCUM: BIGMAC_MFMA(EPI_ACCUM, true); break;
     default: return BIGMAC_ERR_INVALID_ARG;
   }
@@ -969,10 +981,18 @@ int launch_gemm(const GemmDesc& g, hipStream_t s) {
   if (g.mode == GEMM_DENSE && g.ksplit < 1) return BIGMAC_ERR_INVALID_ARG;
   const int combo = g.a_kcontig * 2 + g.b_kcontig;
   if (g.dtype == BIGMAC_BF16) {
+    if (g.tall_tile) {
+      switch (combo) {
+        case 2: return launch_mfma<BIGMAC_TALL_BM, true, false>(g, s);
+        case 3: return launch_mfma<BIGMAC_TALL_BM, true, true>(g, s);
+        case 0: return launch_mfma<BIGMAC_TALL_BM, false, false>(g, s);
+        default: return BIGMAC_ERR_UNSUPPORTED;
+      }
+    }
     switch (combo) {
-      case 2: return launch_mfma<true, false>(g, s);
-      case 3: return launch_mfma<true, true>(g, s);
-      case 0: return launch_mfma<false, false>(g, s);
+      case 2: return launch_mfma<BIGMAC_TILE_BM, true, false>(g, s);
+      case 3: return launch_mfma<BIGMAC_TILE_BM, true, true>(g, s);
+      case 0: return launch_mfma<BIGMAC_TILE_BM, false, false>(g, s);
       default: return BIGMAC_ERR_UNSUPPORTED;
     }
   }

@@ -46,7 +46,7 @@ struct Carver {  // hands out 256-byte aligned pieces of one buffer
 };
 
 struct SavedPlan {
-  size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, x_perm, act, hact, o_perm, y_low, logits, aux, total;
+  size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, tile_map_tall, x_perm, act, hact, o_perm, y_low, logits, aux, total;
 };
 struct FwdPlan {
   size_t logits, perm, x_low, partials, aux, total;
@@ -67,6 +67,31 @@ inline int low_ld(const bigmac_dims& D) { return bf(D) ? 2 * D.r : D.r; }
 inline int wide_ld(const bigmac_dims& D) { return widths(D).hid + (bf(D) ? 64 : 0); }
 inline size_t low_bytes(const bigmac_dims& D) { return (size_t)D.T * (bf(D) ? 2 * D.r * 2 : D.r * 4); }
 
+// Which products run on the GEMM's tall (256-row) workgroup tiles.  The per-expert products on
+// permuted rows (expert up/down, the data gradient of the first matrix): when there are enough
+// tall tiles to fill the chip a few times over, K is at least 512 and the experts hold 512 rows
+// on average (measured: 4-18 % faster at the gpt_xl to zipf_stress shapes; level or slower at
+// the gpt_medium shapes, where K = r = 256 or the tile count is low).  The per-expert weight
+// gradients: whenever their M divides into tall tiles (22-30 % faster at the large shapes, level
+// at gpt_medium).  The products over the token index have few tiles and stay on the square tile.
+inline bool tall_rows(const bigmac_dims& D, int cols, int K) {
+  if (!bf(D)) return false;
+  const long Tk = (long)D.T * D.k;
+  const long tiles = (Tk / 256 + D.N) * ((cols + 127) / 128);
+  return tiles >= 1536 && K >= 512 && Tk / D.N >= 512;
+}
+inline bool tall_wgrad(const bigmac_dims& D, int M) {   // up to a fifth of padding in M still pays
+  return bf(D) && (long)((M + 255) / 256) * 256 * 5 <= (long)M * 6;
+}
+// The shared projections and their data gradients: the same rule as for the per-expert products.
+inline bool tall_dense(const bigmac_dims& D, int M, int N, int K) {
+  return bf(D) && (long)(M / 256) * ((N + 127) / 128) >= 1024 && K >= 512;
+}
+inline bool any_tall_rows(const bigmac_dims& D) {
+  const Widths W = widths(D);
+  return tall_rows(D, W.hid, W.win) || tall_rows(D, W.win, W.hid);
+}
+
 SavedPlan plan_saved(const bigmac_dims& D) {
   const Widths W = widths(D);
   const size_t Tk = (size_t)D.T * D.k, es = esize(D.dtype);
@@ -77,7 +102,8 @@ SavedPlan plan_saved(const bigmac_dims& D) {
   p.offsets = c.take((size_t)(D.N + 1) * 4);
   p.slot_of = c.take(Tk * 4);
   p.src_of = c.take(Tk * 4);
-  p.tile_map = c.take(tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype)) * 4);
+  p.tile_map = c.take(tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype, 0)) * 4);
+  p.tile_map_tall = c.take(any_tall_rows(D) ? tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype, 1)) * 4 : 0);
   p.x_perm = c.take(Tk * W.win * es);
   p.act = c.take(Tk * wide_ld(D) * es);
   p.hact = c.take(Tk * wide_ld(D) * es);
@@ -167,7 +193,7 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
 size_t ffn_ws_bytes(const bigmac_dims& D) {
   const Widths W = widths(D);
   const size_t Tk = (size_t)D.T * D.k;
-  return align_up(Tk * W.hid * esize(D.dtype)) + align_up(tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype)) * 4);
+  return align_up(Tk * W.hid * esize(D.dtype)) + 2 * align_up(tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype, 0)) * 4);
 }
 
 template <typename ET>
@@ -194,16 +220,17 @@ GemmDesc base_desc(const bigmac_dims& D) {
 }
 
 // The two expert products on permuted rows (ragged per-expert row ranges).
-int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* offsets, const int* tile_map,
+int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* offsets, const int* tile_map, const int* tile_map_tall,
                         const void* w1, const void* w2, void* act, void* hact, int ld_wide, void* o_perm, hipStream_t s) {
   const Widths W = widths(D);
   const int Tk = D.T * D.k;
   GemmDesc g = base_desc(D);
   g.mode = GEMM_RAGGED_M;
   g.a_kcontig = 1; g.b_kcontig = 0;
-  g.groups = D.N; g.max_rows = Tk; g.offsets = offsets; g.tile_map = tile_map;
+  g.groups = D.N; g.max_rows = Tk; g.offsets = offsets;
   // hact = gelu(x_perm W1[e])
   g.epilogue = EPI_GELU;
+  g.tall_tile = tall_rows(D, W.hid, W.win); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
   g.A = x_perm; g.lda = W.win; g.K = W.win;
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
   g.C = hact; g.ldc = ld_wide; g.aux_out = act;
@@ -218,6 +245,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.A = hact; g.lda = ld_wide; g.K = W.hid;
   g.B = w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.win;
   g.C = o_perm; g.ldc = W.win;
+  g.tall_tile = tall_rows(D, W.win, W.hid); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
   BIGMAC_STAGE(BIGMAC_STAGE_EXPERT_DOWN);
   return launch_gemm(g, s);
 }
@@ -369,9 +397,11 @@ int bigmac_grouped_ffn(const bigmac_dims* D, const void* x_perm, const int32_t* 
   const size_t Tk = (size_t)D->T * D->k;
   void* hact = ws;
   int* tile_map = (int*)((char*)ws + align_up(Tk * W.hid * esize(D->dtype)));
-  rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype), tile_map, s);
+  int* tile_map_tall = (int*)((char*)tile_map + align_up(tile_map_ints((int)Tk, D->N, gemm_ragged_tile_rows(D->dtype, 0)) * 4));
+  rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype, 0), tile_map, s);
+  if (!rc && any_tall_rows(*D)) rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype, 1), tile_map_tall, s);
   if (rc) return rc;
-  return run_experts_forward(*D, x_perm, expert_offsets, tile_map, w1, w2, act_saved, hact, W.hid, o_perm, s);
+  return run_experts_forward(*D, x_perm, expert_offsets, tile_map, tile_map_tall, w1, w2, act_saved, hact, W.hid, o_perm, s);
 }
 
 int bigmac_combine(const bigmac_dims* D, const void* o_perm, const int32_t* slot_of, const float* topk_w, float* y_low, void* stream) {
@@ -401,6 +431,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   int32_t* slot_of = (int32_t*)(sv + S.slot_of);
   int32_t* src_of = (int32_t*)(sv + S.src_of);
   int* tile_map = (int*)(sv + S.tile_map);
+  int* tile_map_tall = (int*)(sv + S.tile_map_tall);
   void* x_perm = sv + S.x_perm;
   void* act = saved ? sv + S.act : nullptr;
   void* hact = sv + S.hact;
@@ -431,6 +462,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     g.C = wsb + F.x_low; g.ldc = D->r;
     BIGMAC_STAGE(BIGMAC_STAGE_DESCEND);
     g.ksplit = forward_ksplit(*D, D->T, D->r, D->d);
+    g.tall_tile = g.ksplit == 1 && tall_dense(*D, D->T, D->r, D->d);
     if (g.ksplit > 1) {   // fp32 partials, then one rounding to bf16
       g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->r;
       rc = launch_gemm(g, s);
@@ -446,15 +478,19 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     BIGMAC_STAGE(BIGMAC_STAGE_PERMUTATION);
     rc = launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s);
     if (rc) return rc;
-    rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype), tile_map, s);
+    rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype, 0), tile_map, s);
     if (rc) return rc;
+    if (any_tall_rows(*D)) {
+      rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype, 1), tile_map_tall, s);
+      if (rc) return rc;
+    }
   }
   {
     BIGMAC_STAGE(BIGMAC_STAGE_DISPATCH);
     rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);
   }
   if (rc) return rc;
-  rc = run_experts_forward(*D, x_perm, offsets, tile_map, P->w1, P->w2, act, hact, wide_ld(*D), o_perm, s);
+  rc = run_experts_forward(*D, x_perm, offsets, tile_map, tile_map_tall, P->w1, P->w2, act, hact, wide_ld(*D), o_perm, s);
   if (rc) return rc;
   if (!dcca) {  // fine-grained layer: the weighted sum is the output
     BIGMAC_STAGE(BIGMAC_STAGE_COMBINE);
@@ -473,6 +509,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     g.C = y; g.ldc = D->d;
     BIGMAC_STAGE(BIGMAC_STAGE_ASCEND);
     g.ksplit = forward_ksplit(*D, D->T, D->d, low_ld(*D));
+    g.tall_tile = g.ksplit == 1 && tall_dense(*D, D->T, D->d, low_ld(*D));
     if (g.ksplit > 1) {
       g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->d;
       rc = launch_gemm(g, s);
@@ -508,6 +545,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   const int32_t* offsets = (const int32_t*)(sv + S.offsets);
   const int32_t* slot_of = (const int32_t*)(sv + S.slot_of);
   const int* tile_map = (const int*)(sv + S.tile_map);
+  const int* tile_map_tall = (const int*)(sv + S.tile_map_tall);
   const void* x_perm = sv + S.x_perm;
   const void* act = sv + S.act;
   const void* hact = sv + S.hact;
@@ -535,6 +573,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = dy; g.lda = D->d; g.M = D->T; g.K = D->d;
     g.B = P->w_up; g.ldb = D->d; g.N = D->r;
     g.C = dy_low; g.ldc = D->r;
+    g.tall_tile = tall_dense(*D, D->T, D->r, D->d);
     {
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_ASCEND_DGRAD);
       rc = launch_gemm(g, s);
@@ -574,6 +613,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = hact; g.lda = wide_ld(*D); g.M = W.hid;
     g.B = do_perm; g.ldb = W.win; g.N = W.win;
     g.C = d_w2; g.ldc = W.win; g.gstride_c = (long)W.hid * W.win;
+    g.tall_tile = tall_wgrad(*D, W.hid);
     {
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_WGRAD);
       rc = launch_gemm(g, s);
@@ -583,6 +623,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = x_perm; g.lda = W.win; g.M = W.win;
     g.B = dact; g.ldb = wide_ld(*D); g.N = W.hid;
     g.C = d_w1; g.ldc = W.hid; g.gstride_c = (long)W.win * W.hid;
+    g.tall_tile = tall_wgrad(*D, W.win);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_WGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
@@ -594,6 +635,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = dact; g.lda = wide_ld(*D); g.K = W.hid;
     g.B = P->w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.win;
     g.C = dx_perm; g.ldc = W.win;
+    g.tall_tile = tall_rows(*D, W.win, W.hid); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
@@ -625,6 +667,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
       g.A = dx_low; g.lda = low_ld(*D); g.M = D->T; g.K = low_ld(*D);
       g.B = P->w_down; g.ldb = D->r; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
       g.C = dx_f32; g.ldc = D->d;
+      g.tall_tile = tall_dense(*D, D->T, D->d, low_ld(*D));
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_DGRAD);
       rc = launch_gemm(g, s);
       if (rc) return rc;

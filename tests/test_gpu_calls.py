@@ -149,6 +149,10 @@ FFN_CASES = [
     (500, 256, 192, 24, 8, B.BF16, B.ORDER_DCCA),
     (200, 64, 128, 8, 2, B.F32, B.ORDER_DCCA),
     (260, 64, 64, 8, 4, B.BF16, B.ORDER_CDAC),      # expert d=256 -> r=64 -> d
+    # enough rows, tiles and K for the 256-row workgroup tiles: first product tall, second not ...
+    (2560, 512, 2048, 16, 8, B.BF16, B.ORDER_DCCA),
+    # ... and the other way round
+    (5120, 1024, 512, 32, 8, B.BF16, B.ORDER_DCCA),
 ]
 
 
