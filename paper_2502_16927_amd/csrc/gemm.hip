@@ -658,13 +658,13 @@ void mfma_gemm_kernel(GemmDesc p) {
             for (int vr = 0; vr < 4; ++vr) v[vr] = acc[i][j][vq * 4 + vr];
             if (EPI == EPI_GELU) {
 #pragma unroll
-              for (int vr = 0; vr < 4; ++vr) v[vr] = gelu_f(v[vr]);
+              for (int vr = 0; vr < 4; ++vr) v[vr] = gelu_bf16_f(v[vr]);
             } else if (EPI == EPI_DGELU) {
               const u32x2_t sv = pre[(i * TN + j) * 4 + vq];
-              v[0] *= gelu_grad_f(__uint_as_float(sv.x << 16));
-              v[1] *= gelu_grad_f(__uint_as_float(sv.x & 0xFFFF0000u));
-              v[2] *= gelu_grad_f(__uint_as_float(sv.y << 16));
-              v[3] *= gelu_grad_f(__uint_as_float(sv.y & 0xFFFF0000u));
+              v[0] *= gelu_grad_bf16_f(__uint_as_float(sv.x << 16));
+              v[1] *= gelu_grad_bf16_f(__uint_as_float(sv.x & 0xFFFF0000u));
+              v[2] *= gelu_grad_bf16_f(__uint_as_float(sv.y << 16));
+              v[3] *= gelu_grad_bf16_f(__uint_as_float(sv.y & 0xFFFF0000u));
             }
             u32x2_t w;
             w.x = f2bf_pair(v[0], v[1]);
