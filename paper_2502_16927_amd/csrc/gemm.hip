@@ -5,6 +5,7 @@
 // in the same orientation they have in memory (so global reads are row-contiguous for every
 // transposition) with XOR swizzles against bank conflicts; operands whose contraction index is
 // not the fast one in memory are fetched with the gfx950 LDS transpose read (ds_read_b64_tr_b16).
+// Two workgroup tiles, 128 x 128 and 256 x 128, the latter for products with many tiles and a long K.
 // fp32 storage: a plain tiled FMA kernel (only the tiny fp32 workload uses it).
 #include "common.hpp"
 
