@@ -148,19 +148,28 @@ FwdPlan plan_fwd(const bigmac_dims& D) {
   return p;
 }
 
+// The weight gradients over the token index take the tall tile when there are enough tall
+// tiles and enough tokens to be worth it (measured: zipf_stress, T = 32768, d = 4096: 0.34 ->
+// 0.25 ms and 0.38 -> 0.28 ms; at T = 8192 with the same widths level or slower).
+inline bool tall_token_wgrad(const bigmac_dims& D, int M, int N) {
+  return bf(D) && M % 256 == 0 && (long)(M / 256) * ((N + 127) / 128) >= 128 && D.T >= 16384;
+}
 // Slices of K for a weight gradient over the token index (few output tiles, K = T).  More slices
 // fill more of the chip but write and read back more fp32 partials; the count is the power of
 // two (slices of at least 256 rows) with the lowest estimate of product + reduction time:
 // rounds of 768 resident workgroups x k tiles per slice x 0.6 us (measured per k tile of 32)
 // + partial bytes, written and read once, at 5 TB/s.
-int choose_ksplit(int M, int N, int K) {
-  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+// (On the tall tile: 512 resident workgroups, 0.85 us per k tile.)
+int choose_ksplit(int M, int N, int K, bool tall = false) {
+  const long tiles = (long)((M + (tall ? 255 : 127)) / (tall ? 256 : 128)) * ((N + 127) / 128);
+  const long resident = tall ? 512 : 768;
+  const double k_tile_us = tall ? 0.85 : 0.6;
   const double partial_us = (double)M * N * 4 * 2 / 5e6;
   int best = 1;
   double best_us = 1e30;
   for (int ks = 1; ks <= 64 && K / ks >= 256; ks *= 2) {
-    const long rounds = (tiles * ks + 767) / 768;
-    const double us = rounds * ((K / ks + 31) / 32) * 0.6 + (ks > 1 ? ks * partial_us : 0.0);
+    const long rounds = (tiles * ks + resident - 1) / resident;
+    const double us = rounds * ((K / ks + 31) / 32) * k_tile_us + (ks > 1 ? ks * partial_us : 0.0);
     if (us <= best_us * 1.05) { best_us = us < best_us ? us : best_us; best = ks; }   // near ties go to more workgroups
   }
   return best;
@@ -182,9 +191,9 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
   p.dx_f32 = c.take((bf(D) && (D.flags & BIGMAC_FLAG_OUT_BF16)) ? (size_t)D.T * D.d * 4 : 0);
   // split-K partials of the three weight gradients over the token index: one region each, so
   // that one launch at the end can reduce all three
-  p.part_gate = c.take((size_t)choose_ksplit(D.d, D.N, D.T) * D.d * D.N * 4);
-  p.part_up = c.take(dcca ? (size_t)choose_ksplit(D.r, D.d, D.T) * D.r * D.d * 4 : 0);
-  p.part_down = c.take(dcca ? (size_t)choose_ksplit(D.d, D.r, D.T) * D.d * D.r * 4 : 0);
+  p.part_gate = c.take((size_t)choose_ksplit(D.d, D.N, D.T, tall_token_wgrad(D, D.d, D.N)) * D.d * D.N * 4);
+  p.part_up = c.take(dcca ? (size_t)choose_ksplit(D.r, D.d, D.T, tall_token_wgrad(D, D.r, D.d)) * D.r * D.d * 4 : 0);
+  p.part_down = c.take(dcca ? (size_t)choose_ksplit(D.d, D.r, D.T, tall_token_wgrad(D, D.d, D.r)) * D.d * D.r * 4 : 0);
   p.tmp_f32 = 0;
   p.total = c.off;
   return p;
@@ -258,7 +267,8 @@ int run_token_wgrad(const bigmac_dims& D, const void* A, long lda, int M, const 
   g.a_kcontig = 0; g.b_kcontig = 0;
   g.epilogue = EPI_ACCUM; g.beta = 0;
   g.A = A; g.lda = lda; g.M = M; g.B = B; g.ldb = ldb; g.N = N; g.K = D.T;
-  g.ksplit = choose_ksplit(M, N, D.T);
+  g.tall_tile = tall_token_wgrad(D, M, N);
+  g.ksplit = choose_ksplit(M, N, D.T, g.tall_tile);
   g.C = partials; g.ldc = N; g.gstride_c = (long)M * N;
   job->part = partials; job->out = out; job->n = (size_t)M * N; job->nslices = g.ksplit;
   return launch_gemm(g, s);
