@@ -445,9 +445,12 @@ void mfma_gemm_kernel(GemmDesc p) {
   };
   // EPI_DGELU multiplies by act'(saved pre-activation): that tile is requested one tile ahead
   // (row layout: 8 lanes per 64-column row, 8 rows per pass) and used in the epilogue
-  constexpr int AUX_LOADS = EPI == EPI_DGELU ? TM * 4 : 0;
-  uint4 aux[EPI == EPI_DGELU ? TM * 4 : 1];
-  auto request_aux = [&](const TileCoord& t) {
+  // On the tall tile (TM = 4) the saved tile passes through in two halves of TMH sub-tiles: its
+  // registers and those of its quad form would not fit beside 128 accumulators otherwise.
+  constexpr int HALVES = (EPI == EPI_DGELU && TM > 2) ? 2 : 1;
+  constexpr int TMH = TM / HALVES;
+  uint4 aux[EPI == EPI_DGELU ? TMH * 4 : 1];
+  auto request_aux = [&](const TileCoord& t, int half) {
     if (EPI == EPI_DGELU) {
       const __amdgpu_buffer_rsrc_t ra = rows_of(t, p.aux_in, 2);
       const int col = t.n0 + wn + (lane & 7) * 8;
@@ -456,11 +459,11 @@ void mfma_gemm_kernel(GemmDesc p) {
       const unsigned past_n = ((unsigned)(p.N - 1 - col) >> 31) * OUT_OF_RANGE;
       // One offset register, the passes 8 rows apart added per load: the empty statement keeps
       // the compiler from carrying all the per-pass offsets across tiles in registers of their own.
-      unsigned first = (unsigned)(((size_t)(wm + (lane >> 3)) * p.ldc + col) * 2) | past_n;
+      unsigned first = (unsigned)(((size_t)(wm + half * TMH * 32 + (lane >> 3)) * p.ldc + col) * 2) | past_n;
       asm volatile("" : "+v"(first));
       const unsigned pass_step = (unsigned)(8 * p.ldc * 2);
 #pragma unroll
-      for (int c = 0; c < TM * 4; ++c)
+      for (int c = 0; c < TMH * 4; ++c)
         aux[c] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(ra, first + (unsigned)c * pass_step, 0, NON_TEMPORAL));
     }
   };
@@ -476,7 +479,7 @@ void mfma_gemm_kernel(GemmDesc p) {
   if (id < 0) return;
   TileOperands cur = operands(id);
   prefetch(cur);
-  request_aux(cur.t);
+  request_aux(cur.t, 0);
 
   while (true) {
     const TileCoord t = cur.t;
@@ -571,10 +574,12 @@ void mfma_gemm_kernel(GemmDesc p) {
     // EPI_DGELU: turn the saved pre-activation from its row layout into the accumulators' quad
     // layout now; its registers are then free for the next tile's request, which goes out ahead
     // of the prefetch and is therefore complete whenever a k tile of that prefetch is.
-    u32x2_t pre[EPI == EPI_DGELU ? TM * TN * 4 : 1];
-    if (EPI == EPI_DGELU) {
+    // (Tall tile: the first half now, with the second half requested in its place; the second half
+    // is turned, and the next tile's first half requested, between the two halves of the epilogue.)
+    u32x2_t pre[EPI == EPI_DGELU ? TMH * TN * 4 : 1];
+    auto turn_aux = [&]() {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < TMH; ++i) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) lds_write_b128(row_at + q * 8 * SROW, __builtin_bit_cast(u32x4_t, aux[i * 4 + q]));
 #pragma unroll
@@ -583,7 +588,11 @@ void mfma_gemm_kernel(GemmDesc p) {
           for (int vq = 0; vq < 4; ++vq) lds_read_b64(quad_at(j, vq), pre[(i * TN + j) * 4 + vq]);
       }
       lds_wait(pre);
-      request_aux(nxt.t);
+    };
+    if (EPI == EPI_DGELU) {
+      turn_aux();
+      if (HALVES == 2) request_aux(t, 1);
+      else request_aux(nxt.t, 0);
     }
     prefetch(nxt);
 
@@ -638,6 +647,10 @@ void mfma_gemm_kernel(GemmDesc p) {
       };
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
+        if (EPI == EPI_DGELU && HALVES == 2 && i == TMH) {
+          turn_aux();
+          request_aux(nxt.t, 0);
+        }
         if (EPI == EPI_GELU && p.aux_out) {   // the pre-activation itself, for the backward pass
 #pragma unroll
           for (int j = 0; j < TN; ++j)
@@ -661,7 +674,7 @@ void mfma_gemm_kernel(GemmDesc p) {
 #pragma unroll
               for (int vr = 0; vr < 4; ++vr) v[vr] = gelu_bf16_f(v[vr]);
             } else if (EPI == EPI_DGELU) {
-              const u32x2_t sv = pre[(i * TN + j) * 4 + vq];
+              const u32x2_t sv = pre[((i % TMH) * TN + j) * 4 + vq];
               v[0] *= gelu_grad_bf16_f(__uint_as_float(sv.x << 16));
               v[1] *= gelu_grad_bf16_f(__uint_as_float(sv.x & 0xFFFF0000u));
               v[2] *= gelu_grad_bf16_f(__uint_as_float(sv.y << 16));
@@ -938,10 +951,7 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
       else BIGMAC_MFMA(EPI_STORE, false);
       break;
     case EPI_GELU: BIGMAC_MFMA(EPI_GELU, false); break;
-    case EPI_DGELU:   // (its saved-activation registers do not fit beside 128 accumulators)
-      if constexpr (BM > BIGMAC_TILE_BM) return BIGMAC_ERR_UNSUPPORTED;
-      else BIGMAC_MFMA(EPI_DGELU, false);
-      break;
+    case EPI_DGELU: BIGMAC_MFMA(EPI_DGELU, false); break;
     case EPI_ACCUM: BIGMAC_MFMA(EPI_ACCUM, true); break;
     default: return BIGMAC_ERR_INVALID_ARG;
   }

@@ -612,6 +612,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = do_perm; g.lda = W.win; g.K = W.win;
     g.B = P->w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.hid;
     g.C = dact; g.ldc = wide_ld(*D); g.aux_in = act;
+    g.tall_tile = tall_rows(*D, W.hid, W.win); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;

@@ -24,6 +24,9 @@ SMALL = [
     dict(T=1, d=64, r=64, N=8, k=1, h=64, dtype=B.BF16),
     dict(T=200, d=768, r=256, N=8, k=2, h=128, dtype=B.BF16),   # few tiles, long K: the shared projections split K
     dict(T=130, d=128, r=64, N=8, k=3, h=192, dtype=B.F32, x_std=0.5),
+    # enough rows, tiles and K for the 256-row workgroup tiles in expert-up and the GELU' product
+    # (not in expert-down and its counterpart, which have 4 column tiles): both tile maps in one step
+    dict(T=2560, d=512, r=512, N=16, k=8, h=2048, dtype=B.BF16),
 ]
 
 
