@@ -240,6 +240,33 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict_
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
+  if constexpr (PER == 1) {
+    // Up to 64 experts: one logit per lane, sorted across the wavefront by a bitonic network under
+    // the same order (greater logit first, equal logits by lower index: a strict total order, so
+    // the result is the unique sorted sequence); lanes 0 .. k-1 then hold the picks in pick order.
+    float mv = lane < N ? logits[(size_t)t * N + lane] : -INFINITY;
+    int mi = lane;
+#pragma unroll
+    for (int size = 2; size <= 64; size <<= 1) {
+#pragma unroll
+      for (int j = size >> 1; j > 0; j >>= 1) {
+        const float ov = __shfl_xor(mv, j, 64);
+        const int oi = __shfl_xor(mi, j, 64);
+        const bool mine_first = mv > ov || (mv == ov && mi < oi);
+        const bool want_first = ((lane & j) == 0) == ((lane & size) == 0);   // lower lane of an ascending block
+        if (mine_first != want_first) { mv = ov; mi = oi; }
+      }
+    }
+    const float m = __shfl(mv, 0, 64);
+    const float e = lane < k ? expf(mv - m) : 0.0f;
+    float s = 0.0f;
+    for (int j = 0; j < k; ++j) s += __shfl(e, j, 64);
+    if (lane < k) {
+      topk_idx[(size_t)t * k + lane] = mi;
+      topk_w[(size_t)t * k + lane] = e / s;
+    }
+    return;
+  }
   float v[PER];
   int rank[PER];
 #pragma unroll
