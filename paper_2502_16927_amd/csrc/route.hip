@@ -13,6 +13,16 @@ namespace {
 constexpr int R_TB = 8;     // tokens per wave
 constexpr int R_NB = 16;    // experts per pass
 constexpr int R_QT = 4;     // 64-row blocks of W_g staged per LDS tile
+constexpr int ROUTER_DX_PICKS = 1024;   // (token, pick) pairs a workgroup of the router's dx kernel stages
+#ifndef ROUTER_DX_CPL
+#define ROUTER_DX_CPL 4                 // output columns per lane of that kernel (N <= 64; half of it above)
+#endif
+#ifndef ROUTER_DX_THREADS
+#define ROUTER_DX_THREADS 1024
+#endif
+#ifndef ROUTER_DX_TOKENS
+#define ROUTER_DX_TOKENS 128
+#endif
 constexpr int R_PAD = 20;   // floats per staged row (16 + 4: conflict-free 16-byte reads)
 
 // Block = 4 wavefronts x 8 tokens, one pass of 16 experts (blockIdx.y); the 16 router columns are
@@ -456,7 +466,8 @@ template <typename DT, int PER>
 __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
                                                             const float* __restrict__ dgate, const float* __restrict__ wg_t /*[N,d]*/,
                                                             const float* __restrict__ logits, const float* __restrict__ share, float aux_scale,
-                                                            DT* __restrict__ dL, float* __restrict__ dx, int T, int d, int N, int k) {
+                                                            DT* __restrict__ dL, float* __restrict__ dx, float* __restrict__ dl_picked,
+                                                            int T, int d, int N, int k) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -474,6 +485,7 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __res
   float mix = 0.0f;
   for (int j = 0; j < k; ++j) mix = fmaf(__shfl(w, j, 64), __shfl(g, j, 64), mix);
   const float dl = w * (g - mix);
+  if (dl_picked && lane < k) dl_picked[(size_t)t * k + lane] = dl;
   // every lane takes part in the shuffles (uniform trip counts); only loads and stores are guarded
 #pragma unroll
   for (int i = 0; i < PER; ++i) {        // dense row of dL: the k picked experts, zeros (or the loss term) elsewhere
@@ -517,6 +529,96 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const int32_t* __res
       }
     }
     if (c < d) *(float4*)(dx + (size_t)t * d + c) = acc;
+  }
+}
+
+// The router's share of dx without the loss:  dx[t, c] = sum_j dl[t, j] w_gate[c, e_j].  A
+// workgroup keeps CPL*64 rows of w_gate, transposed (wt[n][c]: one expert's weights for the
+// workgroup's columns lie side by side), and its tokens' picks in the LDS, so each pick costs a
+// lane one LDS read of its CPL adjacent columns instead of a cached global row.
+template <int CPL, int NMAX>
+__global__ __launch_bounds__(ROUTER_DX_THREADS) void router_dx_kernel(const int32_t* __restrict__ topk_idx, const float* __restrict__ dl_picked,
+                                                        const float* __restrict__ w_gate /*[d,N]*/, float* __restrict__ dx,
+                                                        int T, int d, int N, int k, int tokens_per_block) {
+  constexpr int TC = CPL * 64, PITCH = TC + 4;
+  constexpr int PER_THREAD = TC * NMAX / 4 / ROUTER_DX_THREADS, BATCH = PER_THREAD > 8 ? 8 : (PER_THREAD < 1 ? 1 : PER_THREAD);
+  typedef float cols_t __attribute__((ext_vector_type(CPL)));
+  __shared__ __attribute__((aligned(16))) float wt[NMAX * PITCH];
+  __shared__ float s_dl[ROUTER_DX_PICKS];
+  __shared__ int s_e[ROUTER_DX_PICKS];
+  const int c0 = blockIdx.x * TC;
+  const int t_beg = blockIdx.y * tokens_per_block, t_end = min(T, t_beg + tokens_per_block);
+  // the picks are requested first and stored last, so that their latency hides behind the rows
+  constexpr int PICK_LOADS = (ROUTER_DX_PICKS + ROUTER_DX_THREADS - 1) / ROUTER_DX_THREADS;
+  const int picks_here = (t_end - t_beg) * k;
+  float pick_dl[PICK_LOADS];
+  int pick_e[PICK_LOADS];
+#pragma unroll
+  for (int u = 0; u < PICK_LOADS; ++u) {
+    const size_t at = (size_t)t_beg * k + min(u * ROUTER_DX_THREADS + (int)threadIdx.x, picks_here - 1);
+    pick_dl[u] = dl_picked[at];
+    pick_e[u] = topk_idx[at];
+  }
+  if ((N & 3) == 0) {
+    // the rows are one contiguous piece of w_gate: 16-byte loads, a batch in flight per lane;
+    // rows past d are clamped to the last one (their outputs are never stored)
+    const int qrow = N >> 2, quads = TC * qrow, last = (d - 1 - c0) * qrow + qrow - 1;
+    const float4* src = (const float4*)(w_gate + (size_t)c0 * N);
+    for (int i0 = 0; i0 < quads; i0 += ROUTER_DX_THREADS * BATCH) {
+      float4 v[BATCH];
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u) v[u] = src[min(min(i0 + u * ROUTER_DX_THREADS + (int)threadIdx.x, quads - 1), last)];
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u) {
+        const int i = i0 + u * ROUTER_DX_THREADS + (int)threadIdx.x;
+        if (i < quads) {
+          const int c = i / qrow, n = (i - c * qrow) * 4;
+          float* dst = wt + n * PITCH + c;
+          dst[0] = v[u].x; dst[PITCH] = v[u].y; dst[2 * PITCH] = v[u].z; dst[3 * PITCH] = v[u].w;
+        }
+      }
+    }
+  } else {
+    for (int i = threadIdx.x; i < TC * N; i += ROUTER_DX_THREADS) {
+      const int c = i / N, n = i - c * N;
+      wt[n * PITCH + c] = c0 + c < d ? w_gate[(size_t)(c0 + c) * N + n] : 0.0f;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < PICK_LOADS; ++u) {
+    const int i = u * ROUTER_DX_THREADS + (int)threadIdx.x;
+    if (i < picks_here) { s_dl[i] = pick_dl[u]; s_e[i] = pick_e[u]; }
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float* mine = wt + lane * CPL;
+  for (int t = t_beg + wave; t < t_end; t += ROUTER_DX_THREADS / 64) {
+    const int base = (t - t_beg) * k;
+    // lane j holds pick j (k <= 64); every lane then reads them back one by one
+    const int at = base + min(lane, k - 1);
+    const int dl_bits = __float_as_int(s_dl[at]), e_mine = s_e[at];
+    cols_t acc = 0.0f;
+    // U picks at a time: their LDS reads are independent, the sums keep the order j = 0, 1, ...
+    auto picks = [&](auto width, int j) {
+      constexpr int U = decltype(width)::value;
+      float dj[U];
+      cols_t w[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        dj[u] = __int_as_float(__builtin_amdgcn_readlane(dl_bits, j + u));
+        w[u] = *(const cols_t*)(mine + __builtin_amdgcn_readlane(e_mine, j + u) * PITCH);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int q = 0; q < CPL; ++q) acc[q] = fmaf(dj[u], w[u][q], acc[q]);
+    };
+    int j = 0;
+    for (; j + 8 <= k; j += 8) picks(std::integral_constant<int, 8>{}, j);
+    if (j + 4 <= k) { picks(std::integral_constant<int, 4>{}, j); j += 4; }
+    for (; j < k; ++j) picks(std::integral_constant<int, 1>{}, j);
+    const int c = c0 + lane * CPL;
+    if (c < d) *(cols_t*)(dx + (size_t)t * d + c) = acc;
   }
 }
 
@@ -568,7 +670,8 @@ int launch_topk_gate(const bigmac_dims& D, const float* logits, int32_t* topk_id
 }
 
 size_t route_backward_ws_bytes(const bigmac_dims& D) {
-  return align_up((size_t)D.N * D.d * sizeof(float));  // transposed router weights
+  // transposed router weights, or the picked entries of dL
+  return align_up(std::max((size_t)D.N * D.d, (size_t)D.T * D.k) * sizeof(float));
 }
 
 __global__ void router_to_bf16_kernel(const float* __restrict__ in, bf16_t* __restrict__ out, size_t n) {
@@ -583,8 +686,11 @@ int launch_route_backward(const bigmac_dims& D, const float* w_gate, const int32
   // product dL w_gate^T: on bf16 runs it goes to the matrix cores (dL is stored in bf16 anyway,
   // w_gate is rounded to bf16 for this product only); otherwise the kernel walks all N rows.
   const bool by_product = logits && D.dtype == BIGMAC_BF16 && D.N % 32 == 0;   // N is the product's K: whole k tiles
+  const bool tiled = !logits && D.N <= 128 && D.k <= 64 && D.d % 4 == 0;         // w_gate rows fit the LDS tile
   float* wg_t = (float*)ws;
-  if (by_product) {
+  if (tiled) {
+    // nothing to prepare: the second kernel reads w_gate as it lies
+  } else if (by_product) {
     const size_t n = (size_t)D.d * D.N;
     hipLaunchKernelGGL(router_to_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w_gate, (bf16_t*)ws, n);
   } else {
@@ -594,10 +700,11 @@ int launch_route_backward(const bigmac_dims& D, const float* w_gate, const int32
   const dim3 grid((D.T + 3) / 4), block(256);
   const float aux_scale = logits ? D.aux_alpha * (float)D.N / (float)D.T : 0.0f;
   const int per = (D.N + 63) / 64;
-  float* dx_kernel = by_product ? nullptr : dx_f32;
+  float* dx_kernel = by_product || tiled ? nullptr : dx_f32;
+  float* dl_picked = tiled ? (float*)ws : nullptr;
 #define BIGMAC_GATE_BWD(DT, P)                                                                                          \
   hipLaunchKernelGGL((gate_backward_kernel<DT, P>), grid, block, 0, s, topk_idx, topk_w, dgate, wg_t, logits, share, aux_scale, \
-                     (DT*)dL_out, dx_kernel, D.T, D.d, D.N, D.k)
+                     (DT*)dL_out, dx_kernel, dl_picked, D.T, D.d, D.N, D.k)
 #define BIGMAC_GATE_BWD_PER(DT)          \
   if (per <= 1) BIGMAC_GATE_BWD(DT, 1);  \
   else if (per <= 2) BIGMAC_GATE_BWD(DT, 2); \
@@ -612,6 +719,22 @@ int launch_route_backward(const bigmac_dims& D, const float* w_gate, const int32
 #undef BIGMAC_GATE_BWD_PER
 #undef BIGMAC_GATE_BWD
   BIGMAC_CHECK_LAUNCH();
+  if (tiled) {
+    // tokens per workgroup: as many as the staging holds, fewer while the grid would leave CUs idle
+    const int width = D.N <= 64 ? ROUTER_DX_CPL * 64 : ROUTER_DX_CPL * 32;
+    const unsigned gx = (unsigned)((D.d + width - 1) / width);
+    int tokens = std::min(ROUTER_DX_TOKENS, ROUTER_DX_PICKS / D.k);
+    while (tokens > 16 && (long)gx * ((D.T + tokens - 1) / tokens) < 256) tokens /= 2;
+    const dim3 grid_dx(gx, (unsigned)((D.T + tokens - 1) / tokens));
+    if (D.N <= 64)
+      hipLaunchKernelGGL((router_dx_kernel<ROUTER_DX_CPL, 64>), grid_dx, dim3(ROUTER_DX_THREADS), 0, s,
+                         topk_idx, dl_picked, w_gate, dx_f32, D.T, D.d, D.N, D.k, tokens);
+    else
+      hipLaunchKernelGGL((router_dx_kernel<ROUTER_DX_CPL / 2, 128>), grid_dx, dim3(ROUTER_DX_THREADS), 0, s,
+                         topk_idx, dl_picked, w_gate, dx_f32, D.T, D.d, D.N, D.k, tokens);
+    BIGMAC_CHECK_LAUNCH();
+    return BIGMAC_OK;
+  }
   if (by_product) {   // dx_f32[T, d] = dL[T, N] . w_gate[d, N]^T
     GemmDesc g = {};
     g.dtype = BIGMAC_BF16; g.mode = GEMM_DENSE; g.ksplit = 1;
