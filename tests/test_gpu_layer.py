@@ -27,6 +27,14 @@ SMALL = [
     # enough rows, tiles and K for the 256-row workgroup tiles in expert-up and the GELU' product
     # (not in expert-down and its counterpart, which have 4 column tiles): both tile maps in one step
     dict(T=2560, d=512, r=512, N=16, k=8, h=2048, dtype=B.BF16),
+    # the router's share of dx: 65..128 experts (narrower LDS tile), N % 4 != 0 (scalar tile fill),
+    # k = 8 + 4 + 1 picks, k = 64 (staging limit), d not a multiple of the tile width, and more than
+    # 128 experts (per-token kernel on a transposed copy of the router weights)
+    dict(T=300, d=192, r=64, N=96, k=5, h=64, dtype=B.BF16),
+    dict(T=130, d=128, r=64, N=6, k=3, h=64, dtype=B.F32, x_std=0.5),
+    dict(T=200, d=320, r=64, N=64, k=13, h=64, dtype=B.BF16),
+    dict(T=70, d=128, r=64, N=128, k=64, h=64, dtype=B.BF16),
+    dict(T=90, d=128, r=64, N=200, k=4, h=64, dtype=B.BF16),
 ]
 
 
