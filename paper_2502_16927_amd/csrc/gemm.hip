@@ -304,7 +304,7 @@ struct TileOperands {
 // counter waits below and the compiler's own ones are derived from.
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32>
 __global__ __launch_bounds__(64 * WAVES_M* WAVES_N)
-    __attribute__((amdgpu_waves_per_eu(BM > BIGMAC_TILE_BM ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU)))
+    __attribute__((amdgpu_waves_per_eu(BM > BIGMAC_TILE_BM || BK > BIGMAC_TILE_BK ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU)))
 void mfma_gemm_kernel(GemmDesc p) {
   constexpr int THREADS = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -960,6 +960,20 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
   return BIGMAC_OK;
 }
 
+// Few output tiles under a long K (the shared projections onto the narrow width): twice the
+// tiles and half the k steps.  128 x 64 outputs, 64-deep k tiles, four wavefronts stacked in M
+// (each 32 x 64: the bf16 epilogue's strip), 72 KB of ring: two workgroups per CU.
+template <bool BKC>
+int launch_mfma_deep(const GemmDesc& g, hipStream_t s) {
+  constexpr int BM = 128, BN = 64, BK = 64;
+  dim3 grid = grid_for<BM, BN>(g, false), block(256);
+  if (grid.x > 512) grid.x = 512;
+  if (g.out_f32) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 4, 1, true, BKC, EPI_STORE, true>), grid, block, 0, s, g);
+  else hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 4, 1, true, BKC, EPI_STORE, false>), grid, block, 0, s, g);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
 template <bool AK, bool BKC>
 int launch_fma(const GemmDesc& g, hipStream_t s) {
   dim3 grid = grid_for<64, 64>(g, false), block(256);
@@ -992,6 +1006,10 @@ int launch_gemm(const GemmDesc& g, hipStream_t s) {
   if (g.mode == GEMM_DENSE && g.ksplit < 1) return BIGMAC_ERR_INVALID_ARG;
   const int combo = g.a_kcontig * 2 + g.b_kcontig;
   if (g.dtype == BIGMAC_BF16) {
+    if (g.deep_tile) {
+      if (g.mode != GEMM_DENSE || g.epilogue != EPI_STORE || !g.a_kcontig || g.K % 64 || g.tall_tile) return BIGMAC_ERR_INVALID_ARG;
+      return g.b_kcontig ? launch_mfma_deep<true>(g, s) : launch_mfma_deep<false>(g, s);
+    }
     if (g.tall_tile) {
       switch (combo) {
         case 2: return launch_mfma<BIGMAC_TALL_BM, true, false>(g, s);

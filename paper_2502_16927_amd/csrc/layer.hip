@@ -34,6 +34,9 @@ struct StageTimer {  // records the caller's events around the launches of one s
     if (g_stage_events) (void)hipEventRecord((hipEvent_t)g_stage_events[2 * stage + 1], s);
   }
 };
+#ifndef BIGMAC_DEEP_MAX_TILES
+#define BIGMAC_DEEP_MAX_TILES 256   // 128 x 128 tiles (one per CU) up to which a dense product takes the 128 x 64 x 64 tile
+#endif
 #define BIGMAC_STAGE(stage) StageTimer stage_timer_##stage(s, stage)
 
 struct Carver {  // hands out 256-byte aligned pieces of one buffer
@@ -86,6 +89,10 @@ inline bool tall_wgrad(const bigmac_dims& D, int M) {   // up to a fifth of padd
 // The shared projections and their data gradients: the same rule as for the per-expert products.
 inline bool tall_dense(const bigmac_dims& D, int M, int N, int K) {
   return bf(D) && (long)(M / 256) * ((N + 127) / 128) >= 1024 && K >= 512;
+}
+// Few 128 x 128 tiles under a long K: the narrower tile with deeper k tiles (see launch_gemm).
+inline bool deep_dense(const bigmac_dims& D, int M, int N, int K) {
+  return bf(D) && K % 64 == 0 && K >= 512 && (long)((M + 127) / 128) * ((N + 127) / 128) <= BIGMAC_DEEP_MAX_TILES;
 }
 inline bool any_tall_rows(const bigmac_dims& D) {
   const Widths W = widths(D);
@@ -473,6 +480,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     BIGMAC_STAGE(BIGMAC_STAGE_DESCEND);
     g.ksplit = forward_ksplit(*D, D->T, D->r, D->d);
     g.tall_tile = g.ksplit == 1 && tall_dense(*D, D->T, D->r, D->d);
+    g.deep_tile = g.ksplit == 1 && !g.tall_tile && deep_dense(*D, D->T, D->r, D->d);
     if (g.ksplit > 1) {   // fp32 partials, then one rounding to bf16
       g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->r;
       rc = launch_gemm(g, s);
@@ -584,6 +592,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.B = P->w_up; g.ldb = D->d; g.N = D->r;
     g.C = dy_low; g.ldc = D->r;
     g.tall_tile = tall_dense(*D, D->T, D->r, D->d);
+    g.deep_tile = !g.tall_tile && deep_dense(*D, D->T, D->r, D->d);
     {
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_ASCEND_DGRAD);
       rc = launch_gemm(g, s);
