@@ -536,7 +536,10 @@ void mfma_gemm_kernel(GemmDesc p) {
         constexpr int READS_PER_STEP = (AK ? TM : 2 * TM) + (BKC ? TN : 2 * TN);
         static_for<0, KS>([&](auto kstep) {
           constexpr int ks = decltype(kstep)::value;
-          lds_wait_for<(KS - 1 - ks) * READS_PER_STEP>();   // the reads of the later k steps may still be under way
+          // the reads of the later k steps may still be under way (the counter saturates at 15:
+          // asking for fewer in flight than allowed only waits a little longer)
+          constexpr int LATER_READS = (KS - 1 - ks) * READS_PER_STEP;
+          lds_wait_for<(LATER_READS < 15 ? LATER_READS : 15)>();
 #pragma unroll
           for (int i = 0; i < TM; ++i) fa[ks][i].settle();
 #pragma unroll
@@ -963,13 +966,17 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
 // Few output tiles under a long K (the shared projections onto the narrow width): twice the
 // tiles and half the k steps.  128 x 64 outputs, 64-deep k tiles, four wavefronts stacked in M
 // (each 32 x 64: the bf16 epilogue's strip), 72 KB of ring: two workgroups per CU.
-template <bool BKC>
+template <bool AK, bool BKC>
 int launch_mfma_deep(const GemmDesc& g, hipStream_t s) {
   constexpr int BM = 128, BN = 64, BK = 64;
   dim3 grid = grid_for<BM, BN>(g, false), block(256);
   if (grid.x > 512) grid.x = 512;
-  if (g.out_f32) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 4, 1, true, BKC, EPI_STORE, true>), grid, block, 0, s, g);
-  else hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 4, 1, true, BKC, EPI_STORE, false>), grid, block, 0, s, g);
+#define BIGMAC_MFMA_DEEP(EPI, OUTF32) \
+  hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 4, 1, AK, BKC, EPI, OUTF32>), grid, block, 0, s, g)
+  if (g.epilogue == EPI_ACCUM) BIGMAC_MFMA_DEEP(EPI_ACCUM, true);
+  else if (g.out_f32) BIGMAC_MFMA_DEEP(EPI_STORE, true);
+  else BIGMAC_MFMA_DEEP(EPI_STORE, false);
+#undef BIGMAC_MFMA_DEEP
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }
@@ -1007,8 +1014,15 @@ int launch_gemm(const GemmDesc& g, hipStream_t s) {
   const int combo = g.a_kcontig * 2 + g.b_kcontig;
   if (g.dtype == BIGMAC_BF16) {
     if (g.deep_tile) {
-      if (g.mode != GEMM_DENSE || g.epilogue != EPI_STORE || !g.a_kcontig || g.K % 64 || g.tall_tile) return BIGMAC_ERR_INVALID_ARG;
-      return g.b_kcontig ? launch_mfma_deep<true>(g, s) : launch_mfma_deep<false>(g, s);
+      if (g.mode != GEMM_DENSE || (g.epilogue != EPI_STORE && g.epilogue != EPI_ACCUM) || g.tall_tile ||
+          ((g.a_kcontig || g.b_kcontig) && g.K % 64))
+        return BIGMAC_ERR_INVALID_ARG;
+      switch (combo) {
+        case 2: return launch_mfma_deep<true, false>(g, s);
+        case 3: return launch_mfma_deep<true, true>(g, s);
+        case 0: return launch_mfma_deep<false, false>(g, s);
+        default: return BIGMAC_ERR_UNSUPPORTED;
+      }
     }
     if (g.tall_tile) {
       switch (combo) {

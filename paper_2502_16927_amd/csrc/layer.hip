@@ -37,6 +37,12 @@ struct StageTimer {  // records the caller's events around the launches of one s
 #ifndef BIGMAC_DEEP_MAX_TILES
 #define BIGMAC_DEEP_MAX_TILES 256   // 128 x 128 tiles (one per CU) up to which a dense product takes the 128 x 64 x 64 tile
 #endif
+#ifndef BIGMAC_DEEP_WGRAD_MAX_TILES
+#define BIGMAC_DEEP_WGRAD_MAX_TILES 16   // measured: 16 tiles 15.5 -> 13.2 us; 64 tiles (gpt_xl widths) 43 -> 48 us
+#endif
+#ifndef BIGMAC_DEEP_K_TILE_US
+#define BIGMAC_DEEP_K_TILE_US 0.7
+#endif
 #define BIGMAC_STAGE(stage) StageTimer stage_timer_##stage(s, stage)
 
 struct Carver {  // hands out 256-byte aligned pieces of one buffer
@@ -167,20 +173,31 @@ inline bool tall_token_wgrad(const bigmac_dims& D, int M, int N) {
 // rounds of 768 resident workgroups x k tiles per slice x 0.6 us (measured per k tile of 32)
 // + partial bytes, written and read once, at 5 TB/s.
 // (On the tall tile: 512 resident workgroups, 0.85 us per k tile.)
-int choose_ksplit(int M, int N, int K, bool tall = false) {
-  const long tiles = (long)((M + (tall ? 255 : 127)) / (tall ? 256 : 128)) * ((N + 127) / 128);
-  const long resident = tall ? 512 : 768;
-  const double k_tile_us = tall ? 0.85 : 0.6;
+enum TileShape { TILE_SQUARE, TILE_TALL, TILE_DEEP };
+int choose_ksplit(int M, int N, int K, TileShape shape = TILE_SQUARE) {
+  const int bm = shape == TILE_TALL ? 256 : 128, bn = shape == TILE_DEEP ? 64 : 128, bk = shape == TILE_DEEP ? 64 : 32;
+  const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+  const long resident = shape == TILE_SQUARE ? 768 : 512;
+  const double k_tile_us = shape == TILE_TALL ? 0.85 : (shape == TILE_DEEP ? BIGMAC_DEEP_K_TILE_US : 0.6);
   const double partial_us = (double)M * N * 4 * 2 / 5e6;
   int best = 1;
   double best_us = 1e30;
   for (int ks = 1; ks <= 64 && K / ks >= 256; ks *= 2) {
     const long rounds = (tiles * ks + resident - 1) / resident;
-    const double us = rounds * ((K / ks + 31) / 32) * k_tile_us + (ks > 1 ? ks * partial_us : 0.0);
+    const double us = rounds * ((K / ks + bk - 1) / bk) * k_tile_us + (ks > 1 ? ks * partial_us : 0.0);
     if (us <= best_us * 1.05) { best_us = us < best_us ? us : best_us; best = ks; }   // near ties go to more workgroups
   }
   return best;
 }
+// Tile shape and slice count of a weight gradient over the token index ([M, T] x [T, N]); the
+// plan of the partials and the launch both take them from here.
+// Few output tiles (K = T is long by nature): the 128 x 64 tile with 64-deep k tiles.
+inline TileShape token_wgrad_shape(const bigmac_dims& D, int M, int N) {
+  if (tall_token_wgrad(D, M, N)) return TILE_TALL;
+  if (bf(D) && (long)((M + 127) / 128) * ((N + 127) / 128) <= BIGMAC_DEEP_WGRAD_MAX_TILES) return TILE_DEEP;
+  return TILE_SQUARE;
+}
+inline int token_wgrad_ksplit(const bigmac_dims& D, int M, int N) { return choose_ksplit(M, N, D.T, token_wgrad_shape(D, M, N)); }
 
 BwdPlan plan_bwd(const bigmac_dims& D) {
   const Widths W = widths(D);
@@ -198,9 +215,9 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
   p.dx_f32 = c.take((bf(D) && (D.flags & BIGMAC_FLAG_OUT_BF16)) ? (size_t)D.T * D.d * 4 : 0);
   // split-K partials of the three weight gradients over the token index: one region each, so
   // that one launch at the end can reduce all three
-  p.part_gate = c.take((size_t)choose_ksplit(D.d, D.N, D.T, tall_token_wgrad(D, D.d, D.N)) * D.d * D.N * 4);
-  p.part_up = c.take(dcca ? (size_t)choose_ksplit(D.r, D.d, D.T, tall_token_wgrad(D, D.r, D.d)) * D.r * D.d * 4 : 0);
-  p.part_down = c.take(dcca ? (size_t)choose_ksplit(D.d, D.r, D.T, tall_token_wgrad(D, D.d, D.r)) * D.d * D.r * 4 : 0);
+  p.part_gate = c.take((size_t)token_wgrad_ksplit(D, D.d, D.N) * D.d * D.N * 4);
+  p.part_up = c.take(dcca ? (size_t)token_wgrad_ksplit(D, D.r, D.d) * D.r * D.d * 4 : 0);
+  p.part_down = c.take(dcca ? (size_t)token_wgrad_ksplit(D, D.d, D.r) * D.d * D.r * 4 : 0);
   p.tmp_f32 = 0;
   p.total = c.off;
   return p;
@@ -274,8 +291,10 @@ int run_token_wgrad(const bigmac_dims& D, const void* A, long lda, int M, const 
   g.a_kcontig = 0; g.b_kcontig = 0;
   g.epilogue = EPI_ACCUM; g.beta = 0;
   g.A = A; g.lda = lda; g.M = M; g.B = B; g.ldb = ldb; g.N = N; g.K = D.T;
-  g.tall_tile = tall_token_wgrad(D, M, N);
-  g.ksplit = choose_ksplit(M, N, D.T, g.tall_tile);
+  const TileShape shape = token_wgrad_shape(D, M, N);
+  g.tall_tile = shape == TILE_TALL;
+  g.deep_tile = shape == TILE_DEEP;
+  g.ksplit = token_wgrad_ksplit(D, M, N);
   g.C = partials; g.ldc = N; g.gstride_c = (long)M * N;
   job->part = partials; job->out = out; job->n = (size_t)M * N; job->nslices = g.ksplit;
   return launch_gemm(g, s);
