@@ -197,8 +197,10 @@ int launch_aux_loss(const bigmac_dims& D, const float* logits, const int32_t* to
 
 // ----------------------------------------------------------------------------- permute --
 size_t permutation_ws_bytes(int T, int k, int N);
+// tile_maps (optional): tile maps of the expert offsets, built by the same launch that finds them
+struct TileMapJobs;
 int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* topk_idx, int32_t* expert_offsets,
-                             int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s);
+                             int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s, const TileMapJobs* tile_maps = nullptr);
 int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, const int32_t* slot_of,
                          void* x_perm, hipStream_t s);
 enum CombineOut { COMBINE_F32 = 0, COMBINE_SPLIT_BF16 = 1 };  // fp32 [T,w]  |  bf16 [T,2w] = (hi | lo)

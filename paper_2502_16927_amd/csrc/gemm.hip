@@ -8,6 +8,7 @@
 // Two workgroup tiles, 128 x 128 and 256 x 128, the latter for products with many tiles and a long K.
 // fp32 storage: a plain tiled FMA kernel (only the tiny fp32 workload uses it).
 #include "common.hpp"
+#include "tile_map.hpp"
 
 // Block tile of the MFMA kernel (build-time tunables): BM x BN outputs per block, BK-deep LDS
 // stages, WM x WN wavefronts each owning a (BM/WM) x (BN/WN) sub-tile of 32x32 MFMA tiles.
@@ -91,7 +92,7 @@ __device__ __forceinline__ int tile_at(const TileSpace& ts, int pos) {
 // equal cost (cost of a group = its k tiles + a constant for set-up and epilogue, see
 // build_tile_map_kernel), each as group * 65536 + 16-bit fraction of that group; every group has
 // the same number of tiles, so a split point turns into a tile index for any tile shape.
-constexpr int TILE_MAP_HEADER = 16;   // ints in front of the (group, first row) pairs: [0] tile count, [1..9] split points
+static_assert(TILE_MAP_K_ROWS == BIGMAC_TILE_BK, "the tile map prices groups in k tiles of the square tile");
 __device__ __forceinline__ void balance_ragged_k(const GemmDesc& p, TileSpace& ts) {
   const int tiles_per_group = ts.gx * ts.gy;
   const int x = (int)(blockIdx.x & 7);
@@ -764,79 +765,8 @@ __global__ __launch_bounds__(256) void fma_gemm_kernel(GemmDesc p) {
 
 // ------------------------------------------------------------------------ helpers ----------
 
-// tile_map[0] = number of M tiles, [1..9] = the split points of the cost-balanced ragged-K
-// schedule (see balance_ragged_k), then from TILE_MAP_HEADER on (group, first row) per M tile,
-// groups in order.  One workgroup of 1024 threads, one thread per group.
-__global__ void build_tile_map_kernel(const int* __restrict__ offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
-  __shared__ int scan[16];
-  const int g = threadIdx.x;
-  int beg = 0, rows = 0, cnt = 0;
-  if (g < groups) {
-    beg = offsets[g];
-    rows = offsets[g + 1] - beg;
-    cnt = (rows + tile_rows - 1) / tile_rows;
-  }
-  // inclusive scan over the 1024 threads: shuffles inside each wavefront, the 16 wavefront totals through LDS
-  auto inclusive_scan = [&](int v) {
-    const int lane = g & 63, wave = g >> 6;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const int o = __shfl_up(v, d, 64);
-      if (lane >= d) v += o;
-    }
-    __syncthreads();
-    if (lane == 63) scan[wave] = v;
-    __syncthreads();
-    int before = 0;
-    for (int w = 0; w < wave; ++w) before += scan[w];
-    return v + before;
-  };
-  const int last_tile = inclusive_scan(cnt);
-  const int first = last_tile - cnt;
-  for (int i = 0; i < cnt; ++i) {
-    tile_map[TILE_MAP_HEADER + 2 * (first + i)] = g;
-    tile_map[TILE_MAP_HEADER + 1 + 2 * (first + i)] = beg + i * tile_rows;
-  }
-  if (g == 1023) tile_map[0] = last_tile;
-  // split points: cost of a group = its k tiles + 8 (set-up and epilogue of a tile, in k tiles)
-  __shared__ int cost_of[1024];
-  __shared__ int incl[1024];
-  __shared__ long long worst_run;
-  const int cost = g < groups ? (rows + BIGMAC_TILE_BK - 1) / BIGMAC_TILE_BK + 8 : 0;
-  const int upto = inclusive_scan(cost);
-  cost_of[g] = cost;
-  incl[g] = upto;
-  if (g == 0) worst_run = 0;
-  __syncthreads();
-  const long long total = incl[1023];
-  // cost in front of position q = group * 65536 + fraction
-  auto cost_before = [&](long long q) {
-    const int gi = (int)(q >> 16);
-    if (gi >= groups) return total;
-    return (long long)(incl[gi] - cost_of[gi]) + (((q & 0xFFFF) * cost_of[gi]) >> 16);
-  };
-  // Near-uniform routing: runs of equal tile counts are as good and keep whole groups together,
-  // and the workgroups of an XCD then get equal numbers of tiles.  Use the cost-balanced cut
-  // only where the equal cut would leave an XCD more than 1/8 over its share.
-  if (g < 8) {
-    const long long q0 = ((long long)groups * g << 16) / 8, q1 = ((long long)groups * (g + 1) << 16) / 8;
-    atomicMax((unsigned long long*)&worst_run, (unsigned long long)(cost_before(q1) - cost_before(q0)));
-  }
-  __syncthreads();
-  const bool balanced = worst_run * 64 > total * 9;
-#pragma unroll 1
-  for (int x = 0; x <= 8; ++x) {
-    if (!balanced) {
-      if (g == 0) tile_map[1 + x] = (int)(((long long)groups * x << 16) / 8);
-      continue;
-    }
-    const long long target = total * x / 8;
-    if (x == 8) {
-      if (g == 0) tile_map[1 + x] = groups << 16;
-    } else if (cost > 0 && target >= upto - cost && target < upto) {
-      tile_map[1 + x] = (g << 16) | (int)(((target - (upto - cost)) << 16) / cost);
-    }
-  }
+__global__ __launch_bounds__(1024) void build_tile_map_kernel(const int* __restrict__ offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
+  build_tile_map_block(offsets, groups, tile_rows, tile_map);
 }
 
 // out[i .. i+4) = (beta ? out : 0) + sum_z part[z*n + i ..]: one float4 of the output per thread;

@@ -1,6 +1,7 @@
 // C ABI of libbigmac: argument checks, workspace planning and the launch sequences of the
 // layer (Eq. 2 with the expert of Eq. 4; CDAC order with the expert of Eq. 3) and its backward.
 #include "common.hpp"
+#include "tile_map.hpp"
 
 namespace bigmac {
 
@@ -513,14 +514,11 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   }
   {
     BIGMAC_STAGE(BIGMAC_STAGE_PERMUTATION);
-    rc = launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s);
+    TileMapJobs maps = {};
+    maps.tile_rows[0] = gemm_ragged_tile_rows(D->dtype, 0); maps.map[0] = tile_map;
+    if (any_tall_rows(*D)) { maps.tile_rows[1] = gemm_ragged_tile_rows(D->dtype, 1); maps.map[1] = tile_map_tall; }
+    rc = launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s, &maps);
     if (rc) return rc;
-    rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype, 0), tile_map, s);
-    if (rc) return rc;
-    if (any_tall_rows(*D)) {
-      rc = launch_build_tile_map(offsets, D->N, gemm_ragged_tile_rows(D->dtype, 1), tile_map_tall, s);
-      if (rc) return rc;
-    }
   }
   {
     BIGMAC_STAGE(BIGMAC_STAGE_DISPATCH);

@@ -4,6 +4,7 @@
 // Slot assignment uses no atomics whose order could matter: counts are order-free, ranks come
 // from ballots inside one wavefront walking its chunk in order.
 #include "common.hpp"
+#include "tile_map.hpp"
 
 namespace bigmac {
 
@@ -52,10 +53,13 @@ __device__ __forceinline__ int block_scan_1024(int v, int* wave_totals) {
 // slot reaches offsets[e] + capacity.
 // The 1024 threads are G groups x NP experts (NP = N rounded up to a power of two, G = 1024 / NP);
 // group g owns a contiguous range of chunks, so all chunk rows are read by many threads at once.
+// At the end the workgroup also builds the tile maps asked for: the offsets are at hand, and a
+// kernel of their own would cost a launch and a round trip through memory.
 __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ counts, int nchunks, int N, int NP, int capacity,
-                                                         int32_t* __restrict__ offsets) {
+                                                         int32_t* __restrict__ offsets, TileMapJobs maps) {
   __shared__ int part[1024];        // [g][e]: pairs of expert e in the chunks of group g
   __shared__ int wave_totals[16];
+  __shared__ int first_slot[1025];  // offsets[0 .. N], for the tile maps
   const int G = 1024 / NP;
   const int e = threadIdx.x % NP, g = threadIdx.x / NP;
   const int per = (nchunks + G - 1) / G;
@@ -85,8 +89,8 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ c
   __syncthreads();
   if (e < N) {
     int run = part[e] + before_me;
-    if (g == 0) offsets[e] = part[e];
-    if (g == 0 && e == N - 1) offsets[N] = part[e] + held;
+    if (g == 0) offsets[e] = first_slot[e] = part[e];
+    if (g == 0 && e == N - 1) offsets[N] = first_slot[N] = part[e] + held;
     for (int c0 = c_beg; c0 < c_end; c0 += 8) {
       int v[8];
 #pragma unroll
@@ -98,6 +102,10 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ c
       }
     }
   }
+  __syncthreads();
+#pragma unroll 1
+  for (int m = 0; m < 2; ++m)
+    if (maps.map[m]) build_tile_map_block(first_slot, N, maps.tile_rows[m], maps.map[m]);
 }
 
 // One wavefront per chunk walks its pairs in flat order, 64 at a time (all read up front).  A
@@ -309,7 +317,9 @@ size_t permutation_ws_bytes(int T, int k, int N) {
 }
 
 int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* topk_idx, int32_t* expert_offsets,
-                             int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s) {
+                             int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s, const TileMapJobs* tile_maps) {
+  if (N > 1024) return BIGMAC_ERR_UNSUPPORTED;   // one thread of the scan per expert
+  const TileMapJobs maps = tile_maps ? *tile_maps : TileMapJobs{};
   const int Tk = T * k;
   const int chunk = perm_chunk(Tk, N);
   const int nchunks = (Tk + chunk - 1) / chunk;
@@ -320,7 +330,7 @@ int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* t
   BIGMAC_CHECK_LAUNCH();
   int NP = 1;
   while (NP < N) NP <<= 1;
-  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, counts, nchunks, N, NP, capacity, expert_offsets);
+  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, counts, nchunks, N, NP, capacity, expert_offsets, maps);
   BIGMAC_CHECK_LAUNCH();
   if (chunk == P_CHUNK_SMALL)
     hipLaunchKernelGGL(perm_rank_kernel<P_CHUNK_SMALL / 64>, dim3(nchunks), dim3(64), 2 * N * sizeof(int), s, topk_idx, Tk, N, nbits, capacity,

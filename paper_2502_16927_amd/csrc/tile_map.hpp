@@ -1,0 +1,159 @@
+// Tile map of a ragged-M problem (rows grouped by expert) and the cost-balanced schedule of the
+// ragged-K one, built by one workgroup of 1024 threads: by the kernel of its own in gemm.hip, or at
+// the end of the counting sort's scan, which has the group offsets at hand.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace bigmac {
+
+constexpr int TILE_MAP_HEADER = 16;   // ints in front of the (group, first row) pairs: [0] tile count, [1..9] split points
+constexpr int TILE_MAP_K_ROWS = 32;   // rows per k tile in the cost of a group (the square tile's depth)
+
+struct TileMapJobs {   // up to two maps (different tile heights) from one set of offsets; map == NULL: none
+  int tile_rows[2];
+  int* map[2];
+};
+
+// The map for at most 64 groups by one wavefront (lane = group): shuffles take the place of the
+// LDS arrays of the general form below, which it follows step by step.
+__device__ inline void build_tile_map_wave(const int* offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
+  const int g = threadIdx.x & 63;
+  int beg = 0, rows = 0, cnt = 0;
+  if (g < groups) {
+    beg = offsets[g];
+    rows = offsets[g + 1] - beg;
+    cnt = (rows + tile_rows - 1) / tile_rows;
+  }
+  auto inclusive_scan = [&](int v) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(v, d, 64);
+      if (g >= d) v += o;
+    }
+    return v;
+  };
+  const int last_tile = inclusive_scan(cnt);
+  const int first = last_tile - cnt;
+  for (int i = 0; i < cnt; ++i) {
+    tile_map[TILE_MAP_HEADER + 2 * (first + i)] = g;
+    tile_map[TILE_MAP_HEADER + 1 + 2 * (first + i)] = beg + i * tile_rows;
+  }
+  if (g == 63) tile_map[0] = last_tile;
+  const int cost = g < groups ? (rows + TILE_MAP_K_ROWS - 1) / TILE_MAP_K_ROWS + 8 : 0;
+  const int upto = inclusive_scan(cost);
+  const long long total = __shfl(upto, 63, 64);
+  // cost in front of position q = group * 65536 + fraction (every lane takes part in the shuffles)
+  auto cost_before = [&](long long q) {
+    const int gi = (int)(q >> 16);
+    const int src = gi < 64 ? gi : 63;
+    const int incl_gi = __shfl(upto, src, 64), cost_gi = __shfl(cost, src, 64);
+    if (gi >= groups) return total;
+    return (long long)(incl_gi - cost_gi) + (((q & 0xFFFF) * cost_gi) >> 16);
+  };
+  const int x8 = g < 8 ? g : 7;
+  const long long q0 = ((long long)groups * x8 << 16) / 8, q1 = ((long long)groups * (x8 + 1) << 16) / 8;
+  long long worst_run = cost_before(q1) - cost_before(q0);
+#pragma unroll
+  for (int off = 1; off < 8; off <<= 1) {
+    const long long o = __shfl_xor(worst_run, off, 64);
+    worst_run = o > worst_run ? o : worst_run;
+  }
+  worst_run = __shfl(worst_run, 0, 64);
+  const bool balanced = worst_run * 64 > total * 9;
+#pragma unroll 1
+  for (int x = 0; x <= 8; ++x) {
+    if (!balanced) {
+      if (g == 0) tile_map[1 + x] = (int)(((long long)groups * x << 16) / 8);
+      continue;
+    }
+    const long long target = total * x / 8;
+    if (x == 8) {
+      if (g == 0) tile_map[1 + x] = groups << 16;
+    } else if (cost > 0 && target >= upto - cost && target < upto) {
+      tile_map[1 + x] = (g << 16) | (int)(((target - (upto - cost)) << 16) / cost);
+    }
+  }
+}
+
+// tile_map[0] = number of M tiles, [1..9] = the split points of the cost-balanced ragged-K
+// schedule (see balance_ragged_k), then from TILE_MAP_HEADER on (group, first row) per M tile,
+// groups in order.  Called by all 1024 threads of a workgroup, one thread per group; offsets may
+// lie in the LDS.
+__device__ inline void build_tile_map_block(const int* offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
+  if (groups <= 64) {                // one wavefront holds every group: the same steps without LDS or barriers
+    if (threadIdx.x < 64) build_tile_map_wave(offsets, groups, tile_rows, tile_map);
+    return;
+  }
+  __shared__ int scan[16];
+  __syncthreads();                   // a previous call in the same kernel may still read the shared arrays
+  const int g = threadIdx.x;
+  int beg = 0, rows = 0, cnt = 0;
+  if (g < groups) {
+    beg = offsets[g];
+    rows = offsets[g + 1] - beg;
+    cnt = (rows + tile_rows - 1) / tile_rows;
+  }
+  // inclusive scan over the 1024 threads: shuffles inside each wavefront, the 16 wavefront totals through LDS
+  auto inclusive_scan = [&](int v) {
+    const int lane = g & 63, wave = g >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(v, d, 64);
+      if (lane >= d) v += o;
+    }
+    __syncthreads();
+    if (lane == 63) scan[wave] = v;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += scan[w];
+    return v + before;
+  };
+  const int last_tile = inclusive_scan(cnt);
+  const int first = last_tile - cnt;
+  for (int i = 0; i < cnt; ++i) {
+    tile_map[TILE_MAP_HEADER + 2 * (first + i)] = g;
+    tile_map[TILE_MAP_HEADER + 1 + 2 * (first + i)] = beg + i * tile_rows;
+  }
+  if (g == 1023) tile_map[0] = last_tile;
+  // split points: cost of a group = its k tiles + 8 (set-up and epilogue of a tile, in k tiles)
+  __shared__ int cost_of[1024];
+  __shared__ int incl[1024];
+  __shared__ long long worst_run;
+  const int cost = g < groups ? (rows + TILE_MAP_K_ROWS - 1) / TILE_MAP_K_ROWS + 8 : 0;
+  const int upto = inclusive_scan(cost);
+  cost_of[g] = cost;
+  incl[g] = upto;
+  if (g == 0) worst_run = 0;
+  __syncthreads();
+  const long long total = incl[1023];
+  // cost in front of position q = group * 65536 + fraction
+  auto cost_before = [&](long long q) {
+    const int gi = (int)(q >> 16);
+    if (gi >= groups) return total;
+    return (long long)(incl[gi] - cost_of[gi]) + (((q & 0xFFFF) * cost_of[gi]) >> 16);
+  };
+  // Near-uniform routing: runs of equal tile counts are as good and keep whole groups together,
+  // and the workgroups of an XCD then get equal numbers of tiles.  Use the cost-balanced cut
+  // only where the equal cut would leave an XCD more than 1/8 over its share.
+  if (g < 8) {
+    const long long q0 = ((long long)groups * g << 16) / 8, q1 = ((long long)groups * (g + 1) << 16) / 8;
+    atomicMax((unsigned long long*)&worst_run, (unsigned long long)(cost_before(q1) - cost_before(q0)));
+  }
+  __syncthreads();
+  const bool balanced = worst_run * 64 > total * 9;
+#pragma unroll 1
+  for (int x = 0; x <= 8; ++x) {
+    if (!balanced) {
+      if (g == 0) tile_map[1 + x] = (int)(((long long)groups * x << 16) / 8);
+      continue;
+    }
+    const long long target = total * x / 8;
+    if (x == 8) {
+      if (g == 0) tile_map[1 + x] = groups << 16;
+    } else if (cost > 0 && target >= upto - cost && target < upto) {
+      tile_map[1 + x] = (g << 16) | (int)(((target - (upto - cost)) << 16) / cost);
+    }
+  }
+}
+
+}  // namespace bigmac
