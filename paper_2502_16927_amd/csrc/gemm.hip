@@ -303,7 +303,7 @@ struct TileOperands {
 // happen are pushed out of their buffer's range instead of being branched around): the number of
 // instructions in flight behind any load is then a compile-time constant, which is what the
 // counter waits below and the compiler's own ones are derived from.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32, int NS = BIGMAC_TILE_STAGES>
 __global__ __launch_bounds__(64 * WAVES_M* WAVES_N)
     __attribute__((amdgpu_waves_per_eu(BM > BIGMAC_TILE_BM || BK > BIGMAC_TILE_BK ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU)))
 void mfma_gemm_kernel(GemmDesc p) {
@@ -312,11 +312,11 @@ void mfma_gemm_kernel(GemmDesc p) {
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int KS = BK / 16;
   constexpr int A_CHUNKS = BM * BK / 8, B_CHUNKS = BN * BK / 8;
-  constexpr int NS = BIGMAC_TILE_STAGES;  // LDS ring: NS - 1 k tiles in flight while one is consumed
+  // NS: stages of the LDS ring, NS - 1 k tiles in flight while one is consumed
   // bf16 results accumulate the transposed tile (operands swapped in the MFMA): a lane then owns
   // one output row and groups of 4 consecutive columns, which pack into 8-byte pieces
   constexpr bool SWAP = !(EPI == EPI_ACCUM || OUTF32);
-  static_assert(NS >= 3 && NS <= 4, "ring of 3 or 4 stages");
+  static_assert(NS >= 2 && NS <= 4, "ring of 2 to 4 stages");
   // The ring.  All reads of it are assembly (see lds_read_*), so the only waits on its loads are
   // the counter waits written out below.
   constexpr int STAGE_CHUNKS = A_CHUNKS + B_CHUNKS;
@@ -896,6 +896,30 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
 // Few output tiles under a long K (the shared projections onto the narrow width): twice the
 // tiles and half the k steps.  128 x 64 outputs, 64-deep k tiles, four wavefronts stacked in M
 // (each 32 x 64: the bf16 epilogue's strip), 72 KB of ring: two workgroups per CU.
+// The square tile with 64-deep k tiles in a ring of two stages (64 KB, two workgroups per CU).  A
+// k-contiguous operand then arrives as whole 128-byte lines; with 32-deep k tiles each of its
+// lines is requested from the L2 twice, half a line per k tile.
+template <bool AK, bool BKC>
+int launch_mfma_widek(const GemmDesc& g, hipStream_t s) {
+  constexpr int BM = 128, BN = 128, BK = 64;
+  dim3 grid = grid_for<BM, BN>(g, false), block(256);
+  if (grid.x > 512) grid.x = 512;
+#define BIGMAC_MFMA_WIDEK(EPI, OUTF32) \
+  hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 2, 2, AK, BKC, EPI, OUTF32, 2>), grid, block, 0, s, g)
+  switch (g.epilogue) {
+    case EPI_STORE:
+      if (g.out_f32) BIGMAC_MFMA_WIDEK(EPI_STORE, true);
+      else BIGMAC_MFMA_WIDEK(EPI_STORE, false);
+      break;
+    case EPI_GELU: BIGMAC_MFMA_WIDEK(EPI_GELU, false); break;
+    case EPI_DGELU: BIGMAC_MFMA_WIDEK(EPI_DGELU, false); break;
+    default: return BIGMAC_ERR_INVALID_ARG;
+  }
+#undef BIGMAC_MFMA_WIDEK
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
 template <bool AK, bool BKC>
 int launch_mfma_deep(const GemmDesc& g, hipStream_t s) {
   constexpr int BM = 128, BN = 64, BK = 64;
@@ -943,6 +967,10 @@ int launch_gemm(const GemmDesc& g, hipStream_t s) {
   if (g.mode == GEMM_DENSE && g.ksplit < 1) return BIGMAC_ERR_INVALID_ARG;
   const int combo = g.a_kcontig * 2 + g.b_kcontig;
   if (g.dtype == BIGMAC_BF16) {
+    if (g.wide_k) {
+      if (g.mode == GEMM_RAGGED_K || g.tall_tile || g.deep_tile || !g.a_kcontig || g.K % 64) return BIGMAC_ERR_INVALID_ARG;
+      return g.b_kcontig ? launch_mfma_widek<true, true>(g, s) : launch_mfma_widek<true, false>(g, s);
+    }
     if (g.deep_tile) {
       if (g.mode != GEMM_DENSE || (g.epilogue != EPI_STORE && g.epilogue != EPI_ACCUM) || g.tall_tile ||
           ((g.a_kcontig || g.b_kcontig) && g.K % 64))

@@ -38,6 +38,12 @@ struct StageTimer {  // records the caller's events around the launches of one s
 #ifndef BIGMAC_DEEP_MAX_TILES
 #define BIGMAC_DEEP_MAX_TILES 256   // 128 x 128 tiles (one per CU) up to which a dense product takes the 128 x 64 x 64 tile
 #endif
+// Which per-expert products take the square tile with 64-deep k tiles (two ring stages) when they
+// do not take the tall one: 1 expert-up, 2 expert-down, 4 the GELU' product, 8 the data gradient
+// of the first matrix.  Measured at gpt_medium: -1 %, +2.5 %, +3 %, -6 %.
+#ifndef BIGMAC_WIDEK_MASK
+#define BIGMAC_WIDEK_MASK 8
+#endif
 #ifndef BIGMAC_DEEP_WGRAD_MAX_TILES
 #define BIGMAC_DEEP_WGRAD_MAX_TILES 16   // measured: 16 tiles 15.5 -> 13.2 us; 64 tiles (gpt_xl widths) 43 -> 48 us
 #endif
@@ -100,6 +106,9 @@ inline bool tall_dense(const bigmac_dims& D, int M, int N, int K) {
 // Few 128 x 128 tiles under a long K: the narrower tile with deeper k tiles (see launch_gemm).
 inline bool deep_dense(const bigmac_dims& D, int M, int N, int K) {
   return bf(D) && K % 64 == 0 && K >= 512 && (long)((M + 127) / 128) * ((N + 127) / 128) <= BIGMAC_DEEP_MAX_TILES;
+}
+inline bool wide_k_ok(const bigmac_dims& D, int K, int bit) {
+  return bf(D) && (BIGMAC_WIDEK_MASK & bit) && K % 64 == 0;
 }
 inline bool any_tall_rows(const bigmac_dims& D) {
   const Widths W = widths(D);
@@ -265,6 +274,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   // hact = gelu(x_perm W1[e])
   g.epilogue = EPI_GELU;
   g.tall_tile = tall_rows(D, W.hid, W.win); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
+  g.wide_k = !g.tall_tile && wide_k_ok(D, W.win, 1);
   g.A = x_perm; g.lda = W.win; g.K = W.win;
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
   g.C = hact; g.ldc = ld_wide; g.aux_out = act;
@@ -280,6 +290,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.B = w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.win;
   g.C = o_perm; g.ldc = W.win;
   g.tall_tile = tall_rows(D, W.win, W.hid); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
+  g.wide_k = !g.tall_tile && wide_k_ok(D, W.hid, 2);
   BIGMAC_STAGE(BIGMAC_STAGE_EXPERT_DOWN);
   return launch_gemm(g, s);
 }
@@ -639,6 +650,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.B = P->w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.hid;
     g.C = dact; g.ldc = wide_ld(*D); g.aux_in = act;
     g.tall_tile = tall_rows(*D, W.hid, W.win); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
+    g.wide_k = !g.tall_tile && wide_k_ok(*D, W.win, 4);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
@@ -673,6 +685,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.B = P->w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.win;
     g.C = dx_perm; g.ldc = W.win;
     g.tall_tile = tall_rows(*D, W.win, W.hid); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
+    g.wide_k = !g.tall_tile && wide_k_ok(*D, W.hid, 8);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
