@@ -36,7 +36,7 @@ SMALL = [
     dict(T=70, d=128, r=64, N=128, k=64, h=64, dtype=B.BF16),
     dict(T=90, d=128, r=64, N=200, k=4, h=64, dtype=B.BF16),
     # 128 tiles under K = 576: descend and the data gradient of ascend take the 128 x 64 tile with
-    # 64-deep k tiles (ragged last row tile, 7 column tiles)
+    # 64-deep k tiles (ragged last row tile, 7 column tiles; r is always a multiple of 64 here)
     dict(T=4000, d=576, r=448, N=8, k=2, h=64, dtype=B.BF16),
 ]
 
