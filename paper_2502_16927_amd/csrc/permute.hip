@@ -157,6 +157,76 @@ __global__ __launch_bounds__(64) void perm_rank_kernel(const int32_t* __restrict
   }
 }
 
+// The whole counting sort for a few pairs (decode batches) in one workgroup of 1024 threads:
+// pair f = (round, wavefront, lane) in flat order; per (round, wavefront) the pairs of each expert
+// are counted by ballots (one writer per counter, no atomics), the counters are scanned per expert
+// in that same order, and a pair's slot is its expert's first slot + the pairs of the expert in
+// earlier (round, wavefront) groups + the earlier lanes of its own group with the same expert.
+// The same slots as the three-kernel form; also writes the offsets and the tile maps.
+constexpr int PS_MAX_ROUNDS = 4;            // up to 4096 pairs
+constexpr int PS_MAX_COUNTERS = 8192;       // rounds x 16 wavefronts x experts, 32 KB of LDS
+template <int ROUNDS>
+__global__ __launch_bounds__(1024) void perm_small_kernel(const int32_t* __restrict__ idx, int Tk, int N, int nbits, int capacity,
+                                                          int32_t* __restrict__ offsets, int32_t* __restrict__ slot_of,
+                                                          int32_t* __restrict__ src_of, TileMapJobs maps) {
+  __shared__ int cnt[PS_MAX_COUNTERS];   // [round][wavefront][expert]
+  __shared__ int wave_totals[16];
+  __shared__ int first_slot[1025];
+  __shared__ int range_end[1024];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < ROUNDS * 16 * N; i += 1024) cnt[i] = 0;
+  __syncthreads();
+  const unsigned long long below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int mine[ROUNDS], rank[ROUNDS];
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int f = r * 1024 + tid;
+    mine[r] = f < Tk ? idx[f] : -1;
+    const bool live = mine[r] >= 0;
+    const int e = live ? mine[r] : 0;
+    unsigned long long same = __ballot(live);
+    for (int b = 0; b < nbits; ++b) {
+      const unsigned long long bal = __ballot((e >> b) & 1);
+      same &= ((e >> b) & 1) ? bal : ~bal;
+    }
+    rank[r] = __popcll(same & below);
+    if (live && (same >> lane) == 1ull) cnt[(r * 16 + wave) * N + e] = __popcll(same);   // highest lane of each expert group
+  }
+  __syncthreads();
+  int total = 0;
+  if (tid < N)
+    for (int g = 0; g < ROUNDS * 16; ++g) {      // counters -> pairs of the expert in earlier groups
+      const int c = cnt[g * N + tid];
+      cnt[g * N + tid] = total;
+      total += c;
+    }
+  const int held = capacity > 0 ? min(total, capacity) : total;
+  const int incl = block_scan_1024(tid < N ? held : 0, wave_totals);
+  if (tid < N) {
+    offsets[tid] = first_slot[tid] = incl - held;
+    range_end[tid] = incl;
+    if (tid == N - 1) offsets[N] = first_slot[N] = incl;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const int f = r * 1024 + tid;
+    if (mine[r] >= 0) {
+      const int e = mine[r];
+      const int slot = first_slot[e] + cnt[(r * 16 + wave) * N + e] + rank[r];
+      if (slot < range_end[e]) {
+        slot_of[f] = slot;
+        src_of[slot] = f;
+      } else {
+        slot_of[f] = -1;
+      }
+    }
+  }
+#pragma unroll 1
+  for (int m = 0; m < 2; ++m)
+    if (maps.map[m]) build_tile_map_block(first_slot, N, maps.tile_rows[m], maps.map[m]);
+}
+
 // 16-byte chunks: thread (t, c) copies chunk c of row t to its k destination rows
 __global__ __launch_bounds__(256) void dispatch_rows_kernel(const uint4* __restrict__ x_low, const int32_t* __restrict__ slot_of,
                                                             uint4* __restrict__ x_perm, int T, int k, int cpr) {
@@ -320,6 +390,22 @@ int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* t
                              int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s, const TileMapJobs* tile_maps) {
   if (N > 1024) return BIGMAC_ERR_UNSUPPORTED;   // one thread of the scan per expert
   const TileMapJobs maps = tile_maps ? *tile_maps : TileMapJobs{};
+  {
+    const int need = (T * k + 1023) / 1024;
+    const int rounds = need <= 1 ? 1 : (need == 2 ? 2 : 4);           // the instantiated round counts
+    if (need <= PS_MAX_ROUNDS && rounds * 16 * N <= PS_MAX_COUNTERS) {
+      int bits = 0;
+      while ((1 << bits) < N) ++bits;
+#define BIGMAC_PERM_SMALL(R) \
+  hipLaunchKernelGGL(perm_small_kernel<R>, dim3(1), dim3(1024), 0, s, topk_idx, T * k, N, bits, capacity, expert_offsets, slot_of, src_of, maps)
+      if (rounds == 1) BIGMAC_PERM_SMALL(1);
+      else if (rounds == 2) BIGMAC_PERM_SMALL(2);
+      else BIGMAC_PERM_SMALL(4);
+#undef BIGMAC_PERM_SMALL
+      BIGMAC_CHECK_LAUNCH();
+      return BIGMAC_OK;
+    }
+  }
   const int Tk = T * k;
   const int chunk = perm_chunk(Tk, N);
   const int nchunks = (Tk + chunk - 1) / chunk;

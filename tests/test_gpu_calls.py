@@ -81,7 +81,10 @@ def test_route_ties_and_order_cases(oracle):
     assert np.array_equal(host(lg), oracle.router_logits(xo, ones)) and np.all(host(lg) == 1.0)
 
 
-PERM_CASES = [(1, 1, 1), (5, 2, 3), (700, 8, 64), (1025, 6, 24), (4096, 8, 128), (3000, 2, 1000), (513, 64, 64)]
+PERM_CASES = [(1, 1, 1), (5, 2, 3), (700, 8, 64), (1025, 6, 24), (4096, 8, 128), (3000, 2, 1000), (513, 64, 64),
+              # up to 4096 pairs one workgroup does the whole sort: 1, 2 and 4 rounds of 1024 pairs, a full last
+              # round, 3 rounds needed, the counter limit (512 x 8 pairs, 128 experts) and just past it
+              (128, 8, 64), (130, 8, 64), (512, 8, 64), (300, 8, 100), (512, 8, 128), (512, 8, 129), (37, 3, 500)]
 
 
 @pytest.mark.parametrize("T,k,N", PERM_CASES)

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("T,k,N,cap", [(5, 2, 3, 1), (700, 8, 64, 40), (1025, 6, 24, 300), (4096, 8, 128, 200), (3000, 2, 1000, 2),
+@pytest.mark.parametrize("T,k,N,cap", [(5, 2, 3, 1), (130, 8, 64, 10), (400, 8, 100, 20), (512, 8, 64, 70), (700, 8, 64, 40), (1025, 6, 24, 300), (4096, 8, 128, 200), (3000, 2, 1000, 2),
                                        (513, 64, 64, 100), (900, 4, 16, 100000)])
 @pytest.mark.parametrize("dtype", [B.BF16, B.F32])
 def test_dispatch_with_capacity(oracle, T, k, N, cap, dtype):
