@@ -118,6 +118,13 @@ def main():
                     help="fixed expert capacity ceil(f T k / N) instead of dropless routing (the paper's training runs: 1.2)")
     ap.add_argument("--aux-alpha", type=float, default=0.0,
                     help="coefficient of the load-balance loss (the paper's training runs: 0.001); 0 = off")
+    ap.add_argument("--mfma-peak", action="store_true",
+                    help="only time the matrix-core rate probe (register-resident 32x32x16 bf16 MFMAs): the "
+                         "achievable dense bf16 peak of this device, printed beside the published one")
+    ap.add_argument("--evict-mib", type=int, default=0,
+                    help="before every step of the eager pass, overwrite a scratch buffer of this many MiB, so "
+                         "that the per-stage times are those of cold caches (512 or more exceeds the 256 MB "
+                         "last-level cache); the timed graph replays are not affected")
     ap.add_argument("--no-graph", action="store_true",
                     help="time eager launches instead of replays of the step captured in a HIP graph")
     args = ap.parse_args()
@@ -138,6 +145,24 @@ def main():
         return
     from paper_2502_16927_amd import binding as B
     from paper_2502_16927_amd import synth
+    if args.mfma_peak:
+        torch.cuda.set_device(0)
+        props = torch.cuda.get_device_properties(0)
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+        blocks, iters = props.multi_processor_count * 8, 20000
+        B.bigmac_mfma_probe(blocks, 100, sink)
+        rates = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = B.bigmac_mfma_probe(blocks, iters, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            rates.append(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        print(json.dumps({"mfma_probe_tflops": max(rates), "runs": rates, "compute_units": props.multi_processor_count,
+                          "clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None, "published_peak_tflops": PEAK_MFMA_BF16 / 1e12,
+                          "probe": "32x32x16 bf16, 4 accumulators per wavefront, %d workgroups x 4 wavefronts" % blocks}))
+        return
 
     wl = synth.WORKLOADS.get(args.workload) or synth.NEXT_WORKLOADS[args.workload]
     if args.workload == "vanilla_moe":
@@ -188,7 +213,10 @@ def main():
     tables = [] if args.no_stage_events else [B.StageEvents() for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    evict = torch.empty(args.evict_mib << 20, dtype=torch.uint8, device=dev) if args.evict_mib > 0 else None
     for i in range(args.steps):
+        if evict is not None:
+            evict.fill_(i & 127)
         if tables:
             tables[i].install()
         step()
@@ -258,6 +286,11 @@ def main():
         "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
         "stage_sum_ms": round(sum(stage_ms.values()), 4),
     }
+    if args.evict_mib > 0:
+        out["stage_ms_caches"] = "cold: %d MiB overwritten before every eager step" % args.evict_mib
+        if stage_ms:   # the permutes against their compulsory bytes
+            out["permute_gbps_cold"] = {n: round(work[n][2] / (stage_ms[n] * 1e-3) / 1e9, 1)
+                                        for n in ("dispatch", "combine", "bwd_combine", "bwd_dispatch") if n in stage_ms}
     if args.cpu_sample > 0 and not cdac and not variant:
         out["cpu_baseline"] = cpu_baseline(wl, data, args.cpu_sample, training)
     else:

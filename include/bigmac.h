@@ -209,6 +209,14 @@ typedef enum {
   BIGMAC_STAGE_COUNT
 } bigmac_stage;
 int bigmac_set_stage_events(void *const *events);
+
+/* Measurement aid: the achievable dense bf16 matrix-core rate of the device, against which the
+ * rates of the layer's products are set (the published peak is the other yardstick).  Enqueues one
+ * kernel of `blocks` workgroups (256 threads) in which every wavefront issues 16 * iters
+ * 32x32x16 bf16 MFMAs on register operands, no memory traffic.  sink: device, one float, never
+ * written (keeps the arithmetic alive); *flops (host) receives the flops of the launch.  The
+ * caller times the launch.  blocks in [1, 65536], iters in [1, 2^20]; else BIGMAC_ERR_INVALID_ARG. */
+int bigmac_mfma_probe(int blocks, int iters, float *sink /*device*/, double *flops /*host*/, void *stream);
 const char *bigmac_stage_name(int stage);
 
 #ifdef __cplusplus

@@ -72,13 +72,16 @@ def lib() -> ctypes.CDLL:
         L.bigmac_set_stage_events.argtypes = [ctypes.POINTER(vp)]
         L.bigmac_stage_name.restype = ctypes.c_char_p
         L.bigmac_stage_name.argtypes = [ci]
+        L.bigmac_mfma_probe.restype = ci
+        L.bigmac_mfma_probe.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
         _lib = L
     return _lib
 
 
 EXPORTS = ("bigmac_workspace_bytes", "bigmac_status_string", "bigmac_forward_matrix_flops", "bigmac_permute_bytes",
            "bigmac_saved_layout", "bigmac_saved_aux_layout", "bigmac_aux_loss", "bigmac_route", "bigmac_dispatch", "bigmac_grouped_ffn", "bigmac_combine",
-           "bigmac_layer_forward", "bigmac_layer_backward", "bigmac_set_stage_events", "bigmac_stage_name")
+           "bigmac_layer_forward", "bigmac_layer_backward", "bigmac_set_stage_events", "bigmac_stage_name",
+           "bigmac_mfma_probe")
 STAGE_COUNT = 22
 
 
@@ -174,6 +177,13 @@ def bigmac_grouped_ffn(dims, x_perm, expert_offsets, w1, w2, act_saved, o_perm, 
 def bigmac_combine(dims, o_perm, slot_of, topk_w, y_low, stream=None):
     _check(lib().bigmac_combine(ctypes.byref(dims), _ptr(o_perm), _ptr(slot_of), _ptr(topk_w), _ptr(y_low),
                                 _stream(stream)), "bigmac_combine")
+
+
+def bigmac_mfma_probe(blocks, iters, sink, stream=None) -> float:
+    """Enqueues the matrix-core rate probe; returns the flops of the launch (the caller times it)."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().bigmac_mfma_probe(int(blocks), int(iters), _ptr(sink), ctypes.byref(flops), _stream(stream)), "bigmac_mfma_probe")
+    return flops.value
 
 
 def bigmac_layer_forward(dims, params, x, y, saved, ws, stream=None):

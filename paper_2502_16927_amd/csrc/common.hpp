@@ -159,6 +159,7 @@ int launch_gemm(const GemmDesc& g, hipStream_t s);
 inline size_t tile_map_ints(int total_rows, int groups, int tile_rows) {
   return 16 + 2 * ((size_t)total_rows / tile_rows + groups + 1);
 }
+double launch_mfma_probe(int blocks, int iters, float* sink, hipStream_t s);   // returns the flops issued, < 0 on a launch error
 int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* tile_map, hipStream_t s);
 // out[i] = (beta ? out[i] : 0) + sum_z part[z*n + i]
 int launch_reduce_partials(const float* part, int nslices, size_t n, float* out, int beta, hipStream_t s);

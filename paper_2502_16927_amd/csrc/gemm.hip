@@ -951,6 +951,42 @@ int launch_fma(const GemmDesc& g, hipStream_t s) {
 
 }  // namespace
 
+// Matrix-core rate probe: every wavefront issues 32x32x16 bf16 MFMAs back to back on four
+// independent accumulators held in registers; no memory traffic inside the loop.  What this
+// reaches is the achievable dense bf16 peak that the products' rates are set against.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* __restrict__ sink) {
+  bf16x8_t a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
+    b[i] = (__bf16)(float)((threadIdx.x * 3 + i) & 1);
+  }
+  f32x16_t acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  float total = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) total += acc[j][v];
+  if (total == -1.0f) sink[0] = total;   // never true (the sums are non-negative): keeps the loop alive
+}
+
+// flops issued by one launch of the probe
+double launch_mfma_probe(int blocks, int iters, float* sink, hipStream_t s) {
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
+  if (hipGetLastError() != hipSuccess) return -1.0;
+  return (double)blocks * 4 * iters * 16 * (2.0 * 32 * 32 * 16);
+}
+
 int launch_gemm(const GemmDesc& g, hipStream_t s) {
   // host-side shape checks: the kernels move 16-byte chunks and 64-wide k tiles
   if (g.N <= 0 || (g.mode != GEMM_RAGGED_M && g.M <= 0) || (g.mode != GEMM_RAGGED_K && g.K <= 0)) return BIGMAC_ERR_INVALID_ARG;

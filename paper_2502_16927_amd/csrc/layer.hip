@@ -360,6 +360,14 @@ double bigmac_permute_bytes(const bigmac_dims* D) {
   return 4.0 * (double)D->T * D->k * widths(*D).win * esize(D->dtype);
 }
 
+int bigmac_mfma_probe(int blocks, int iters, float* sink, double* flops, void* stream) {
+  if (blocks <= 0 || blocks > 65536 || iters <= 0 || iters > (1 << 20) || !sink || !flops) return BIGMAC_ERR_INVALID_ARG;
+  const double f = launch_mfma_probe(blocks, iters, sink, (hipStream_t)stream);
+  if (f < 0) return BIGMAC_ERR_HIP;
+  *flops = f;
+  return BIGMAC_OK;
+}
+
 int bigmac_set_stage_events(void* const* events) {
   g_stage_events = events;
   return BIGMAC_OK;

@@ -189,3 +189,15 @@ def test_grouped_ffn_matches_oracle(oracle, T, r, h, N, k, dtype, order):
     B.bigmac_grouped_ffn(dims, *args, None, o2, ws)        # inference: no pre-activation kept
     torch.cuda.synchronize()
     assert torch.equal(o, o2)
+
+
+def test_mfma_probe_counts_its_flops():
+    sink = torch.zeros(1, dtype=torch.float32, device=DEV)
+    flops = B.bigmac_mfma_probe(8, 10, sink)
+    torch.cuda.synchronize()
+    assert flops == 8 * 4 * 10 * 16 * 2.0 * 32 * 32 * 16
+    assert float(sink.item()) == 0.0            # never written
+    with pytest.raises(B.BigmacError):
+        B.bigmac_mfma_probe(0, 10, sink)
+    with pytest.raises(B.BigmacError):
+        B.bigmac_mfma_probe(8, 0, sink)
