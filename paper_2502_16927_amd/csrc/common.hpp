@@ -182,7 +182,7 @@ int launch_topk_gate(const bigmac_dims& D, const float* logits, int32_t* topk_id
 //   dlogit[t,j] = w[t,j] (dgate[t,j] - sum_m w[t,m] dgate[t,m])
 //   dL_out [T,N] (storage dtype) = dlogit scattered to its expert columns, zeros elsewhere
 //   dx_f32[t,:] = sum_j dlogit[t,j] * w_gate[:, idx[t,j]]      (overwritten)
-// ws: route_backward_ws_bytes (a transposed copy of w_gate).
+// ws: route_backward_ws_bytes (a transposed or bf16 copy of w_gate, or the k picked entries of dL per token).
 size_t route_backward_ws_bytes(const bigmac_dims& D);
 // With logits and share (the load-balance loss is on) the loss's gradient
 //   D.aux_alpha N / T * p[t,n] (share[n] - sum_e share[e] p[t,e]),  p = softmax(logits[t,:]),
