@@ -150,6 +150,7 @@ struct GemmDesc {
   int kwrap_b;               // B's k index is taken modulo this (0 = off); multiple of 64
   int tall_tile;             // bf16 only: 256-row workgroup tiles (ragged-M: the tile map must be built for them)
   int wide_k;                // bf16, k-contiguous A, K % 64 == 0: the square tile with 64-deep k tiles, two ring stages
+  int kloop_priority;        // MFMA kernels: raise the wave priority inside the k loop (see the kernel)
   int deep_tile;             // bf16, dense, store or accumulate (K % 64 == 0 with a k-contiguous operand): 128 x 64 outputs, 64-deep k tiles
 };
 // Rows per M tile of the ragged-M schedule for this dtype (the tile map must be built with it).

@@ -497,6 +497,9 @@ void mfma_gemm_kernel(GemmDesc p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+    // optional: waves in a k loop issue ahead of the CU's waves that are in an epilogue, so that the
+    // next operand request and the matrix instructions do not queue behind epilogue arithmetic
+    if (p.kloop_priority) __builtin_amdgcn_s_setprio(3);
     for (int it0 = 0; it0 < nk; it0 += NS) {
       static_for<0, NS>([&](auto stage) {
         constexpr int s = decltype(stage)::value;
@@ -555,6 +558,7 @@ void mfma_gemm_kernel(GemmDesc p) {
       });
     }
     BIGMAC_TRACE_AT(cur_id, 2);
+    if (p.kloop_priority) __builtin_amdgcn_s_setprio(0);
 
     // Once every wave has left the k loop the ring is free, and nothing is in flight into its
     // last stage (the last k step waited for everything that was requested into it).
