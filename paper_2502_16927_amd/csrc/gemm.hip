@@ -147,11 +147,22 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 // 16-byte chunk index inside an LDS tile.  "kc" tiles keep k contiguous (CPR = BK/8 chunks per
 // row); "tr" tiles keep the m (or n) index contiguous (CPR = BM/8 chunks per k row).  Both are
 // XOR-swizzled inside 128-byte lines so that fragment reads spread over the banks.
+#ifndef BIGMAC_KC_WINDOW
+#define BIGMAC_KC_WINDOW 16   // chunks per swizzle window: 16 = the 256 bytes the 64 LDS banks span
+#endif
 template <int CPR>
 __device__ __forceinline__ int lds_chunk_kc(int row, int cc) {
   int L = row * CPR + cc;
+#if BIGMAC_KC_WINDOW == 16
+  // 16 consecutive rows at one k chunk (what a quarter of a fragment read touches) lie in CPR
+  // consecutive windows; the XOR with the window index gives their CPR-chunk groups CPR different
+  // rotations, 16 different 16-byte bank groups in all
+  int w = L >> 4;
+  return (w << 4) | ((L & 15) ^ (w & (CPR - 1)));
+#else
   int line = L >> 3;
   return (line << 3) | ((L & 7) ^ (line & 7));
+#endif
 }
 template <int CPR>
 __device__ __forceinline__ int lds_chunk_tr(int krow, int cc) {
@@ -161,8 +172,13 @@ __device__ __forceinline__ int lds_chunk_tr(int krow, int cc) {
 // Inverse of the two swizzles: which (row, 16-byte column chunk) lives at LDS chunk position q.
 template <int CPR>
 __device__ __forceinline__ void lds_unchunk_kc(int q, int& row, int& cc) {
+#if BIGMAC_KC_WINDOW == 16
+  const int w = q >> 4;
+  const int L = (w << 4) | ((q & 15) ^ (w & (CPR - 1)));
+#else
   const int line = q >> 3;
   const int L = (line << 3) | ((q & 7) ^ (line & 7));
+#endif
   row = L / CPR;
   cc = L % CPR;
 }
