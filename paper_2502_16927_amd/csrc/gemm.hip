@@ -147,6 +147,9 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 // 16-byte chunk index inside an LDS tile.  "kc" tiles keep k contiguous (CPR = BK/8 chunks per
 // row); "tr" tiles keep the m (or n) index contiguous (CPR = BM/8 chunks per k row).  Both are
 // XOR-swizzled inside 128-byte lines so that fragment reads spread over the banks.
+#ifndef BIGMAC_TR_PIECES
+#define BIGMAC_TR_PIECES 1    // transposed tiles: permute 64-byte pieces (1) or 32-byte pairs of chunks (0, the first layout)
+#endif
 #ifndef BIGMAC_KC_WINDOW
 #define BIGMAC_KC_WINDOW 16   // chunks per swizzle window: 16 = the 256 bytes the 64 LDS banks span
 #endif
@@ -164,9 +167,23 @@ __device__ __forceinline__ int lds_chunk_kc(int row, int cc) {
   return (line << 3) | ((L & 7) ^ (line & 7));
 #endif
 }
+// A transposing fragment read takes 64 contiguous bytes from each of 4 consecutive k rows; the
+// 64-byte pieces of a row are permuted by (a function of) the row index so that those four land
+// on the four quarters of the 256 bytes the banks span, whatever the row pitch.
+template <int CPR>
+__device__ __forceinline__ int tr_piece_swap(int krow) {
+  static_assert(CPR >= 4 && (CPR & (CPR - 1)) == 0, "a power of two of chunks per row");
+  constexpr int ROWS_PER_WINDOW = CPR >= 16 ? 1 : 16 / CPR;     // rows that already differ in their position modulo 256 bytes
+  constexpr int PIECES = CPR / 4;                                // 64-byte pieces per row
+  return (krow / ROWS_PER_WINDOW) & 3 & (PIECES - 1);
+}
 template <int CPR>
 __device__ __forceinline__ int lds_chunk_tr(int krow, int cc) {
+#if BIGMAC_TR_PIECES
+  return krow * CPR + ((((cc >> 2) ^ tr_piece_swap<CPR>(krow)) << 2) | (cc & 3));
+#else
   return krow * CPR + ((((cc >> 1) ^ (krow & 3)) << 1) | (cc & 1));
+#endif
 }
 
 // Inverse of the two swizzles: which (row, 16-byte column chunk) lives at LDS chunk position q.
@@ -186,7 +203,11 @@ template <int CPR>
 __device__ __forceinline__ void lds_unchunk_tr(int q, int& krow, int& cc) {
   krow = q / CPR;
   const int pc = q % CPR;
+#if BIGMAC_TR_PIECES
+  cc = ((((pc >> 2) ^ tr_piece_swap<CPR>(krow)) << 2) | (pc & 3));
+#else
   cc = ((((pc >> 1) ^ (krow & 3)) << 1) | (pc & 1));
+#endif
 }
 
 // Moves one operand tile (ROWS x COLS elements, COLS contiguous in memory) from global memory
@@ -417,31 +438,31 @@ void mfma_gemm_kernel(GemmDesc p) {
 
   // Per-lane fragment positions for every k step of a tile.  k-contiguous tiles: chunk index of
   // sub-tile 0 (sub-tile i is 32 rows = a whole number of swizzle periods further).  Transposed
-  // tiles: byte offsets of the two 4-row reads for sub-tiles 0 and 1 (32 columns are half a
-  // swizzle period; sub-tile i is (i / 2) * 128 bytes past sub-tile i % 2).
-  unsigned pa[KS][2][2], pb[KS][2][2];   // LDS byte addresses within stage 0
+  // tiles: byte addresses of the two 4-row reads of every sub-tile (the piece permutation moves
+  // sub-tiles by lane-dependent amounts).
+  unsigned pa[KS][2][AK ? 1 : TM], pb[KS][2][BKC ? 1 : TN];   // LDS byte addresses within stage 0
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     if (AK) {
       pa[ks][0][0] = ring_at + lds_chunk_kc<BK / 8>(wm + (lane & 31), ks * 2 + (lane >> 5)) * 16;
     } else {
 #pragma unroll
-      for (int par = 0; par < 2; ++par) {
-        const int c = wm + par * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+      for (int i = 0; i < (AK ? 1 : TM); ++i) {
+        const int c = wm + i * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
-          pa[ks][jj][par] = ring_at + lds_chunk_tr<BM / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
+          pa[ks][jj][i] = ring_at + lds_chunk_tr<BM / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
       }
     }
     if (BKC) {
       pb[ks][0][0] = ring_at + A_CHUNKS * 16 + lds_chunk_kc<BK / 8>(wn + (lane & 31), ks * 2 + (lane >> 5)) * 16;
     } else {
 #pragma unroll
-      for (int par = 0; par < 2; ++par) {
-        const int c = wn + par * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+      for (int j = 0; j < (BKC ? 1 : TN); ++j) {
+        const int c = wn + j * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
-          pb[ks][jj][par] = ring_at + A_CHUNKS * 16 + lds_chunk_tr<BN / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
+          pb[ks][jj][j] = ring_at + A_CHUNKS * 16 + lds_chunk_tr<BN / 8>(ks * 16 + (lane >> 5) * 8 + jj * 4 + ((lane & 15) >> 2), c >> 3) * 16 + (c & 7) * 2;
       }
     }
   }
@@ -540,16 +561,16 @@ void mfma_gemm_kernel(GemmDesc p) {
             constexpr int i = decltype(sub)::value;
             if constexpr (AK) lds_read_b128<s * STAGE_BYTES + i * 32 * (BK / 8) * 16>(pa[ks][0][0], fa[ks][i].q);
             else {
-              lds_read_tr_b64<s * STAGE_BYTES + (i >> 1) * 128>(pa[ks][0][i & 1], fa[ks][i].h[0]);
-              lds_read_tr_b64<s * STAGE_BYTES + (i >> 1) * 128>(pa[ks][1][i & 1], fa[ks][i].h[1]);
+              lds_read_tr_b64<s * STAGE_BYTES>(pa[ks][0][i], fa[ks][i].h[0]);
+              lds_read_tr_b64<s * STAGE_BYTES>(pa[ks][1][i], fa[ks][i].h[1]);
             }
           });
           static_for<0, TN>([&](auto sub) {
             constexpr int j = decltype(sub)::value;
             if constexpr (BKC) lds_read_b128<s * STAGE_BYTES + j * 32 * (BK / 8) * 16>(pb[ks][0][0], fb[ks][j].q);
             else {
-              lds_read_tr_b64<s * STAGE_BYTES + (j >> 1) * 128>(pb[ks][0][j & 1], fb[ks][j].h[0]);
-              lds_read_tr_b64<s * STAGE_BYTES + (j >> 1) * 128>(pb[ks][1][j & 1], fb[ks][j].h[1]);
+              lds_read_tr_b64<s * STAGE_BYTES>(pb[ks][0][j], fb[ks][j].h[0]);
+              lds_read_tr_b64<s * STAGE_BYTES>(pb[ks][1][j], fb[ks][j].h[1]);
             }
           });
         });
