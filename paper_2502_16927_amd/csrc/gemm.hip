@@ -146,26 +146,16 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 // 16-byte chunk index inside an LDS tile.  "kc" tiles keep k contiguous (CPR = BK/8 chunks per
 // row); "tr" tiles keep the m (or n) index contiguous (CPR = BM/8 chunks per k row).  Both are
-// XOR-swizzled inside 128-byte lines so that fragment reads spread over the banks.
-#ifndef BIGMAC_TR_PIECES
-#define BIGMAC_TR_PIECES 1    // transposed tiles: permute 64-byte pieces (1) or 32-byte pairs of chunks (0, the first layout)
-#endif
-#ifndef BIGMAC_KC_WINDOW
-#define BIGMAC_KC_WINDOW 16   // chunks per swizzle window: 16 = the 256 bytes the 64 LDS banks span
-#endif
+// XOR-swizzled so that what one pass of a fragment read touches (256 bytes, the span of the 64
+// banks) falls on all banks once.
 template <int CPR>
 __device__ __forceinline__ int lds_chunk_kc(int row, int cc) {
   int L = row * CPR + cc;
-#if BIGMAC_KC_WINDOW == 16
   // 16 consecutive rows at one k chunk (what a quarter of a fragment read touches) lie in CPR
   // consecutive windows; the XOR with the window index gives their CPR-chunk groups CPR different
   // rotations, 16 different 16-byte bank groups in all
-  int w = L >> 4;
+  int w = L >> 4;   // window of 16 chunks = the 256 bytes the 64 banks span
   return (w << 4) | ((L & 15) ^ (w & (CPR - 1)));
-#else
-  int line = L >> 3;
-  return (line << 3) | ((L & 7) ^ (line & 7));
-#endif
 }
 // A transposing fragment read takes 64 contiguous bytes from each of 4 consecutive k rows; the
 // 64-byte pieces of a row are permuted by (a function of) the row index so that those four land
@@ -179,23 +169,14 @@ __device__ __forceinline__ int tr_piece_swap(int krow) {
 }
 template <int CPR>
 __device__ __forceinline__ int lds_chunk_tr(int krow, int cc) {
-#if BIGMAC_TR_PIECES
   return krow * CPR + ((((cc >> 2) ^ tr_piece_swap<CPR>(krow)) << 2) | (cc & 3));
-#else
-  return krow * CPR + ((((cc >> 1) ^ (krow & 3)) << 1) | (cc & 1));
-#endif
 }
 
 // Inverse of the two swizzles: which (row, 16-byte column chunk) lives at LDS chunk position q.
 template <int CPR>
 __device__ __forceinline__ void lds_unchunk_kc(int q, int& row, int& cc) {
-#if BIGMAC_KC_WINDOW == 16
   const int w = q >> 4;
   const int L = (w << 4) | ((q & 15) ^ (w & (CPR - 1)));
-#else
-  const int line = q >> 3;
-  const int L = (line << 3) | ((q & 7) ^ (line & 7));
-#endif
   row = L / CPR;
   cc = L % CPR;
 }
@@ -203,11 +184,7 @@ template <int CPR>
 __device__ __forceinline__ void lds_unchunk_tr(int q, int& krow, int& cc) {
   krow = q / CPR;
   const int pc = q % CPR;
-#if BIGMAC_TR_PIECES
   cc = ((((pc >> 2) ^ tr_piece_swap<CPR>(krow)) << 2) | (pc & 3));
-#else
-  cc = ((((pc >> 1) ^ (krow & 3)) << 1) | (pc & 1));
-#endif
 }
 
 // Moves one operand tile (ROWS x COLS elements, COLS contiguous in memory) from global memory
