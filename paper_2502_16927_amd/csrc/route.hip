@@ -142,9 +142,12 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
     xoff[i] = q < XCH ? (unsigned)((q / XROW) * d * sizeof(XT) + (q % XROW) * 16) : 0x80000000u;
   }
 #pragma unroll
-  for (int i = 0; i < WL; ++i) {   // LDS position q holds column chunk (q & 3) ^ ((row >> 1) & 3) of row q >> 2
+  // LDS position q holds column chunk (q & 3) ^ ((row >> 2) & 3) of row q >> 2: the 16 rows that one
+  // pass of a 16-byte read touches (64 bytes apart, 4 to every 256 bytes the banks span) then fall
+  // on 16 different bank groups
+  for (int i = 0; i < WL; ++i) {
     const int q = i * 256 + threadIdx.x, row = q >> 2;
-    woff[i] = (unsigned)((row * N + (((q & 3) ^ ((row >> 1) & 3)) << 2)) * 4);
+    woff[i] = (unsigned)((row * N + (((q & 3) ^ ((row >> 2) & 3)) << 2)) * 4);
   }
   auto issue = [&](int tile, uint4* xs, uint4* ws) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -176,7 +179,7 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
       float wv[R_NB];
 #pragma unroll
       for (int c4 = 0; c4 < 4; ++c4) {
-        const uint4 w = ws[row * 4 + (c4 ^ ((row >> 1) & 3))];
+        const uint4 w = ws[row * 4 + (c4 ^ ((row >> 2) & 3))];
         wv[c4 * 4 + 0] = __uint_as_float(w.x); wv[c4 * 4 + 1] = __uint_as_float(w.y);
         wv[c4 * 4 + 2] = __uint_as_float(w.z); wv[c4 * 4 + 3] = __uint_as_float(w.w);
       }
@@ -560,20 +563,29 @@ __global__ __launch_bounds__(ROUTER_DX_THREADS) void router_dx_kernel(const int3
     pick_e[u] = topk_idx[at];
   }
   if ((N & 3) == 0) {
-    // the rows are one contiguous piece of w_gate: 16-byte loads, a batch in flight per lane;
-    // rows past d are clamped to the last one (their outputs are never stored)
-    const int qrow = N >> 2, quads = TC * qrow, last = (d - 1 - c0) * qrow + qrow - 1;
+    // 16-byte loads, a batch in flight per lane.  Work item g = (group, quad in row % 4, row % 16):
+    // 16 lanes take the same quad of 16 consecutive rows, 4 such sets make a wavefront.  Its four
+    // transposing stores then write 16 consecutive words in each of 4 rows of wt that lie
+    // 4 * PITCH = 16 (mod 64) words apart: all 64 banks once.  (In row-major order of w_gate the
+    // stores of a wavefront would fall on 4 banks.)  Rows past d are clamped to the last one
+    // (their outputs are never stored).
+    const int qrow = N >> 2, qsets = (qrow + 3) >> 2, items = (TC / 16) * qsets * 64, last_row = d - 1 - c0;
     const float4* src = (const float4*)(w_gate + (size_t)c0 * N);
-    for (int i0 = 0; i0 < quads; i0 += ROUTER_DX_THREADS * BATCH) {
+    for (int g0 = 0; g0 < items; g0 += ROUTER_DX_THREADS * BATCH) {
       float4 v[BATCH];
 #pragma unroll
-      for (int u = 0; u < BATCH; ++u) v[u] = src[min(min(i0 + u * ROUTER_DX_THREADS + (int)threadIdx.x, quads - 1), last)];
+      for (int u = 0; u < BATCH; ++u) {
+        const int g = g0 + u * ROUTER_DX_THREADS + (int)threadIdx.x, group = g >> 6;
+        const int c = min((group % (TC / 16)) * 16 + (g & 15), last_row);
+        const int n4 = min((group / (TC / 16)) * 4 + ((g >> 4) & 3), qrow - 1);
+        v[u] = src[c * qrow + n4];
+      }
 #pragma unroll
       for (int u = 0; u < BATCH; ++u) {
-        const int i = i0 + u * ROUTER_DX_THREADS + (int)threadIdx.x;
-        if (i < quads) {
-          const int c = i / qrow, n = (i - c * qrow) * 4;
-          float* dst = wt + n * PITCH + c;
+        const int g = g0 + u * ROUTER_DX_THREADS + (int)threadIdx.x, group = g >> 6;
+        const int c = (group % (TC / 16)) * 16 + (g & 15), n4 = (group / (TC / 16)) * 4 + ((g >> 4) & 3);
+        if (g < items && n4 < qrow) {
+          float* dst = wt + n4 * 4 * PITCH + c;
           dst[0] = v[u].x; dst[PITCH] = v[u].y; dst[2 * PITCH] = v[u].z; dst[3 * PITCH] = v[u].w;
         }
       }
