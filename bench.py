@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM = 8.0e12          # bytes/s, MI355X HBM3E
 PEAK_MFMA_BF16 = 2.5e15    # flop/s, dense bf16 MFMA
-PEAK_ALU_F32 = 78.6e12     # flop/s: 256 CUs x 64 fp32 lanes x 2 (fma) x 2.4 GHz, no packed fp32 ops
+PEAK_ALU_F32 = 157.3e12    # flop/s, published fp32 vector peak (unpacked v_fmac_f32 measured at 146 TFLOP/s with two waves per SIMD)
 
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, the
