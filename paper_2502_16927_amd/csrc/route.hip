@@ -10,6 +10,9 @@ namespace bigmac {
 
 namespace {
 
+#ifndef ROUTER_TB_LARGE
+#define ROUTER_TB_LARGE 8   // tokens per wavefront of the pipelined router kernel when there are plenty of tokens
+#endif
 constexpr int R_TB = 8;     // tokens per wave
 constexpr int R_NB = 16;    // experts per pass
 constexpr int R_QT = 4;     // 64-row blocks of W_g staged per LDS tile
@@ -107,6 +110,29 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const XT* __restrict
   }
 }
 
+// LDS reads with a compile-time instruction offset, as assembly (see the kernel below for why).
+template <int OFFSET>
+__device__ __forceinline__ void router_lds_read_u16(unsigned addr, unsigned& v) {
+  asm volatile("ds_read_u16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+}
+template <int OFFSET>
+__device__ __forceinline__ void router_lds_read_b32(unsigned addr, unsigned& v) {
+  asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+}
+typedef unsigned int router_u32x4 __attribute__((ext_vector_type(4)));
+template <int OFFSET>
+__device__ __forceinline__ void router_lds_read_b128(unsigned addr, router_u32x4& v) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+}
+template <int I> struct RouterIndex { static constexpr int value = I; };
+template <int BEGIN, int END, typename F>
+__device__ __forceinline__ void router_static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(RouterIndex<BEGIN>{});
+    router_static_for<BEGIN + 1, END>(f);
+  }
+}
+
 // Same computation for N % 4 == 0, software-pipelined: the 32 x 256 token tile and the 256 x 16
 // router tile of the next step travel global -> LDS directly (16 bytes per lane, no registers)
 // while the current step's 512 fused multiply-adds per lane run.  Token rows past T and router
@@ -167,19 +193,51 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
   float acc[ACCS];
 #pragma unroll
   for (int v = 0; v < ACCS; ++v) acc[v] = 0.0f;
+  // The tile reads are assembly: for LDS accesses it can see, the compiler waits for every
+  // direct-to-LDS load in flight, the next tile's included, which would put the loads and the
+  // arithmetic one after the other instead of side by side.  The only waits on the loads are the
+  // counter waits of the loop below.
   auto compute = [&](int tile, const uint4* xs, const uint4* ws) {
-    const XT* xt = (const XT*)xs + (wave * TB) * 256 + lane;
+    // one address register for the token rows, four for the router columns (the swizzle term
+    // (row >> 2) & 3 is the same in every 64-row block); everything else is instruction offsets
+    const unsigned xat = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)xs + (unsigned)(((wave * TB) * 256 + lane) * sizeof(XT));
+    const unsigned wbase = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)ws;
+    unsigned wat[4];
 #pragma unroll
-    for (int qq = 0; qq < 4; ++qq) {
-      if (tile * 4 + qq >= nq) break;
-      float xv[TB];
+    for (int c4 = 0; c4 < 4; ++c4) wat[c4] = wbase + (unsigned)((lane * 4 + (c4 ^ ((lane >> 2) & 3))) * 16);
+    unsigned xraw[2][TB];
+    router_u32x4 wraw[2][4];
+    // the reads of 64-row block QQ, into register set QQ % 2
+    auto request = [&](auto block) {
+      constexpr int QQ = decltype(block)::value;
+      router_static_for<0, TB>([&](auto token) {
+        constexpr int I = decltype(token)::value;
+        if constexpr (sizeof(XT) == 2) router_lds_read_u16<(I * 256 + QQ * 64) * 2>(xat, xraw[QQ & 1][I]);
+        else router_lds_read_b32<(I * 256 + QQ * 64) * 4>(xat, xraw[QQ & 1][I]);
+      });
+      router_static_for<0, 4>([&](auto chunk) {
+        constexpr int C4 = decltype(chunk)::value;
+        router_lds_read_b128<QQ * 64 * 4 * 16>(wat[C4], wraw[QQ & 1][C4]);
+      });
+    };
+    request(RouterIndex<0>{});
+    router_static_for<0, 4>([&](auto block) {
+      constexpr int QQ = decltype(block)::value;
+      if (tile * 4 + QQ >= nq) return;
+      // block QQ has arrived (it was requested before the previous block's arithmetic); the next
+      // block is requested now and arrives while this one's 128 multiply-adds run
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-      for (int i = 0; i < TB; ++i) xv[i] = Elem<XT>::load(xt + i * 256 + qq * 64);
-      const int row = qq * 64 + lane;
-      float wv[R_NB];
+      for (int i = 0; i < TB; ++i) asm volatile("" : "+v"(xraw[QQ & 1][i]));
+#pragma unroll
+      for (int c4 = 0; c4 < 4; ++c4) asm volatile("" : "+v"(wraw[QQ & 1][c4]));
+      if constexpr (QQ + 1 < 4) request(RouterIndex<QQ + 1>{});   // (a block past d holds zeros or stale rows: never used)
+      float xv[TB], wv[R_NB];
+#pragma unroll
+      for (int i = 0; i < TB; ++i) xv[i] = __uint_as_float(sizeof(XT) == 2 ? xraw[QQ & 1][i] << 16 : xraw[QQ & 1][i]);
 #pragma unroll
       for (int c4 = 0; c4 < 4; ++c4) {
-        const uint4 w = ws[row * 4 + (c4 ^ ((row >> 2) & 3))];
+        const router_u32x4 w = wraw[QQ & 1][c4];
         wv[c4 * 4 + 0] = __uint_as_float(w.x); wv[c4 * 4 + 1] = __uint_as_float(w.y);
         wv[c4 * 4 + 2] = __uint_as_float(w.z); wv[c4 * 4 + 3] = __uint_as_float(w.w);
       }
@@ -187,7 +245,8 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
       for (int i = 0; i < TB; ++i)
 #pragma unroll
         for (int c = 0; c < R_NB; ++c) acc[i * R_NB + c] = fmaf(xv[i], wv[c], acc[i * R_NB + c]);
-    }
+    });
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // a request past the last block used: done before the stage is refilled
   };
   issue(0, xs0, ws0);
   for (int tile = 0; tile < ntiles; tile += 2) {
@@ -209,7 +268,7 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
   // (the same addition, a + b, in both).  The sum of accumulator v ends on the lanes whose top
   // bits spell v.
   constexpr int SCATTER_STEPS = ACCS >= 64 ? 6 : (ACCS == 32 ? 5 : 4);
-  static_assert(ACCS == 128 || ACCS == 32 || ACCS == 16, "1, 2 or 8 tokens per wavefront");
+  static_assert(ACCS == 128 || ACCS == 64 || ACCS == 32 || ACCS == 16, "1, 2, 4 or 8 tokens per wavefront");
 #pragma unroll
   for (int step = 0; step < 6; ++step) {
     const int off = 32 >> step;
@@ -649,16 +708,18 @@ int launch_router_logits(const bigmac_dims& D, const void* x, const float* w_gat
   }
   // tokens per wavefront: 8 unless that leaves most CUs without a workgroup
   const long groups8 = (long)((D.T + 31) / 32) * gy;
-  const int tb = groups8 >= 1024 ? 8 : (groups8 * 4 >= 512 ? 2 : 1);
+  const int tb = groups8 >= 1024 ? ROUTER_TB_LARGE : (groups8 * 4 >= 512 ? 2 : 1);
 #define BIGMAC_ROUTER(XT, TBV)                                                                                       \
   hipLaunchKernelGGL((router_logits_pipelined_kernel<XT, TBV>), dim3((D.T + 4 * TBV - 1) / (4 * TBV), gy), block, 0, s, \
                      (const XT*)x, w_gate, bias, logits, D.T, D.d, D.N)
   if (D.dtype == BIGMAC_BF16) {
     if (tb == 8) BIGMAC_ROUTER(bf16_t, 8);
+    else if (tb == 4) BIGMAC_ROUTER(bf16_t, 4);
     else if (tb == 2) BIGMAC_ROUTER(bf16_t, 2);
     else BIGMAC_ROUTER(bf16_t, 1);
   } else {
     if (tb == 8) BIGMAC_ROUTER(float, 8);
+    else if (tb == 4) BIGMAC_ROUTER(float, 4);
     else if (tb == 2) BIGMAC_ROUTER(float, 2);
     else BIGMAC_ROUTER(float, 1);
   }
