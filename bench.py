@@ -225,7 +225,7 @@ def main():
     B.StageEvents.clear()
     # Pass 2, the timed region: the same step (the library only enqueues kernels, no memsets,
     # no synchronisation) captured once in a HIP graph and replayed K times, which removes the
-    # host's launch gaps between the ~35 kernels of a step.
+    # host's launch gaps between the ~33 kernels of a step.
     elapsed, timed = eager_elapsed, "eager launches"
     if not args.no_graph:
         graph = torch.cuda.CUDAGraph()
