@@ -13,6 +13,9 @@ namespace {
 #ifndef ROUTER_TB_LARGE
 #define ROUTER_TB_LARGE 8   // tokens per wavefront of the pipelined router kernel when there are plenty of tokens
 #endif
+#ifndef ROUTER_SLICES
+#define ROUTER_SLICES 2     // 16-expert slices per workgroup of the pipelined router kernel when there are plenty of workgroups
+#endif
 constexpr int R_TB = 8;     // tokens per wave
 constexpr int R_NB = 16;    // experts per pass
 constexpr int R_QT = 4;     // 64-row blocks of W_g staged per LDS tile
@@ -140,7 +143,10 @@ __device__ __forceinline__ void router_static_for(F&& f) {
 #define BIGMAC_ROUTER_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 // TB = tokens per wavefront (8 for large T; 1 or 2 when T is small, so that the few tokens still
 // spread over many CUs).  The summation order does not depend on it.
-template <typename XT, int TB>
+// SL = 16-expert slices a workgroup computes one after the other on its token tile: the next
+// slice's first tiles are requested before the reduction of the current one, so the fixed cost
+// of a workgroup (set-up, first-tile latency) is paid once per SL slices.
+template <typename XT, int TB, int SL>
 __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* __restrict__ x, const float* __restrict__ wg,
                                                                       const float* __restrict__ bias, float* __restrict__ logits,
                                                                       int T, int d, int N) {
@@ -155,11 +161,15 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
   __shared__ uint4 ws1[WCH];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int tb = blockIdx.x * TOKENS, t0 = tb + wave * TB;
-  const int n0 = blockIdx.y * R_NB;
+  int n0 = blockIdx.y * (SL * R_NB);
   const int nq = d / 64, ntiles = (nq + 3) / 4;
-  const int rows = min(TOKENS, T - tb), cols = min(R_NB, N - n0);
+  const int rows = min(TOKENS, T - tb);
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)(x + (size_t)tb * d), 0, (int)((size_t)rows * d * sizeof(XT)), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)(wg + n0), 0, (int)(((size_t)(d - 1) * N + cols) * 4), 0x00020000);
+  auto router_columns = [&](int first) {   // the slice's 16 columns of w_gate as a buffer
+    const int cols = min(R_NB, N - first);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(wg + first), 0, (int)(((size_t)(d - 1) * N + cols) * 4), 0x00020000);
+  };
+  __amdgpu_buffer_rsrc_t rw = router_columns(n0);
   const int wave_chunk = __builtin_amdgcn_readfirstlane((int)(threadIdx.x & ~63u));
   unsigned xoff[XL], woff[WL];
 #pragma unroll
@@ -191,8 +201,6 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
   };
   constexpr int ACCS = TB * R_NB;
   float acc[ACCS];
-#pragma unroll
-  for (int v = 0; v < ACCS; ++v) acc[v] = 0.0f;
   // The tile reads are assembly: for LDS accesses it can see, the compiler waits for every
   // direct-to-LDS load in flight, the next tile's included, which would put the loads and the
   // arithmetic one after the other instead of side by side.  The only waits on the loads are the
@@ -249,6 +257,10 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // a request past the last block used: done before the stage is refilled
   };
   issue(0, xs0, ws0);
+#pragma unroll 1
+  for (int sl = 0; sl < SL; ++sl) {
+#pragma unroll
+  for (int v = 0; v < ACCS; ++v) acc[v] = 0.0f;
   for (int tile = 0; tile < ntiles; tile += 2) {
     if (tile + 1 < ntiles) { issue(tile + 1, xs1, ws1); BIGMAC_ROUTER_WAIT_VMCNT(XL + WL); }
     else BIGMAC_ROUTER_WAIT_VMCNT(0);
@@ -261,6 +273,15 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
     __builtin_amdgcn_s_barrier();
     compute(tile + 1, xs1, ws1);
     __builtin_amdgcn_s_barrier();
+  }
+  // every wavefront has left the last tile: the next slice's first tile can be on its way while
+  // this slice is reduced and stored
+  const int n_cur = n0;
+  const bool more = sl + 1 < SL && n0 + R_NB < N;
+  if (more) {
+    n0 += R_NB;
+    rw = router_columns(n0);
+    issue(0, xs0, ws0);
   }
   // Halving tree (lane l with lane l ^ off, off = 32 .. 1).  While a lane still holds two or more
   // sums the step is a reduce-scatter: each half of the pair keeps one half of the sums (see
@@ -291,13 +312,15 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
 #pragma unroll
     for (int u = 0; u < LEFT; ++u) {
       const int v = LEFT * (lane >> SHARE) + u;
-      const int t = t0 + v / R_NB, n = n0 + v % R_NB;
+      const int t = t0 + v / R_NB, n = n_cur + v % R_NB;
       if (t < T && n < N) {
         float val = acc[u];
         if (bias) val = val + bias[n];
         logits[(size_t)t * N + n] = val;
       }
     }
+  }
+  if (!more) break;
   }
 }
 
@@ -706,22 +729,24 @@ int launch_router_logits(const bigmac_dims& D, const void* x, const float* w_gat
     BIGMAC_CHECK_LAUNCH();
     return BIGMAC_OK;
   }
-  // tokens per wavefront: 8 unless that leaves most CUs without a workgroup
+  // tokens per wavefront: 8 unless that leaves most CUs without a workgroup; two expert slices per
+  // workgroup while that still gives every CU two workgroups
   const long groups8 = (long)((D.T + 31) / 32) * gy;
-  const int tb = groups8 >= 1024 ? ROUTER_TB_LARGE : (groups8 * 4 >= 512 ? 2 : 1);
-#define BIGMAC_ROUTER(XT, TBV)                                                                                       \
-  hipLaunchKernelGGL((router_logits_pipelined_kernel<XT, TBV>), dim3((D.T + 4 * TBV - 1) / (4 * TBV), gy), block, 0, s, \
+  const int tb = groups8 >= 1024 ? 8 : (groups8 * 4 >= 512 ? 2 : 1);
+  const int sl = tb == 8 && gy >= 2 && (long)((D.T + 31) / 32) * ((gy + 1) / 2) >= 512 ? ROUTER_SLICES : 1;
+#define BIGMAC_ROUTER(XT, TBV, SLV)                                                                                  \
+  hipLaunchKernelGGL((router_logits_pipelined_kernel<XT, TBV, SLV>), dim3((D.T + 4 * TBV - 1) / (4 * TBV), (gy + SLV - 1) / SLV), block, 0, s, \
                      (const XT*)x, w_gate, bias, logits, D.T, D.d, D.N)
   if (D.dtype == BIGMAC_BF16) {
-    if (tb == 8) BIGMAC_ROUTER(bf16_t, 8);
-    else if (tb == 4) BIGMAC_ROUTER(bf16_t, 4);
-    else if (tb == 2) BIGMAC_ROUTER(bf16_t, 2);
-    else BIGMAC_ROUTER(bf16_t, 1);
+    if (tb == 8 && sl == 2) BIGMAC_ROUTER(bf16_t, 8, 2);
+    else if (tb == 8) BIGMAC_ROUTER(bf16_t, 8, 1);
+    else if (tb == 2) BIGMAC_ROUTER(bf16_t, 2, 1);
+    else BIGMAC_ROUTER(bf16_t, 1, 1);
   } else {
-    if (tb == 8) BIGMAC_ROUTER(float, 8);
-    else if (tb == 4) BIGMAC_ROUTER(float, 4);
-    else if (tb == 2) BIGMAC_ROUTER(float, 2);
-    else BIGMAC_ROUTER(float, 1);
+    if (tb == 8 && sl == 2) BIGMAC_ROUTER(float, 8, 2);
+    else if (tb == 8) BIGMAC_ROUTER(float, 8, 1);
+    else if (tb == 2) BIGMAC_ROUTER(float, 2, 1);
+    else BIGMAC_ROUTER(float, 1, 1);
   }
 #undef BIGMAC_ROUTER
   BIGMAC_CHECK_LAUNCH();
