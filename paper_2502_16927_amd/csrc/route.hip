@@ -293,7 +293,23 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
 #pragma unroll
   for (int step = 0; step < 6; ++step) {
     const int off = 32 >> step;
-    if (step < SCATTER_STEPS) {
+    if (step < SCATTER_STEPS && off >= 16) {
+      // distances 32 and 16: one swap instruction exchanges the upper half (odd 16-lane rows) of
+      // acc[v] with the lower half (even rows) of acc[v + half]; afterwards every lane holds what
+      // it keeps in one register and what its partner sent in the other, and a + b = b + a
+      const int half = ACCS >> (step + 1);
+#pragma unroll
+      for (int v = 0; v < half; ++v) {
+        const unsigned a = __float_as_uint(acc[v]), b = __float_as_uint(acc[v + half]);
+        if (off == 32) {
+          const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+          acc[v] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+        } else {
+          const auto r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+          acc[v] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+        }
+      }
+    } else if (step < SCATTER_STEPS) {
       const int half = ACCS >> (step + 1);
       const bool hi = (lane & off) != 0;
 #pragma unroll
