@@ -13,6 +13,12 @@ namespace {
 #ifndef ROUTER_TB_LARGE
 #define ROUTER_TB_LARGE 8   // tokens per wavefront of the pipelined router kernel when there are plenty of tokens
 #endif
+#ifndef ROUTER_TILE_BLOCKS
+#define ROUTER_TILE_BLOCKS 2      // 64-row blocks of d per LDS tile of the pipelined router kernel
+#endif
+#ifndef ROUTER_TILE_STAGES
+#define ROUTER_TILE_STAGES 3      // tiles in its ring (at most 4: the waits count up to two younger tiles); 2 to 4 measured alike
+#endif
 #ifndef ROUTER_SLICES
 #define ROUTER_SLICES 2     // 16-expert slices per workgroup of the pipelined router kernel when there are plenty of workgroups
 #endif
@@ -136,10 +142,11 @@ __device__ __forceinline__ void router_static_for(F&& f) {
   }
 }
 
-// Same computation for N % 4 == 0, software-pipelined: the 32 x 256 token tile and the 256 x 16
-// router tile of the next step travel global -> LDS directly (16 bytes per lane, no registers)
-// while the current step's 512 fused multiply-adds per lane run.  Token rows past T and router
-// rows past d lie outside the buffer ranges and arrive as zeros; they are never used anyway.
+// Same computation for N % 4 == 0, software-pipelined: token tiles (32 tokens x 64 QQT elements)
+// and router tiles (64 QQT rows x 16 columns) travel global -> LDS directly (16 bytes per lane, no
+// registers) through a ring of S stages, S - 1 tiles in flight while the 128 QQT fused
+// multiply-adds per lane of the current one run.  Token rows past T and router rows past d lie
+// outside the buffer ranges and arrive as zeros; they are never used anyway.
 #define BIGMAC_ROUTER_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 // TB = tokens per wavefront (8 for large T; 1 or 2 when T is small, so that the few tokens still
 // spread over many CUs).  The summation order does not depend on it.
@@ -150,19 +157,22 @@ template <typename XT, int TB, int SL>
 __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* __restrict__ x, const float* __restrict__ wg,
                                                                       const float* __restrict__ bias, float* __restrict__ logits,
                                                                       int T, int d, int N) {
-  constexpr int XROW = 256 * sizeof(XT) / 16;       // 16-byte chunks per token row of a tile
+  constexpr int QQT = ROUTER_TILE_BLOCKS;           // 64-row blocks of d per tile
+  constexpr int S = sizeof(XT) == 2 ? ROUTER_TILE_STAGES : 3;   // ring of S tiles, S - 1 in flight while one is consumed
+  static_assert(S >= 2 && S <= 4 && QQT >= 1 && QQT <= 4, "the counter waits below cover up to two younger tiles");
+  constexpr int TROWS = 64 * QQT;                   // rows of d per tile
+  constexpr int XROW = TROWS * sizeof(XT) / 16;     // 16-byte chunks per token row of a tile
   constexpr int TOKENS = 4 * TB;                    // tokens per workgroup
   constexpr int XCH = TOKENS * XROW;                // chunks of a token tile
-  constexpr int WCH = 256 * 4;                      // chunks of a router tile (256 rows x 16 floats)
-  constexpr int XL = (XCH + 255) / 256, WL = WCH / 256;   // loads per thread
-  __shared__ uint4 xs0[XL * 256];                   // (a tile of fewer than 256 chunks is padded: the surplus lanes load out of range)
-  __shared__ uint4 xs1[XL * 256];
-  __shared__ uint4 ws0[WCH];
-  __shared__ uint4 ws1[WCH];
+  constexpr int WCH = TROWS * 4;                    // chunks of a router tile (TROWS rows x 16 floats)
+  constexpr int XL = (XCH + 255) / 256, WL = (WCH + 255) / 256;   // loads per thread
+  constexpr int LPT = XL + WL;
+  __shared__ uint4 xring[S * XL * 256];             // (a tile of fewer than 256 chunks is padded: the surplus lanes load out of range)
+  __shared__ uint4 wring[S * WL * 256];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int tb = blockIdx.x * TOKENS, t0 = tb + wave * TB;
   int n0 = blockIdx.y * (SL * R_NB);
-  const int nq = d / 64, ntiles = (nq + 3) / 4;
+  const int nq = d / 64, ntiles = (nq + QQT - 1) / QQT;
   const int rows = min(TOKENS, T - tb);
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)(x + (size_t)tb * d), 0, (int)((size_t)rows * d * sizeof(XT)), 0x00020000);
   auto router_columns = [&](int first) {   // the slice's 16 columns of w_gate as a buffer
@@ -177,51 +187,58 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
     const int q = i * 256 + threadIdx.x;
     xoff[i] = q < XCH ? (unsigned)((q / XROW) * d * sizeof(XT) + (q % XROW) * 16) : 0x80000000u;
   }
-#pragma unroll
   // LDS position q holds column chunk (q & 3) ^ ((row >> 2) & 3) of row q >> 2: the 16 rows that one
   // pass of a 16-byte read touches (64 bytes apart, 4 to every 256 bytes the banks span) then fall
   // on 16 different bank groups
+#pragma unroll
   for (int i = 0; i < WL; ++i) {
     const int q = i * 256 + threadIdx.x, row = q >> 2;
-    woff[i] = (unsigned)((row * N + (((q & 3) ^ ((row >> 2) & 3)) << 2)) * 4);
+    woff[i] = q < WCH ? (unsigned)((row * N + (((q & 3) ^ ((row >> 2) & 3)) << 2)) * 4) : 0x80000000u;
   }
-  auto issue = [&](int tile, uint4* xs, uint4* ws) {
+  auto issue = [&](int tile) {
+    uint4* xs = xring + (tile % S) * (XL * 256);
+    uint4* ws = wring + (tile % S) * (WL * 256);
 #if defined(__HIP_DEVICE_COMPILE__)
 #pragma unroll
     for (int i = 0; i < XL; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(xs + i * 256 + wave_chunk), 16,
-                                               xoff[i] + (unsigned)(tile * 256 * sizeof(XT)), 0, 0, 0);
+                                               xoff[i] + (unsigned)(tile * TROWS * sizeof(XT)), 0, 0, 0);
 #pragma unroll
     for (int i = 0; i < WL; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void*)(ws + i * 256 + wave_chunk), 16,
-                                               woff[i] + (unsigned)(tile * 256 * N * 4), 0, 0, 0);
+                                               woff[i] + (unsigned)(tile * TROWS * N * 4), 0, 0, 0);
 #else
-    (void)tile; (void)xs; (void)ws;
+    (void)xs; (void)ws;
 #endif
   };
   constexpr int ACCS = TB * R_NB;
   float acc[ACCS];
   // The tile reads are assembly: for LDS accesses it can see, the compiler waits for every
-  // direct-to-LDS load in flight, the next tile's included, which would put the loads and the
+  // direct-to-LDS load in flight, the next tiles' included, which would put the loads and the
   // arithmetic one after the other instead of side by side.  The only waits on the loads are the
   // counter waits of the loop below.
-  auto compute = [&](int tile, const uint4* xs, const uint4* ws) {
-    // one address register for the token rows, four for the router columns (the swizzle term
-    // (row >> 2) & 3 is the same in every 64-row block); everything else is instruction offsets
-    const unsigned xat = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)xs + (unsigned)(((wave * TB) * 256 + lane) * sizeof(XT));
-    const unsigned wbase = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)ws;
+  const unsigned xring_at = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)xring + (unsigned)(((wave * TB) * TROWS + lane) * sizeof(XT));
+  const unsigned wring_at = (unsigned)(size_t)(__attribute__((address_space(3))) const void*)wring;
+  unsigned wlane[4];   // the swizzle term (row >> 2) & 3 is the same in every 64-row block
+#pragma unroll
+  for (int c4 = 0; c4 < 4; ++c4) wlane[c4] = wring_at + (unsigned)((lane * 4 + (c4 ^ ((lane >> 2) & 3))) * 16);
+  auto compute = [&](int tile) {
+    // one address register for the token rows, four for the router columns; everything else is
+    // instruction offsets
+    const unsigned stage = (unsigned)(tile % S);
+    const unsigned xat = xring_at + stage * (XL * 256 * 16);
     unsigned wat[4];
 #pragma unroll
-    for (int c4 = 0; c4 < 4; ++c4) wat[c4] = wbase + (unsigned)((lane * 4 + (c4 ^ ((lane >> 2) & 3))) * 16);
+    for (int c4 = 0; c4 < 4; ++c4) wat[c4] = wlane[c4] + stage * (WL * 256 * 16);
     unsigned xraw[2][TB];
     router_u32x4 wraw[2][4];
-    // the reads of 64-row block QQ, into register set QQ % 2
+    // the reads of 64-row block QQ of the tile, into register set QQ % 2
     auto request = [&](auto block) {
       constexpr int QQ = decltype(block)::value;
       router_static_for<0, TB>([&](auto token) {
         constexpr int I = decltype(token)::value;
-        if constexpr (sizeof(XT) == 2) router_lds_read_u16<(I * 256 + QQ * 64) * 2>(xat, xraw[QQ & 1][I]);
-        else router_lds_read_b32<(I * 256 + QQ * 64) * 4>(xat, xraw[QQ & 1][I]);
+        if constexpr (sizeof(XT) == 2) router_lds_read_u16<(I * TROWS + QQ * 64) * 2>(xat, xraw[QQ & 1][I]);
+        else router_lds_read_b32<(I * TROWS + QQ * 64) * 4>(xat, xraw[QQ & 1][I]);
       });
       router_static_for<0, 4>([&](auto chunk) {
         constexpr int C4 = decltype(chunk)::value;
@@ -229,9 +246,9 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
       });
     };
     request(RouterIndex<0>{});
-    router_static_for<0, 4>([&](auto block) {
+    router_static_for<0, QQT>([&](auto block) {
       constexpr int QQ = decltype(block)::value;
-      if (tile * 4 + QQ >= nq) return;
+      if (tile * QQT + QQ >= nq) return;
       // block QQ has arrived (it was requested before the previous block's arithmetic); the next
       // block is requested now and arrives while this one's 128 multiply-adds run
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -239,7 +256,7 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
       for (int i = 0; i < TB; ++i) asm volatile("" : "+v"(xraw[QQ & 1][i]));
 #pragma unroll
       for (int c4 = 0; c4 < 4; ++c4) asm volatile("" : "+v"(wraw[QQ & 1][c4]));
-      if constexpr (QQ + 1 < 4) request(RouterIndex<QQ + 1>{});   // (a block past d holds zeros or stale rows: never used)
+      if constexpr (QQ + 1 < QQT) request(RouterIndex<QQ + 1>{});   // (a block past d holds zeros or stale rows: never used)
       float xv[TB], wv[R_NB];
 #pragma unroll
       for (int i = 0; i < TB; ++i) xv[i] = __uint_as_float(sizeof(XT) == 2 ? xraw[QQ & 1][i] << 16 : xraw[QQ & 1][i]);
@@ -256,32 +273,37 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
     });
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // a request past the last block used: done before the stage is refilled
   };
-  issue(0, xs0, ws0);
+  // The ring: tiles 0 .. S-2 are requested up front; at tile t a wavefront waits until only the
+  // tiles requested after t are in flight, the barrier makes that true for everyone's part of t
+  // and says that everyone has left tile t - 1, whose stage then takes tile t + S - 1.
+  auto start_ring = [&]() {
+#pragma unroll
+    for (int a = 0; a < S - 1; ++a)
+      if (a < ntiles) issue(a);
+  };
+  start_ring();
 #pragma unroll 1
   for (int sl = 0; sl < SL; ++sl) {
 #pragma unroll
   for (int v = 0; v < ACCS; ++v) acc[v] = 0.0f;
-  for (int tile = 0; tile < ntiles; tile += 2) {
-    if (tile + 1 < ntiles) { issue(tile + 1, xs1, ws1); BIGMAC_ROUTER_WAIT_VMCNT(XL + WL); }
+  for (int tile = 0; tile < ntiles; ++tile) {
+    const int younger = min(S - 2, ntiles - 1 - tile);
+    if (younger >= 2) BIGMAC_ROUTER_WAIT_VMCNT(2 * LPT);
+    else if (younger == 1) BIGMAC_ROUTER_WAIT_VMCNT(LPT);
     else BIGMAC_ROUTER_WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
-    compute(tile, xs0, ws0);
-    __builtin_amdgcn_s_barrier();
-    if (tile + 1 >= ntiles) break;
-    if (tile + 2 < ntiles) { issue(tile + 2, xs0, ws0); BIGMAC_ROUTER_WAIT_VMCNT(XL + WL); }
-    else BIGMAC_ROUTER_WAIT_VMCNT(0);
-    __builtin_amdgcn_s_barrier();
-    compute(tile + 1, xs1, ws1);
-    __builtin_amdgcn_s_barrier();
+    if (tile + S - 1 < ntiles) issue(tile + S - 1);
+    compute(tile);
   }
-  // every wavefront has left the last tile: the next slice's first tile can be on its way while
-  // this slice is reduced and stored
+  // once every wavefront has left the last tile, the next slice's first tiles can be on their way
+  // while this slice is reduced and stored
   const int n_cur = n0;
   const bool more = sl + 1 < SL && n0 + R_NB < N;
   if (more) {
+    __builtin_amdgcn_s_barrier();
     n0 += R_NB;
     rw = router_columns(n0);
-    issue(0, xs0, ws0);
+    start_ring();
   }
   // Halving tree (lane l with lane l ^ off, off = 32 .. 1).  While a lane still holds two or more
   // sums the step is a reduce-scatter: each half of the pair keeps one half of the sums (see
