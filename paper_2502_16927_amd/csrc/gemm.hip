@@ -931,6 +931,7 @@ int launch_mfma_widek(const GemmDesc& g, hipStream_t s) {
       break;
     case EPI_GELU: BIGMAC_MFMA_WIDEK(EPI_GELU, false); break;
     case EPI_DGELU: BIGMAC_MFMA_WIDEK(EPI_DGELU, false); break;
+    case EPI_ACCUM: BIGMAC_MFMA_WIDEK(EPI_ACCUM, true); break;
     default: return BIGMAC_ERR_INVALID_ARG;
   }
 #undef BIGMAC_MFMA_WIDEK

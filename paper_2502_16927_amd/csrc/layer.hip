@@ -38,11 +38,12 @@ struct StageTimer {  // records the caller's events around the launches of one s
 #ifndef BIGMAC_DEEP_MAX_TILES
 #define BIGMAC_DEEP_MAX_TILES 256   // 128 x 128 tiles (one per CU) up to which a dense product takes the 128 x 64 x 64 tile
 #endif
-// Which per-expert products take the square tile with 64-deep k tiles (two ring stages) when they
-// do not take the tall one: 1 expert-up, 2 expert-down, 4 the GELU' product, 8 the data gradient
-// of the first matrix.  Measured at gpt_medium: -1 %, +2.5 %, +3 %, -6 %.
+// Which products take the square tile with 64-deep k tiles (two ring stages) when they do not
+// take the tall one: 1 expert-up, 2 expert-down, 4 the GELU' product, 8 the data gradient of the
+// first matrix, 16 the data gradient of the descending projection, 32 the ascending projection.
+// Measured at gpt_medium: -1 %, +2.5 %, +3 %, -6 %, -11 %, -8 %.
 #ifndef BIGMAC_WIDEK_MASK
-#define BIGMAC_WIDEK_MASK 8
+#define BIGMAC_WIDEK_MASK 56
 #endif
 #ifndef BIGMAC_DEEP_WGRAD_MAX_TILES
 #define BIGMAC_DEEP_WGRAD_MAX_TILES 16   // measured: 16 tiles 15.5 -> 13.2 us; 64 tiles (gpt_xl widths) 43 -> 48 us
@@ -566,6 +567,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     BIGMAC_STAGE(BIGMAC_STAGE_ASCEND);
     g.ksplit = forward_ksplit(*D, D->T, D->d, low_ld(*D));
     g.tall_tile = g.ksplit == 1 && tall_dense(*D, D->T, D->d, low_ld(*D));
+    g.wide_k = g.ksplit == 1 && !g.tall_tile && wide_k_ok(*D, low_ld(*D), 32);
     if (g.ksplit > 1) {
       g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->d;
       rc = launch_gemm(g, s);
@@ -730,6 +732,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
       g.B = P->w_down; g.ldb = D->r; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
       g.C = dx_f32; g.ldc = D->d;
       g.tall_tile = tall_dense(*D, D->T, D->d, low_ld(*D));
+      g.wide_k = !g.tall_tile && wide_k_ok(*D, low_ld(*D), 16);
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_DGRAD);
       rc = launch_gemm(g, s);
       if (rc) return rc;
