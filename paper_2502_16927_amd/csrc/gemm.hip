@@ -583,16 +583,21 @@ void mfma_gemm_kernel(GemmDesc p) {
     // bf16 epilogue staging, in the ring's last stage: the prefetch below fills stages
     // 0 .. NS - 2, and the last stage is requested again only behind the first barrier of the next
     // k loop.  A staged row is 128 bytes = 8 chunks of 16; chunk c of row r sits at position
-    // c ^ (r % 8), which spreads both the column-wise quad accesses and the row-wise ones over
-    // all banks.  One strip (32 rows x 64 columns) per wave.
+    // c ^ ((r / 2) % 8).  The 64 banks span two rows, so the 16 rows of one parity share 8 chunk
+    // positions: a column-wise quad access (32 lanes, one row each, 8 bytes) meets every position
+    // twice, the least this form allows while a chunk keeps its two quads in order; a row-wise
+    // access takes whole rows.  One strip (32 rows x 64 columns) per wave.
     constexpr int SROW = 128;
     static_assert(!SWAP || WN == 64, "the strip holds 64-column wave tiles");
     static_assert(WAVES_M * WAVES_N * 32 * SROW <= (A_CHUNKS + B_CHUNKS) * 16, "staging strips do not fit a ring stage");
     const unsigned strip = ring_at + (NS - 1) * STAGE_BYTES + wave * (32 * SROW);
     const unsigned quad_row = strip + (lane & 31) * SROW + (lane >> 5) * 8;
-    const unsigned quad_swz = lane & 7;                                     // row % 8 of the quads' row
+    const unsigned quad_swz = (lane >> 1) & 7;                              // (row / 2) % 8 of the quads' row
     auto quad_at = [&](int j, int vq) { return quad_row + ((((unsigned)(j * 4 + vq)) ^ quad_swz) << 4); };
-    const unsigned row_at = strip + (lane >> 3) * SROW + (((lane & 7) ^ ((lane >> 3) & 7)) << 4);   // + pass * 8 * SROW
+    // row-wise: pass q takes row lane / 8 + 8 q, whose swizzle is lane / 16 + 4 (q % 2)
+    const unsigned row_even = strip + (lane >> 3) * SROW + (((lane & 7) ^ (lane >> 4)) << 4);
+    const unsigned row_odd = strip + (lane >> 3) * SROW + (((lane & 7) ^ (lane >> 4) ^ 4) << 4);
+    auto row_at = [&](int q) { return (q & 1 ? row_odd : row_even) + q * 8 * SROW; };
     // EPI_DGELU: turn the saved pre-activation from its row layout into the accumulators' quad
     // layout now; its registers are then free for the next tile's request, which goes out ahead
     // of the prefetch and is therefore complete whenever a k tile of that prefetch is.
@@ -603,7 +608,7 @@ void mfma_gemm_kernel(GemmDesc p) {
 #pragma unroll
       for (int i = 0; i < TMH; ++i) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) lds_write_b128(row_at + q * 8 * SROW, __builtin_bit_cast(u32x4_t, aux[i * 4 + q]));
+        for (int q = 0; q < 4; ++q) lds_write_b128(row_at(q), __builtin_bit_cast(u32x4_t, aux[i * 4 + q]));
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -661,7 +666,7 @@ void mfma_gemm_kernel(GemmDesc p) {
       auto flush_rows = [&](const __amdgpu_buffer_rsrc_t& dst, int i) {
         u32x4_t v[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) lds_read_b128(row_at + q * 8 * SROW, v[q]);
+        for (int q = 0; q < 4; ++q) lds_read_b128(row_at(q), v[q]);
         lds_wait(v);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
