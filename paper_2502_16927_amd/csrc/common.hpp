@@ -152,6 +152,8 @@ struct GemmDesc {
   int wide_k;                // bf16, k-contiguous A, K % 64 == 0: the square tile with 64-deep k tiles, two ring stages
   int kloop_priority;        // MFMA kernels: raise the wave priority inside the k loop (see the kernel)
   int deep_tile;             // bf16, dense, store or accumulate (K % 64 == 0 with a k-contiguous operand): 128 x 64 outputs, 64-deep k tiles
+  const void* touch;         // MFMA kernels, optional: a region (device) every line of which is read once as the kernel starts,
+  size_t touch_bytes;        //   so that its first use in a k loop meets the caches and not the memory (0 = off)
 };
 // Rows per M tile of the ragged-M schedule for this dtype (the tile map must be built with it).
 int gemm_ragged_tile_rows(int dtype, int tall_tile);

@@ -108,6 +108,36 @@ inline bool tall_dense(const bigmac_dims& D, int M, int N, int K) {
 inline bool deep_dense(const bigmac_dims& D, int M, int N, int K) {
   return bf(D) && K % 64 == 0 && K >= 512 && (long)((M + 127) / 128) * ((N + 127) / 128) <= BIGMAC_DEEP_MAX_TILES;
 }
+// Expert weights read line by line as a grouped product starts (GemmDesc::touch); bits: 1 expert-up,
+// 2 expert-down, 4 GELU' product, 8 the first matrix's data gradient.  Measured: it pays where
+// an expert has so few output tiles that they all run at once and each meets its weights in
+// memory (expert-up at gpt_medium, 64 tiles per expert and K = 256: 102 -> 81 us), costs a few us
+// where an expert's first tiles fetch the weights for many later ones (8192 rows per expert:
+// +6 us) or where every matrix is read by one or two row tiles anyway (up to 256 rows per expert:
+// +2 to +3 us), and reading more than a fraction of the 256 MB memory-side cache ahead costs more
+// than it saves (128 MB at gpt_xl: +30 us); the other three products lose 1 to 4 us by it.
+#ifndef BIGMAC_TOUCH_MASK
+#define BIGMAC_TOUCH_MASK 1
+#endif
+#ifndef BIGMAC_TOUCH_MAX_BYTES
+#define BIGMAC_TOUCH_MAX_BYTES ((size_t)64 << 20)
+#endif
+#ifndef BIGMAC_TOUCH_MAX_TILES
+#define BIGMAC_TOUCH_MAX_TILES 256
+#endif
+#ifndef BIGMAC_TOUCH_MIN_ROWS
+#define BIGMAC_TOUCH_MIN_ROWS 512
+#endif
+inline void touch_weights(const bigmac_dims& D, GemmDesc& g, const void* w, int bit) {
+  const size_t bytes = (size_t)D.N * g.K * g.N * 2;
+  const long rows_per_expert = ((long)D.T * D.k + D.N - 1) / D.N;
+  const long tiles_per_expert = ((rows_per_expert + 127) / 128) * ((g.N + 127) / 128);   // 128 x 128 output tiles
+  if (bf(D) && (BIGMAC_TOUCH_MASK & bit) && bytes <= BIGMAC_TOUCH_MAX_BYTES && tiles_per_expert <= BIGMAC_TOUCH_MAX_TILES &&
+      rows_per_expert >= BIGMAC_TOUCH_MIN_ROWS) {
+    g.touch = w;
+    g.touch_bytes = bytes;
+  }
+}
 inline bool wide_k_ok(const bigmac_dims& D, int K, int bit) {
   return bf(D) && (BIGMAC_WIDEK_MASK & bit) && K % 64 == 0;
 }
@@ -280,6 +310,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.A = x_perm; g.lda = W.win; g.K = W.win;
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
   g.C = hact; g.ldc = ld_wide; g.aux_out = act;
+  touch_weights(D, g, w1, 1);
   int rc;
   {
     BIGMAC_STAGE(BIGMAC_STAGE_EXPERT_UP);
@@ -294,6 +325,8 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.tall_tile = tall_rows(D, W.win, W.hid); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
   g.wide_k = !g.tall_tile && wide_k_ok(D, W.hid, 2);
   g.kloop_priority = 1;
+  g.touch = nullptr; g.touch_bytes = 0;
+  touch_weights(D, g, w2, 2);
   BIGMAC_STAGE(BIGMAC_STAGE_EXPERT_DOWN);
   return launch_gemm(g, s);
 }
@@ -664,6 +697,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.tall_tile = tall_rows(*D, W.hid, W.win); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
     g.wide_k = !g.tall_tile && wide_k_ok(*D, W.win, 4);
     g.kloop_priority = 1;              // measured: -3.5 % (gpt_medium), -1.7 % (gpt_xl)
+    touch_weights(*D, g, P->w2, 4);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
@@ -700,6 +734,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.tall_tile = tall_rows(*D, W.win, W.hid); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
     g.wide_k = !g.tall_tile && wide_k_ok(*D, W.hid, 8);
     g.kloop_priority = 1;
+    touch_weights(*D, g, P->w1, 8);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
