@@ -306,11 +306,13 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.epilogue = EPI_GELU;
   g.tall_tile = tall_rows(D, W.hid, W.win); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
   g.wide_k = !g.tall_tile && wide_k_ok(D, W.win, 1);
-  g.kloop_priority = W.win >= 512;   // measured: -3 % at K = 512 (gpt_xl), +2 % at K = 256 (gpt_medium)
   g.A = x_perm; g.lda = W.win; g.K = W.win;
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
   g.C = hact; g.ldc = ld_wide; g.aux_out = act;
   touch_weights(D, g, w1, 1);
+  // measured: -3 % at K = 512 (gpt_xl); at K = 256 (gpt_medium) +2 % while the weights came from
+  // memory, -4.6 % with the warm-up
+  g.kloop_priority = W.win >= 512 || g.touch_bytes != 0;
   int rc;
   {
     BIGMAC_STAGE(BIGMAC_STAGE_EXPERT_UP);
