@@ -489,20 +489,18 @@ void mfma_gemm_kernel(GemmDesc p) {
   constexpr int RING_AHEAD = (NS - 2) * LOADS_PER_TILE;
 
   // Warm-up of a region the k loops will read for the first time (the expert weights): one
-  // 4-byte read per 128-byte line, the lines dealt out over the launch, XCD x taking the x-th
-  // eighth (with even group sizes that is the part its own tiles use).  A k loop that meets a
-  // new expert's weights in memory waits a full miss latency at every k step; after this
-  // they come from the L2 or the memory-side cache.
+  // 4-byte read per 128-byte line, the lines dealt out evenly over the launch.  A k loop that
+  // meets a new expert's weights in memory waits a full miss latency at every k step; after
+  // this they come from the memory-side cache.  (Giving every XCD the part its own tiles use,
+  // for its L2, measured no better than this even split, which does not depend on the group sizes.)
   if (p.touch_bytes) {
-    const size_t lines = p.touch_bytes >> 7, per_xcd = (lines + 7) >> 3;
-    const size_t first = (blockIdx.x & 7) * per_xcd, last = first + per_xcd < lines ? first + per_xcd : lines;
-    const size_t step = (size_t)(gridDim.x >> 3) * THREADS;
+    const size_t lines = p.touch_bytes >> 7, step = (size_t)gridDim.x * THREADS;
     const unsigned* src = (const unsigned*)p.touch;
     unsigned seen = 0;
-    for (size_t l = first + (size_t)(blockIdx.x >> 3) * THREADS + threadIdx.x; l < last; l += 4 * step) {
+    for (size_t l = (size_t)blockIdx.x * THREADS + threadIdx.x; l < lines; l += 4 * step) {
       unsigned v[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) v[u] = l + u * step < last ? src[(l + u * step) * 32] : 0u;
+      for (int u = 0; u < 4; ++u) v[u] = l + u * step < lines ? src[(l + u * step) * 32] : 0u;
       seen |= v[0] | v[1] | v[2] | v[3];
     }
     asm volatile("" ::"v"(seen));   // the reads have to happen; their values are of no interest
