@@ -17,6 +17,13 @@
  *   - top-k picks the largest logit k times, equal logits go to the lowest expert index;
  *   - the gate value is the softmax over the k selected logits;
  *   - act is the exact (erf) GELU; there are no biases; routing is dropless (Section 3.3).
+ * Two variants the paper names are options of the *_ext entry points (off in the plain ones):
+ *   - the router may read x' instead of x (Section 3.1 leaves the choice open): W_g is then [r, N],
+ *     the router's input is x' rounded to the type it is stored and dispatched in (fp32 or bf16,
+ *     ROUTE_LOW_F32 / ROUTE_LOW_BF16), and the gate's gradient reaches x through x' (the rounding
+ *     is passed straight through);
+ *   - expert biases (the 2rh term of the expert parameter count in Table 3):
+ *     E_i(x') = (act(x' W1[i] + b1[i])) W2[i] + b2[i], b1 [N, hid], b2 [N, win].
  *
  * Precision: inputs arrive as fp32 values (already rounded to the run's storage type by the
  * caller).  The router logits are fp32 in the fixed order.  Everything else is accumulated and
@@ -41,6 +48,25 @@
 #endif
 
 #define LANES 64
+
+enum { ROUTE_FULL = 0, ROUTE_LOW_F32 = 1, ROUTE_LOW_BF16 = 2 };
+
+/* round to the nearest bfloat16, ties to even (finite inputs) */
+static float round_bf16(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
+    memcpy(&v, &u, 4);
+    return v;
+}
+/* x' as the router of the x'-variant sees it: the stored value */
+static float stored_low(double v, int route_low)
+{
+    float f = (float)v;
+    return route_low == ROUTE_LOW_BF16 ? round_bf16(f) : f;
+}
 
 /* number of threads the parallel loops below use */
 int oracle_num_threads(void)
@@ -188,8 +214,19 @@ void oracle_dispatch(int T, int k, int width, const float *x_low, const int32_t 
 
 /* The expert of Eq. 4 (or Eq. 3 with the widths swapped) applied to permuted rows: rows
  * [offsets[e], offsets[e+1]) belong to expert e.  a_out (pre-activation) may be NULL. */
+void oracle_expert_rows_ext(int N, int win, int hid, const int32_t *offsets, const float *x_perm,
+                            const float *w1, const float *w2, const float *b1, const float *b2,
+                            double *a_out, double *o_perm);
 void oracle_expert_rows(int N, int win, int hid, const int32_t *offsets, const float *x_perm,
                         const float *w1, const float *w2, double *a_out, double *o_perm)
+{
+    oracle_expert_rows_ext(N, win, hid, offsets, x_perm, w1, w2, NULL, NULL, a_out, o_perm);
+}
+/* The same with expert biases b1 [N, hid], b2 [N, win] (either may be NULL); a_out then holds
+ * the pre-activation with b1 added. */
+void oracle_expert_rows_ext(int N, int win, int hid, const int32_t *offsets, const float *x_perm,
+                            const float *w1, const float *w2, const float *b1, const float *b2,
+                            double *a_out, double *o_perm)
 {
 #pragma omp parallel for schedule(dynamic, 1)
     for (int e = 0; e < N; ++e) {
@@ -199,9 +236,11 @@ void oracle_expert_rows(int N, int win, int hid, const int32_t *offsets, const f
         for (int s = offsets[e]; s < offsets[e + 1]; ++s) {
             for (int i = 0; i < win; ++i) xin[i] = (double)x_perm[(size_t)s * win + i];
             vec_mat(xin, W1, win, hid, a);
+            if (b1) for (int c = 0; c < hid; ++c) a[c] += (double)b1[(size_t)e * hid + c];
             if (a_out) memcpy(a_out + (size_t)s * hid, a, sizeof(double) * (size_t)hid);
             for (int c = 0; c < hid; ++c) a[c] = gelu(a[c]);
             vec_mat(a, W2, hid, win, o_perm + (size_t)s * win);
+            if (b2) for (int c = 0; c < win; ++c) o_perm[(size_t)s * win + c] += (double)b2[(size_t)e * win + c];
         }
         free(xin); free(a);
     }
@@ -225,6 +264,21 @@ void oracle_combine(int T, int k, int width, const double *o_perm, const int32_t
     }
 }
 
+/* x' = x W_down (Eq. 2's first step) as it is stored: the fp64 sum rounded to fp32, and on to bf16
+ * for ROUTE_LOW_BF16.  This is what the router of the x'-variant reads. */
+void oracle_stored_low(int T, int d, int r, const float *x, const float *w_down, int route_low, float *x_low)
+{
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        double *xd = (double *)malloc(sizeof(double) * (size_t)d);
+        double *xl = (double *)malloc(sizeof(double) * (size_t)r);
+        for (int i = 0; i < d; ++i) xd[i] = (double)x[(size_t)t * d + i];
+        vec_mat(xd, w_down, d, r, xl);
+        for (int c = 0; c < r; ++c) x_low[(size_t)t * r + c] = stored_low(xl[c], route_low);
+        free(xd); free(xl);
+    }
+}
+
 /* ---------------------------------------------------------------- layers ----------------- */
 
 /* BigMac layer forward, Eq. 2 with the expert of Eq. 4, token by token, no permutation.
@@ -232,10 +286,28 @@ void oracle_combine(int T, int k, int width, const double *o_perm, const int32_t
  * row s of y (and y_low) is token sel[s].  y is [nsel, d]; y_low ([nsel, r]) may be NULL.
  * keep ([T, k], NULL = every pair) marks the pairs that survived the expert capacity (from
  * oracle_permutation); a dropped pair adds nothing, and the gate values stay as they are. */
+void oracle_bigmac_forward_ext(int T, int d, int r, int N, int k, int h,
+                               const float *x, const float *w_gate, const float *bias,
+                               const float *w_down, const float *w_up, const float *w1, const float *w2,
+                               const float *b1, const float *b2, int route_low,
+                               int nsel, const int32_t *sel, const int32_t *keep, double *y, double *y_low);
 void oracle_bigmac_forward(int T, int d, int r, int N, int k, int h,
                            const float *x, const float *w_gate, const float *bias,
                            const float *w_down, const float *w_up, const float *w1, const float *w2,
                            int nsel, const int32_t *sel, const int32_t *keep, double *y, double *y_low)
+{
+    oracle_bigmac_forward_ext(T, d, r, N, k, h, x, w_gate, bias, w_down, w_up, w1, w2, NULL, NULL, ROUTE_FULL,
+                              nsel, sel, keep, y, y_low);
+}
+
+/* The same with the two variants: route_low != ROUTE_FULL: the router reads the stored x' and
+ * w_gate is [r, N] (Section 3.1); b1 [N, h], b2 [N, r] (either may be NULL): expert biases
+ * (Table 3's 2rh parameters per expert). */
+void oracle_bigmac_forward_ext(int T, int d, int r, int N, int k, int h,
+                               const float *x, const float *w_gate, const float *bias,
+                               const float *w_down, const float *w_up, const float *w1, const float *w2,
+                               const float *b1, const float *b2, int route_low,
+                               int nsel, const int32_t *sel, const int32_t *keep, double *y, double *y_low)
 {
     (void)T;
 #pragma omp parallel for schedule(dynamic, 4)
@@ -250,17 +322,26 @@ void oracle_bigmac_forward(int T, int d, int r, int N, int k, int h,
         double *a = (double *)malloc(sizeof(double) * (size_t)h);
         double *o = (double *)malloc(sizeof(double) * (size_t)r);
         double *yl = (double *)malloc(sizeof(double) * (size_t)r);
-        oracle_router_logits(1, d, N, xt, w_gate, bias, logit);
-        oracle_topk_gate(1, N, k, logit, idx, gate);
         for (int i = 0; i < d; ++i) xd[i] = (double)xt[i];
         vec_mat(xd, w_down, d, r, xl);                                  /* x' = x W_down       */
+        if (route_low == ROUTE_FULL) {
+            oracle_router_logits(1, d, N, xt, w_gate, bias, logit);
+        } else {                                                        /* the router reads x' */
+            float *xr = (float *)malloc(sizeof(float) * (size_t)r);
+            for (int c = 0; c < r; ++c) xr[c] = stored_low(xl[c], route_low);
+            oracle_router_logits(1, r, N, xr, w_gate, bias, logit);
+            free(xr);
+        }
+        oracle_topk_gate(1, N, k, logit, idx, gate);
         for (int c = 0; c < r; ++c) yl[c] = 0.0;
         for (int j = 0; j < k; ++j) {
             int e = idx[j];
             if (keep && !keep[(size_t)t * k + j]) continue;
             vec_mat(xl, w1 + (size_t)e * r * h, r, h, a);               /* x' W1[e]            */
+            if (b1) for (int c = 0; c < h; ++c) a[c] += (double)b1[(size_t)e * h + c];
             for (int c = 0; c < h; ++c) a[c] = gelu(a[c]);
             vec_mat(a, w2 + (size_t)e * h * r, h, r, o);                /* E_e(x')             */
+            if (b2) for (int c = 0; c < r; ++c) o[c] += (double)b2[(size_t)e * r + c];
             for (int c = 0; c < r; ++c) yl[c] += gate[j] * o[c];        /* y' += p_e E_e(x')   */
         }
         vec_mat(yl, w_up, r, d, y + (size_t)s * d);                     /* y = y' W_up         */
@@ -321,14 +402,19 @@ void oracle_cdac_forward(int T, int d, int r, int N, int k,
  *   dW_down += x^T dx'
  * keep ([T, k], NULL = every pair): pairs dropped by the expert capacity have no output, so
  * o_j = 0, dgate_j = 0 and they reach no expert; the gate values are those of the full top-k.
+ * Variants: with expert biases, a_j = x' W1[e] + b1[e], o_j = g_j W2[e] + b2[e], and
+ *   d_b1[e] += da_j ;  d_b2[e] += do_j.
+ * With the router on x' (shared layers only; W_g is [win, N], xr = the stored x'):
+ *   dW_g[:, e_j] += xr^T dlogit_j ;  dx' += sum_j dlogit_j W_g[:, e_j]^T ;  dx = dx' W_down^T.
  */
 static void layer_backward(int shared, int T, int d, int win, int hid, int N, int k,
                            const float *x, const float *dy,
                            const float *w_gate, const float *bias,
                            const float *w_down, const float *w_up, const float *w1, const float *w2,
+                           const float *b1, const float *b2, int route_low,
                            int nsel, const int32_t *sel, const int32_t *keep,
                            double *dx, double *d_w_down, double *d_w_up, double *d_w_gate,
-                           double *d_w1, double *d_w2)
+                           double *d_w1, double *d_w2, double *d_b1, double *d_b2)
 {
     (void)T;
     size_t ns = (size_t)nsel;
@@ -342,6 +428,7 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
     double *ylow = (double *)malloc(sizeof(double) * ns * win);     /* y'                        */
     double *dxl = (double *)malloc(sizeof(double) * ns * win);      /* dx'                       */
     double *dlg = (double *)malloc(sizeof(double) * ns * k);        /* dlogit_j                  */
+    float *xrt = route_low != ROUTE_FULL ? (float *)malloc(sizeof(float) * ns * win) : NULL; /* stored x' */
 
     /* phase 1, per token: routing, x', dy' */
 #pragma omp parallel for schedule(static)
@@ -350,8 +437,6 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
         const float *xt = x + (size_t)t * d, *dyt = dy + (size_t)t * d;
         float *logit = (float *)malloc(sizeof(float) * (size_t)N);
         double *tmp = (double *)malloc(sizeof(double) * (size_t)d);
-        oracle_router_logits(1, d, N, xt, w_gate, bias, logit);
-        oracle_topk_gate(1, N, k, logit, idx + (size_t)s * k, gate + (size_t)s * k);
         if (shared) {
             for (int i = 0; i < d; ++i) tmp[i] = (double)xt[i];
             vec_mat(tmp, w_down, d, win, xlow + (size_t)s * win);
@@ -361,6 +446,13 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
             for (int i = 0; i < d; ++i) xlow[(size_t)s * win + i] = (double)xt[i];
             for (int i = 0; i < d; ++i) dyl[(size_t)s * win + i] = (double)dyt[i];
         }
+        if (route_low == ROUTE_FULL) {
+            oracle_router_logits(1, d, N, xt, w_gate, bias, logit);
+        } else {
+            for (int c = 0; c < win; ++c) xrt[(size_t)s * win + c] = stored_low(xlow[(size_t)s * win + c], route_low);
+            oracle_router_logits(1, win, N, xrt + (size_t)s * win, w_gate, bias, logit);
+        }
+        oracle_topk_gate(1, N, k, logit, idx + (size_t)s * k, gate + (size_t)s * k);
         free(logit); free(tmp);
     }
 
@@ -380,16 +472,20 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
                 const double *xl = xlow + (size_t)s * win, *dl = dyl + (size_t)s * win;
                 double *o = opair + p * win;
                 vec_mat(xl, W1, win, hid, a);
+                if (b1) for (int c = 0; c < hid; ++c) a[c] += (double)b1[(size_t)e * hid + c];
                 for (int c = 0; c < hid; ++c) g[c] = gelu(a[c]);
                 vec_mat(g, W2, hid, win, o);
+                if (b2) for (int c = 0; c < win; ++c) o[c] += (double)b2[(size_t)e * win + c];
                 double dot = 0.0;
                 for (int c = 0; c < win; ++c) dot += dl[c] * o[c];
                 dgt[p] = dot;
                 for (int c = 0; c < win; ++c) dout[c] = gate[p] * dl[c];
                 if (d_w2) outer_acc(d_w2 + (size_t)e * hid * win, g, dout, hid, win);
+                if (d_b2) for (int c = 0; c < win; ++c) d_b2[(size_t)e * win + c] += dout[c];
                 vec_matT(dout, W2, hid, win, dg);
                 for (int c = 0; c < hid; ++c) dg[c] *= gelu_grad(a[c]);         /* now da */
                 if (d_w1) outer_acc(d_w1 + (size_t)e * win * hid, xl, dg, win, hid);
+                if (d_b1) for (int c = 0; c < hid; ++c) d_b1[(size_t)e * hid + c] += dg[c];
                 vec_matT(dg, W1, win, hid, dxp + p * win);
             }
         free(a); free(g); free(dg); free(dout);
@@ -413,13 +509,20 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
             dlg[p] = gate[p] * (dgt[p] - mix);
         }
         double *dxt = dx + (size_t)t * d;
+        if (route_low != ROUTE_FULL)                      /* the gate's gradient enters at x' */
+            for (int j = 0; j < k; ++j) {
+                size_t p = (size_t)s * k + j;
+                int e = idx[p];
+                for (int c = 0; c < win; ++c) dl[c] += dlg[p] * (double)w_gate[(size_t)c * N + e];
+            }
         if (shared) vec_matT(dl, w_down, d, win, dxt);
         else for (int i = 0; i < d; ++i) dxt[i] = dl[i];
-        for (int j = 0; j < k; ++j) {
-            size_t p = (size_t)s * k + j;
-            int e = idx[p];
-            for (int i = 0; i < d; ++i) dxt[i] += dlg[p] * (double)w_gate[(size_t)i * N + e];
-        }
+        if (route_low == ROUTE_FULL)
+            for (int j = 0; j < k; ++j) {
+                size_t p = (size_t)s * k + j;
+                int e = idx[p];
+                for (int i = 0; i < d; ++i) dxt[i] += dlg[p] * (double)w_gate[(size_t)i * N + e];
+            }
     }
 
     /* phase 4, per output row of the shared matrices */
@@ -442,17 +545,18 @@ static void layer_backward(int shared, int T, int d, int win, int hid, int N, in
             }
     }
     if (d_w_gate) {
+        const int din = route_low != ROUTE_FULL ? win : d;     /* width of the router's input */
 #pragma omp parallel for schedule(static)
-        for (int i = 0; i < d; ++i)
+        for (int i = 0; i < din; ++i)
             for (int s = 0; s < nsel; ++s) {
                 int t = sel ? sel[s] : s;
-                double v = (double)x[(size_t)t * d + i];
+                double v = route_low != ROUTE_FULL ? (double)xrt[(size_t)s * win + i] : (double)x[(size_t)t * d + i];
                 for (int j = 0; j < k; ++j)
                     d_w_gate[(size_t)i * N + idx[(size_t)s * k + j]] += v * dlg[(size_t)s * k + j];
             }
     }
     free(idx); free(gate); free(xlow); free(dyl); free(opair); free(dxp); free(dgt);
-    free(ylow); free(dxl); free(dlg);
+    free(ylow); free(dxl); free(dlg); free(xrt);
 }
 
 void oracle_bigmac_backward(int T, int d, int r, int N, int k, int h,
@@ -462,8 +566,22 @@ void oracle_bigmac_backward(int T, int d, int r, int N, int k, int h,
                             double *dx, double *d_w_down, double *d_w_up, double *d_w_gate,
                             double *d_w1, double *d_w2)
 {
-    layer_backward(1, T, d, r, h, N, k, x, dy, w_gate, bias, w_down, w_up, w1, w2, nsel, sel, keep,
-                   dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2);
+    layer_backward(1, T, d, r, h, N, k, x, dy, w_gate, bias, w_down, w_up, w1, w2, NULL, NULL, ROUTE_FULL,
+                   nsel, sel, keep, dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2, NULL, NULL);
+}
+
+/* With the variants of oracle_bigmac_forward_ext; d_b1 [N, h], d_b2 [N, r] are added to like the
+ * other weight gradients (NULL: not wanted); d_w_gate is [r, N] when the router reads x'. */
+void oracle_bigmac_backward_ext(int T, int d, int r, int N, int k, int h,
+                                const float *x, const float *dy, const float *w_gate, const float *bias,
+                                const float *w_down, const float *w_up, const float *w1, const float *w2,
+                                const float *b1, const float *b2, int route_low,
+                                int nsel, const int32_t *sel, const int32_t *keep,
+                                double *dx, double *d_w_down, double *d_w_up, double *d_w_gate,
+                                double *d_w1, double *d_w2, double *d_b1, double *d_b2)
+{
+    layer_backward(1, T, d, r, h, N, k, x, dy, w_gate, bias, w_down, w_up, w1, w2, b1, b2, route_low,
+                   nsel, sel, keep, dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2, d_b1, d_b2);
 }
 
 /* Fine-grained layer backward: wdn [N, d, r], wup [N, r, d]; gradients d_wdn, d_wup likewise. */
@@ -473,8 +591,8 @@ void oracle_cdac_backward(int T, int d, int r, int N, int k,
                           const int32_t *keep,
                           double *dx, double *d_w_gate, double *d_wdn, double *d_wup)
 {
-    layer_backward(0, T, d, d, r, N, k, x, dy, w_gate, bias, NULL, NULL, wdn, wup, nsel, sel, keep,
-                   dx, NULL, NULL, d_w_gate, d_wdn, d_wup);
+    layer_backward(0, T, d, d, r, N, k, x, dy, w_gate, bias, NULL, NULL, wdn, wup, NULL, NULL, ROUTE_FULL,
+                   nsel, sel, keep, dx, NULL, NULL, d_w_gate, d_wdn, d_wup, NULL, NULL);
 }
 
 /* Closed forms of Table 3, MoE-layer terms only (paper symbols: rho = r/d is the paper's r).

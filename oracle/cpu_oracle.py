@@ -103,14 +103,18 @@ def dispatch(x_low, slot_of):
     return out
 
 
-def expert_rows(x_perm, offsets, w1, w2, want_a=False):
-    x_perm, offsets, w1, w2 = _f32(x_perm), _i32(offsets), _f32(w1), _f32(w2)
+ROUTE_FULL, ROUTE_LOW_F32, ROUTE_LOW_BF16 = 0, 1, 2   # what the router reads: x, or x' as stored in fp32 / bf16
+
+
+def expert_rows(x_perm, offsets, w1, w2, want_a=False, b1=None, b2=None):
+    x_perm, offsets, w1, w2, b1, b2 = _f32(x_perm), _i32(offsets), _f32(w1), _f32(w2), _f32(b1), _f32(b2)
     N, win, hid = w1.shape
     assert w2.shape == (N, hid, win) and x_perm.shape[1] == win
     rows = x_perm.shape[0]
     a = np.empty((rows, hid), np.float64) if want_a else None
     o = np.empty((rows, win), np.float64)
-    lib().oracle_expert_rows(N, win, hid, _p(offsets), _p(x_perm), _p(w1), _p(w2), _p(a), _p(o))
+    assert (b1 is None or b1.shape == (N, hid)) and (b2 is None or b2.shape == (N, win))
+    lib().oracle_expert_rows_ext(N, win, hid, _p(offsets), _p(x_perm), _p(w1), _p(w2), _p(b1), _p(b2), _p(a), _p(o))
     return (o, a) if want_a else o
 
 
@@ -123,19 +127,42 @@ def combine(o_perm, slot_of, gate=None):
     return y
 
 
-def bigmac_forward(x, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, want_y_low=False, keep=None):
-    x, w_gate, bias, w_down, w_up, w1, w2 = map(_f32, (x, w_gate, bias, w_down, w_up, w1, w2))
+def bigmac_forward(x, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, want_y_low=False, keep=None,
+                   b1=None, b2=None, route_low=ROUTE_FULL):
+    """route_low != ROUTE_FULL: the router reads the stored x' and w_gate is [r, N]; b1 [N, h], b2 [N, r]:
+    expert biases."""
+    x, w_gate, bias, w_down, w_up, w1, w2, b1, b2 = map(_f32, (x, w_gate, bias, w_down, w_up, w1, w2, b1, b2))
     T, d = x.shape
     r = w_down.shape[1]
     N, _, h = w1.shape
     assert w_down.shape == (d, r) and w_up.shape == (r, d) and w1.shape == (N, r, h) and w2.shape == (N, h, r)
+    assert w_gate.shape == ((r, N) if route_low else (d, N))
+    assert (b1 is None or b1.shape == (N, h)) and (b2 is None or b2.shape == (N, r))
     sel = _i32(sel)
     nsel = T if sel is None else sel.shape[0]
     y = np.empty((nsel, d), np.float64)
     y_low = np.empty((nsel, r), np.float64) if want_y_low else None
-    lib().oracle_bigmac_forward(T, d, r, N, k, h, _p(x), _p(w_gate), _p(bias), _p(w_down), _p(w_up),
-                                _p(w1), _p(w2), nsel, _p(sel), _p(_i32(keep)), _p(y), _p(y_low))
+    lib().oracle_bigmac_forward_ext(T, d, r, N, k, h, _p(x), _p(w_gate), _p(bias), _p(w_down), _p(w_up),
+                                    _p(w1), _p(w2), _p(b1), _p(b2), int(route_low), nsel, _p(sel), _p(_i32(keep)),
+                                    _p(y), _p(y_low))
     return (y, y_low) if want_y_low else y
+
+
+def stored_low(x, w_down, mode=ROUTE_LOW_BF16):
+    """x' = x W_down as it is stored (fp32, or bf16 for ROUTE_LOW_BF16): what the router of the
+    x'-variant reads."""
+    x, w_down = _f32(x), _f32(w_down)
+    T, d = x.shape
+    r = w_down.shape[1]
+    out = np.empty((T, r), np.float32)
+    lib().oracle_stored_low(T, d, r, _p(x), _p(w_down), int(mode), _p(out))
+    return out
+
+
+def route_low(x, w_down, w_gate, bias, k, mode=ROUTE_LOW_BF16):
+    """Routing of the variant whose router reads x' (w_gate is [r, N]): idx, gate, logits, x'."""
+    xl = stored_low(x, w_down, mode)
+    return route(xl, w_gate, bias, k) + (xl,)
 
 
 def cdac_forward(x, w_gate, bias, wdn, wup, k, sel=None, keep=None):
@@ -151,10 +178,11 @@ def cdac_forward(x, w_gate, bias, wdn, wup, k, sel=None, keep=None):
     return y
 
 
-def bigmac_backward(x, dy, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, init=None, keep=None):
-    """Returns dict(dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2).  init: optional dict of starting
-    values the weight gradients are added to (default zeros)."""
-    x, dy, w_gate, bias, w_down, w_up, w1, w2 = map(_f32, (x, dy, w_gate, bias, w_down, w_up, w1, w2))
+def bigmac_backward(x, dy, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, init=None, keep=None,
+                    b1=None, b2=None, route_low=ROUTE_FULL):
+    """Returns dict(dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2[, d_b1, d_b2]).  init: optional dict of
+    starting values the weight gradients are added to (default zeros)."""
+    x, dy, w_gate, bias, w_down, w_up, w1, w2, b1, b2 = map(_f32, (x, dy, w_gate, bias, w_down, w_up, w1, w2, b1, b2))
     T, d = x.shape
     r = w_down.shape[1]
     N, _, h = w1.shape
@@ -165,14 +193,18 @@ def bigmac_backward(x, dy, w_gate, bias, w_down, w_up, w1, w2, k, sel=None, init
         "dx": np.zeros((T, d), np.float64),
         "d_w_down": _f64(init.get("d_w_down", np.zeros((d, r)))).copy(),
         "d_w_up": _f64(init.get("d_w_up", np.zeros((r, d)))).copy(),
-        "d_w_gate": _f64(init.get("d_w_gate", np.zeros((d, N)))).copy(),
+        "d_w_gate": _f64(init.get("d_w_gate", np.zeros((r if route_low else d, N)))).copy(),
         "d_w1": _f64(init.get("d_w1", np.zeros((N, r, h)))).copy(),
         "d_w2": _f64(init.get("d_w2", np.zeros((N, h, r)))).copy(),
     }
-    lib().oracle_bigmac_backward(T, d, r, N, k, h, _p(x), _p(dy), _p(w_gate), _p(bias), _p(w_down),
-                                 _p(w_up), _p(w1), _p(w2), nsel, _p(sel), _p(_i32(keep)), _p(g["dx"]),
-                                 _p(g["d_w_down"]), _p(g["d_w_up"]), _p(g["d_w_gate"]),
-                                 _p(g["d_w1"]), _p(g["d_w2"]))
+    if b1 is not None:
+        g["d_b1"] = _f64(init.get("d_b1", np.zeros((N, h)))).copy()
+    if b2 is not None:
+        g["d_b2"] = _f64(init.get("d_b2", np.zeros((N, r)))).copy()
+    lib().oracle_bigmac_backward_ext(T, d, r, N, k, h, _p(x), _p(dy), _p(w_gate), _p(bias), _p(w_down),
+                                     _p(w_up), _p(w1), _p(w2), _p(b1), _p(b2), int(route_low), nsel, _p(sel),
+                                     _p(_i32(keep)), _p(g["dx"]), _p(g["d_w_down"]), _p(g["d_w_up"]), _p(g["d_w_gate"]),
+                                     _p(g["d_w1"]), _p(g["d_w2"]), _p(g.get("d_b1")), _p(g.get("d_b2")))
     return g
 
 
