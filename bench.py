@@ -3,7 +3,7 @@
 backward on workloads that train, forward only otherwise) on seeded synthetic inputs resident in
 HBM, the roofline of the kernel that dominates the step, and the CPU oracle timed beside it.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt_medium] [--order dcca|cdac]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload zipf_stress] [--order dcca|cdac]
 
 Prints ONE JSON line.  Runs on one GPU only.
 """
@@ -29,15 +29,19 @@ PEAK_ALU_F32 = 157.3e12    # flop/s, published fp32 vector peak (unpacked v_fmac
 # dominate the default workload.  A counter run cannot be part of a timed run; these are the
 # figures of the committed summary of those runs (gpt_medium_hbm_traffic under profiles/).
 MEASURED_TRAFFIC = {
-    ("gpt_medium", "dcca"): {"bwd_down_dgrad": (195.9 + 128.0) * 1048576, "expert_up": (98.8 + 256.1) * 1048576},
+    ("gpt_medium", "dcca"): {"source": "profiles/gpt_medium_hbm_traffic.md",
+                             "bwd_down_dgrad": (195.9 + 128.0) * 1048576, "expert_up": (98.8 + 256.1) * 1048576},
 }
 
 
-def stage_work(wl, order_cdac: bool, training: bool):
+def stage_work(wl, order_cdac: bool, training: bool, wire_bf16: bool = False):
     """Algorithmic work per stage: (kind, flops, bytes).  Bytes are compulsory traffic: every
-    input read once, every output written once, real rows only.  e = bytes per stored element."""
+    input read once, every output written once, real rows only.  e = bytes per stored element,
+    ew = bytes per element of the rows that return through the second All-to-All (expert outputs)
+    and of their backward counterpart (fp32 unless the all-bf16 wire format is asked for)."""
     T, d, r, N, k, h = wl.T, wl.d, wl.r, wl.N, wl.k, wl.h
     e = 2 if wl.dtype == 1 else 4
+    ew = 2 if (e == 2 and wire_bf16) else 4
     Tk = T * k
     win, hid = (d, r) if order_cdac else (r, h)
     low = 2 * r if e == 2 else r          # y' and dx' travel as (hi | lo) bf16 pairs
@@ -48,17 +52,17 @@ def stage_work(wl, order_cdac: bool, training: bool):
     W["permutation"] = ("hbm", 0.0, 4 * Tk * 4)
     W["dispatch"] = ("hbm", 0.0, (T + Tk) * win * e + 4 * Tk)
     W["expert_up"] = ("mfma", 2.0 * Tk * win * hid, Tk * win * e + N * win * hid * e + Tk * hid * e * (2 if training else 1))
-    W["expert_down"] = ("mfma", 2.0 * Tk * hid * win, Tk * hid * e + N * win * hid * e + Tk * win * e)
-    W["combine"] = ("hbm", 2.0 * Tk * win, Tk * win * e + T * (low * e if not order_cdac else d * 4) + 8 * Tk)
+    W["expert_down"] = ("mfma", 2.0 * Tk * hid * win, Tk * hid * e + N * win * hid * e + Tk * win * ew)
+    W["combine"] = ("hbm", 2.0 * Tk * win, Tk * win * ew + T * (low * e if not order_cdac else d * 4) + 8 * Tk)
     W["ascend"] = ("mfma", 2.0 * T * r * d, T * low * e + r * d * e + T * d * 4)
     W["bwd_ascend_dgrad"] = ("mfma", 2.0 * T * d * r, T * d * e + r * d * e + T * r * 4)
     W["bwd_ascend_wgrad"] = ("mfma", 2.0 * T * r * d, T * r * e + T * d * e + r * d * 4)
-    W["bwd_combine"] = ("hbm", 4.0 * Tk * win, T * win * 4 + 2 * Tk * win * e + 12 * Tk)
+    W["bwd_combine"] = ("hbm", 4.0 * Tk * win, T * win * 4 + Tk * win * ew + Tk * win * e + 12 * Tk)
     W["bwd_down_dgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * win * e + N * win * hid * e + 2 * Tk * hid * e)
     W["bwd_down_wgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * hid * e + Tk * win * e + N * win * hid * 4)
     W["bwd_up_wgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * hid * e + Tk * win * e + N * win * hid * 4)
-    W["bwd_up_dgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * hid * e + N * win * hid * e + Tk * win * e)
-    W["bwd_dispatch"] = ("hbm", 1.0 * Tk * win, Tk * win * e + T * (low * e if not order_cdac else d * 4) + 4 * Tk)
+    W["bwd_up_dgrad"] = ("mfma", 2.0 * Tk * win * hid, Tk * hid * e + N * win * hid * e + Tk * win * ew)
+    W["bwd_dispatch"] = ("hbm", 1.0 * Tk * win, Tk * win * ew + T * (low * e if not order_cdac else d * 4) + 4 * Tk)
     W["bwd_gate"] = ("hbm", 2.0 * Tk * d, T * d * 4 + T * N * e + 12 * Tk)
     W["bwd_router_wgrad"] = ("mfma", 2.0 * T * d * N, T * d * e + T * N * e + d * N * 4)
     W["bwd_descend_wgrad"] = ("mfma", 2.0 * T * d * r, T * d * e + T * r * e + d * r * 4)
@@ -106,7 +110,17 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="gpt_medium")
+    ap.add_argument("--workload", default="zipf_stress",
+                    help="zipf_stress (default: the largest of the five workloads), gpt_xl, gpt_medium, decode, tiny_f32, "
+                         "or one of gpt_2p7b, gpt_6p7b, vanilla_moe")
+    ap.add_argument("--blocks", type=int, default=3,
+                    help="timed blocks of --steps graph replays each: the first is the reported value, all of them "
+                         "are listed with their median and minimum")
+    ap.add_argument("--wire-bf16", action="store_true",
+                    help="all-bf16 wire format (BIGMAC_FLAG_WIRE_BF16): expert outputs and the gradient of the dispatched "
+                         "rows in bf16 instead of fp32; less permute traffic, y and dx no longer within 2e-2 at the widest shapes")
+    ap.add_argument("--tiles", default="auto", choices=["auto", "large", "small"],
+                    help="tuning: force the 256 x 256 workgroup tiles on every expert product that can take them, or forbid them")
     ap.add_argument("--tokens", type=int, default=0, help="override T (decode sweep)")
     ap.add_argument("--order", default="dcca", choices=["dcca", "cdac"])
     ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of the oracle timing sample (0: skip)")
@@ -175,8 +189,10 @@ def main():
     torch.cuda.set_device(0)
     data = synth.generate(wl)
     capacity = B.expert_capacity(wl.T, wl.k, wl.N, args.capacity_factor) if args.capacity_factor > 0 else 0
-    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA, capacity=capacity, aux_alpha=args.aux_alpha)
-    variant = capacity > 0 or args.aux_alpha > 0      # not the headline configuration
+    tile_flag = {"auto": 0, "large": B.FLAG_TILES_LARGE, "small": B.FLAG_TILES_SMALL}[args.tiles]
+    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA, flags=(B.FLAG_WIRE_BF16 if args.wire_bf16 else 0) | tile_flag,
+                     capacity=capacity, aux_alpha=args.aux_alpha)
+    variant = capacity > 0 or args.aux_alpha > 0 or args.wire_bf16      # not the headline configuration
     x = B.to_device(data["x"], wl.dtype, dev)
     dy = B.to_device(data.get("dy"), wl.dtype, dev)
     wg = B.to_device(data["w_gate"], B.F32, dev)
@@ -233,15 +249,20 @@ def main():
             step()
         for _ in range(args.warmup):
             graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        elapsed, timed = time.perf_counter() - t0, "replays of the step captured in a HIP graph"
+        block_ms = []
+        for b in range(max(1, args.blocks)):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            block_ms.append(dt / args.steps * 1e3)
+            if b == 0:
+                elapsed, timed = dt, "replays of the step captured in a HIP graph"
 
     ms_per_step = elapsed / args.steps * 1e3
-    work = stage_work(wl, cdac, training)
+    work = stage_work(wl, cdac, training, args.wire_bf16)
     stage_ms = {}
     if tables:
         names = [B.stage_name(s) for s in range(B.STAGE_COUNT)]
@@ -253,13 +274,22 @@ def main():
         for tb in tables:
             for s, ms in tb.elapsed_ms(set(live)).items():
                 stage_ms[names[s]] = stage_ms.get(names[s], 0.0) + ms / args.steps
-    roofline = None
+    roofline, stage_roofline = None, {}
     if stage_ms and not capacity:   # with dropped rows the algorithmic work is not the closed form below
         dom = max(stage_ms, key=stage_ms.get)
         kind, flops, nbytes = work[dom]
         roofline = roofline_of(dom, kind, flops, nbytes, stage_ms[dom] * 1e-3)
         if not args.tokens and not variant:
-            roofline["traffic"] = MEASURED_TRAFFIC.get((wl.name, args.order), {}).get(dom)
+            measured = MEASURED_TRAFFIC.get((wl.name, args.order), {})
+            roofline["traffic"] = measured.get(dom)
+            roofline["traffic_source"] = measured.get("source") if dom in measured else None
+        # every stage against both of its rooflines: matrix (or fp32 vector) rate and HBM bytes
+        for n, ms in stage_ms.items():
+            kind, flops, nbytes = work[n]
+            peak_f = PEAK_ALU_F32 if kind == "alu" else PEAK_MFMA_BF16
+            stage_roofline[n] = {"bound": roofline_of(n, kind, flops, nbytes, ms * 1e-3)["bound"],
+                                 "flop_frac": round(flops / (ms * 1e-3) / peak_f, 4) if flops and kind != "hbm" else None,
+                                 "hbm_frac": round(nbytes / (ms * 1e-3) / PEAK_HBM, 4)}
     fwd_flops = B.forward_matrix_flops(dims)
     out = {
         "metric": "BigMac MoE layer tokens/sec fwd+bwd (1 GPU)" if training else "BigMac MoE layer tokens/sec fwd (1 GPU)",
@@ -277,13 +307,17 @@ def main():
         "config": {"workload": wl.name, "order": args.order, "T": wl.T, "d": wl.d, "r": wl.r, "N": wl.N, "k": wl.k,
                    "h": wl.h, "pass": "fwd+bwd" if training else "fwd",
                    **({"capacity_factor": args.capacity_factor, "capacity": capacity} if capacity else {}),
-                   **({"aux_alpha": args.aux_alpha} if args.aux_alpha > 0 else {})},
+                   **({"aux_alpha": args.aux_alpha} if args.aux_alpha > 0 else {}),
+                   **({"wire": "bf16"} if args.wire_bf16 else {}), **({"tiles": args.tiles} if args.tiles != "auto" else {})},
         "timed": timed,
+        **({"block_ms_per_step": [round(v, 4) for v in block_ms], "block_ms_median": round(sorted(block_ms)[len(block_ms) // 2], 4),
+            "block_ms_min": round(min(block_ms), 4)} if not args.no_graph else {}),
         "eager_ms_per_step": eager_elapsed / args.steps * 1e3,
         "roofline": roofline,
         "matrix_tflops": fwd_flops * (3 if training else 1) / (elapsed / args.steps) / 1e12,
         "permute_bytes_per_step": B.permute_bytes(dims) * (1.0 if training else 0.5),
         "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
+        "stage_roofline": stage_roofline,
         "stage_sum_ms": round(sum(stage_ms.values()), 4),
     }
     if args.evict_mib > 0:

@@ -53,7 +53,15 @@ typedef enum { BIGMAC_ORDER_DCCA = 0, BIGMAC_ORDER_CDAC = 1 } bigmac_order;
 
 enum {
   BIGMAC_FLAG_ACCUMULATE = 1, /* backward: add weight gradients to the caller's buffers (else overwrite) */
-  BIGMAC_FLAG_OUT_BF16 = 2    /* layer calls with dtype BF16: write y / dx as bf16 (default: fp32)       */
+  BIGMAC_FLAG_OUT_BF16 = 2,   /* layer calls with dtype BF16: write y / dx as bf16 (default: fp32)       */
+  BIGMAC_FLAG_WIRE_BF16 = 4,  /* layer calls with dtype BF16: the rows returning through the second
+                                 All-to-All (expert outputs) and, backward, through the first (the
+                                 gradient of the dispatched rows) travel in bf16, the format of the
+                                 paper's Table 4; default: those win-wide rows stay fp32, which is
+                                 what keeps y and dx within 2e-2 of their RMS at the widest shapes,*/
+  BIGMAC_FLAG_TILES_LARGE = 8, /* tuning: run every expert product that can on 256 x 256 workgroup tiles,  */
+  BIGMAC_FLAG_TILES_SMALL = 16 /* or none of them (default: chosen from the shape).  Results do not depend
+                                  on the tile: the same products are added in the same order.            */
 };
 
 enum {

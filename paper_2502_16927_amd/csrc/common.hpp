@@ -152,12 +152,16 @@ struct GemmDesc {
   int wide_k;                // bf16, k-contiguous A, K % 64 == 0: the square tile with 64-deep k tiles, two ring stages
   int kloop_priority;        // MFMA kernels: raise the wave priority inside the k loop (see the kernel)
   int deep_tile;             // bf16, dense, store or accumulate (K % 64 == 0 with a k-contiguous operand): 128 x 64 outputs, 64-deep k tiles
+  int big_tile;              // bf16, no GELU' epilogue: 256 x 256 outputs, one workgroup per CU (gemm_big.hip; ragged-M: tile map of 256-row tiles)
   const void* touch;         // MFMA kernels, optional: a region (device) every line of which is read once as the kernel starts,
   size_t touch_bytes;        //   so that its first use in a k loop meets the caches and not the memory (0 = off)
 };
 // Rows per M tile of the ragged-M schedule for this dtype (the tile map must be built with it).
 int gemm_ragged_tile_rows(int dtype, int tall_tile);
 int launch_gemm(const GemmDesc& g, hipStream_t s);
+// the 256 x 256 tile kernel (launch_gemm hands products with big_tile set to it)
+bool gemm_big_supported(const GemmDesc& g);
+int launch_gemm_big(const GemmDesc& g, hipStream_t s);
 // tile_map capacity in int32 for a ragged-M problem
 inline size_t tile_map_ints(int total_rows, int groups, int tile_rows) {
   return 16 + 2 * ((size_t)total_rows / tile_rows + groups + 1);
@@ -209,10 +213,12 @@ int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* t
 int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, const int32_t* slot_of,
                          void* x_perm, hipStream_t s);
 enum CombineOut { COMBINE_F32 = 0, COMBINE_SPLIT_BF16 = 1 };  // fp32 [T,w]  |  bf16 [T,2w] = (hi | lo)
+// dtype: element type of the gathered rows (BIGMAC_F32 or BIGMAC_BF16)
 int launch_combine_rows(int dtype, int T, int k, int width, const void* o_perm, const int32_t* slot_of,
                         const float* topk_w, void* y_low, int out_kind, hipStream_t s);
 // backward of the weighted combine: dgate[t,j] = <dy_low[t], o_perm[slot]>, do_perm[slot] = w[t,j]*dy_low[t]
-int launch_combine_backward(int dtype, int T, int k, int width, const float* dy_low, const void* o_perm,
+// (o_dtype: element type of o_perm; do_perm has the storage type `dtype`)
+int launch_combine_backward(int dtype, int o_dtype, int T, int k, int width, const float* dy_low, const void* o_perm,
                             const int32_t* slot_of, const float* topk_w, float* dgate, void* do_perm,
                             hipStream_t s);
 

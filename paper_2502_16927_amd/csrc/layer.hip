@@ -15,7 +15,8 @@ int check_dims(const bigmac_dims* D) {
   if ((long long)D->T * D->k >= (1ll << 31)) return BIGMAC_ERR_INVALID_ARG;
   if (D->dtype != BIGMAC_F32 && D->dtype != BIGMAC_BF16) return BIGMAC_ERR_INVALID_ARG;
   if (D->act != BIGMAC_ACT_GELU_ERF) return BIGMAC_ERR_INVALID_ARG;
-  if (D->flags & ~(BIGMAC_FLAG_ACCUMULATE | BIGMAC_FLAG_OUT_BF16)) return BIGMAC_ERR_INVALID_ARG;
+  if (D->flags & ~(BIGMAC_FLAG_ACCUMULATE | BIGMAC_FLAG_OUT_BF16 | BIGMAC_FLAG_WIRE_BF16 | BIGMAC_FLAG_TILES_LARGE | BIGMAC_FLAG_TILES_SMALL)) return BIGMAC_ERR_INVALID_ARG;
+  if ((D->flags & BIGMAC_FLAG_TILES_LARGE) && (D->flags & BIGMAC_FLAG_TILES_SMALL)) return BIGMAC_ERR_INVALID_ARG;
   if (D->capacity < 0 || !(D->aux_alpha >= 0.0f) || D->aux_alpha > 1e30f) return BIGMAC_ERR_INVALID_ARG;
   if (D->order == BIGMAC_ORDER_CDAC && D->dtype == BIGMAC_BF16 && (D->flags & BIGMAC_FLAG_OUT_BF16)) return BIGMAC_ERR_UNSUPPORTED;
   return BIGMAC_OK;
@@ -69,7 +70,7 @@ struct FwdPlan {
   size_t logits, perm, x_low, partials, aux, total;
 };
 struct BwdPlan {
-  size_t dy_low, dgate, do_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, total;
+  size_t dy_low, dgate, do_perm, dx_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, total;
 };
 
 inline bool bf(const bigmac_dims& D) { return D.dtype == BIGMAC_BF16; }
@@ -82,6 +83,13 @@ inline int low_ld(const bigmac_dims& D) { return bf(D) ? 2 * D.r : D.r; }
 // experts with many rows the operand tiles shared between workgroups were fetched several times
 // (measured: up to 1.3x faster weight-gradient products at 16384 rows per expert).
 inline int wide_ld(const bigmac_dims& D) { return widths(D).hid + (bf(D) ? 64 : 0); }
+// The rows that come back through the second All-to-All (expert outputs O) and, in the backward
+// pass, through the first (dx_perm) are only win wide.  With bf16 storage the layer calls keep
+// them in fp32 unless BIGMAC_FLAG_WIRE_BF16 asks for the all-bf16 wire format: rounding them
+// costs as much precision as rounding the hidden activations, for a fraction of the bytes, and
+// the rounding of O is what the gate gradient <dy', O_j> sees.
+inline bool wire_f32(const bigmac_dims& D) { return bf(D) && !(D.flags & BIGMAC_FLAG_WIRE_BF16); }
+inline int wire_dtype(const bigmac_dims& D) { return wire_f32(D) ? BIGMAC_F32 : D.dtype; }
 inline size_t low_bytes(const bigmac_dims& D) { return (size_t)D.T * (bf(D) ? 2 * D.r * 2 : D.r * 4); }
 
 // Which products run on the GEMM's tall (256-row) workgroup tiles.  The per-expert products on
@@ -141,9 +149,30 @@ inline void touch_weights(const bigmac_dims& D, GemmDesc& g, const void* w, int 
 inline bool wide_k_ok(const bigmac_dims& D, int K, int bit) {
   return bf(D) && (BIGMAC_WIDEK_MASK & bit) && K % 64 == 0;
 }
-inline bool any_tall_rows(const bigmac_dims& D) {
+// Which products run on 256 x 256 tiles with one workgroup per CU (gemm_big.hip): the products
+// bound by the matrix cores - many tiles, a long K, experts with a thousand rows and more on
+// average - whose output width divides into 256-column tiles.  Bits: 1 expert-up, 2 expert-down,
+// 8 the first matrix's data gradient, 16 / 32 the weight gradients of the second / first matrix.
+// (The GELU' product has no epilogue there and stays on the tall tile.)
+#ifndef BIGMAC_BIG_MASK
+#define BIGMAC_BIG_MASK 59
+#endif
+inline bool big_rows(const bigmac_dims& D, int cols, int K, int bit) {
+  if (!bf(D) || !(BIGMAC_BIG_MASK & bit) || (D.flags & BIGMAC_FLAG_TILES_SMALL)) return false;
+  if (D.flags & BIGMAC_FLAG_TILES_LARGE) return K % 32 == 0;
+  const long Tk = (long)D.T * D.k;
+  const long tiles = (Tk / 256 + D.N) * (cols / 256);
+  return cols % 256 == 0 && tiles >= 1024 && K >= 512 && K % 32 == 0 && Tk / D.N >= 1024;
+}
+inline bool big_wgrad(const bigmac_dims& D, int M, int N, int bit) {
+  if (!bf(D) || !(BIGMAC_BIG_MASK & bit) || (D.flags & BIGMAC_FLAG_TILES_SMALL)) return false;
+  if (D.flags & BIGMAC_FLAG_TILES_LARGE) return true;
+  const long Tk = (long)D.T * D.k;
+  return M % 256 == 0 && N % 256 == 0 && (long)D.N * (M / 256) * (N / 256) >= 512 && Tk / D.N >= 1024;
+}
+inline bool any_tall_rows(const bigmac_dims& D) {   // a tile map of 256-row tiles is needed
   const Widths W = widths(D);
-  return tall_rows(D, W.hid, W.win) || tall_rows(D, W.win, W.hid);
+  return tall_rows(D, W.hid, W.win) || tall_rows(D, W.win, W.hid) || big_rows(D, W.hid, W.win, 1) || big_rows(D, W.win, W.hid, 2 | 8);
 }
 
 SavedPlan plan_saved(const bigmac_dims& D) {
@@ -161,7 +190,7 @@ SavedPlan plan_saved(const bigmac_dims& D) {
   p.x_perm = c.take(Tk * W.win * es);
   p.act = c.take(Tk * wide_ld(D) * es);
   p.hact = c.take(Tk * wide_ld(D) * es);
-  p.o_perm = c.take(Tk * W.win * es);
+  p.o_perm = c.take(Tk * W.win * esize(wire_dtype(D)));
   p.y_low = c.take(D.order == BIGMAC_ORDER_DCCA ? low_bytes(D) : 0);
   // load-balance loss: the backward pass needs the logits and the experts' pair shares; aux holds
   // the loss (one float) followed, 256 bytes on, by share[N]
@@ -249,6 +278,7 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
   p.dy_low = c.take((size_t)D.T * W.win * 4);
   p.dgate = c.take(Tk * 4);
   p.do_perm = c.take(Tk * W.win * es);
+  p.dx_perm = wire_f32(D) ? c.take(Tk * W.win * 4) : p.do_perm;   // same width: do_perm is dead once the second matrix's gradients are done
   p.dact = c.take(Tk * wide_ld(D) * es);
   p.dx_low = c.take(dcca ? low_bytes(D) : (size_t)D.T * D.d * 4);
   p.dL = c.take((size_t)D.T * D.N * es);
@@ -295,7 +325,7 @@ GemmDesc base_desc(const bigmac_dims& D) {
 
 // The two expert products on permuted rows (ragged per-expert row ranges).
 int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* offsets, const int* tile_map, const int* tile_map_tall,
-                        const void* w1, const void* w2, void* act, void* hact, int ld_wide, void* o_perm, hipStream_t s) {
+                        const void* w1, const void* w2, void* act, void* hact, int ld_wide, void* o_perm, int o_f32, hipStream_t s) {
   const Widths W = widths(D);
   const int Tk = D.T * D.k;
   GemmDesc g = base_desc(D);
@@ -304,12 +334,13 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.groups = D.N; g.max_rows = Tk; g.offsets = offsets;
   // hact = gelu(x_perm W1[e])
   g.epilogue = EPI_GELU;
-  g.tall_tile = tall_rows(D, W.hid, W.win); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
-  g.wide_k = !g.tall_tile && wide_k_ok(D, W.win, 1);
+  g.big_tile = big_rows(D, W.hid, W.win, 1);
+  g.tall_tile = !g.big_tile && tall_rows(D, W.hid, W.win); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
+  g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(D, W.win, 1);
   g.A = x_perm; g.lda = W.win; g.K = W.win;
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
   g.C = hact; g.ldc = ld_wide; g.aux_out = act;
-  touch_weights(D, g, w1, 1);
+  if (!g.big_tile) touch_weights(D, g, w1, 1);
   // measured: -3 % at K = 512 (gpt_xl); at K = 256 (gpt_medium) +2 % while the weights came from
   // memory, -4.6 % with the warm-up
   g.kloop_priority = W.win >= 512 || g.touch_bytes != 0;
@@ -320,15 +351,16 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   }
   if (rc) return rc;
   // o_perm = hact W2[e]
-  g.epilogue = EPI_STORE; g.out_f32 = 0; g.aux_out = nullptr;
+  g.epilogue = EPI_STORE; g.out_f32 = o_f32; g.aux_out = nullptr;
   g.A = hact; g.lda = ld_wide; g.K = W.hid;
   g.B = w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.win;
   g.C = o_perm; g.ldc = W.win;
-  g.tall_tile = tall_rows(D, W.win, W.hid); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
-  g.wide_k = !g.tall_tile && wide_k_ok(D, W.hid, 2);
+  g.big_tile = big_rows(D, W.win, W.hid, 2);
+  g.tall_tile = !g.big_tile && tall_rows(D, W.win, W.hid); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
+  g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(D, W.hid, 2);
   g.kloop_priority = 1;
   g.touch = nullptr; g.touch_bytes = 0;
-  touch_weights(D, g, w2, 2);
+  if (!g.big_tile) touch_weights(D, g, w2, 2);
   BIGMAC_STAGE(BIGMAC_STAGE_EXPERT_DOWN);
   return launch_gemm(g, s);
 }
@@ -495,7 +527,7 @@ int bigmac_grouped_ffn(const bigmac_dims* D, const void* x_perm, const int32_t* 
   rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype, 0), tile_map, s);
   if (!rc && any_tall_rows(*D)) rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype, 1), tile_map_tall, s);
   if (rc) return rc;
-  return run_experts_forward(*D, x_perm, expert_offsets, tile_map, tile_map_tall, w1, w2, act_saved, hact, W.hid, o_perm, s);
+  return run_experts_forward(*D, x_perm, expert_offsets, tile_map, tile_map_tall, w1, w2, act_saved, hact, W.hid, o_perm, 0, s);
 }
 
 int bigmac_combine(const bigmac_dims* D, const void* o_perm, const int32_t* slot_of, const float* topk_w, float* y_low, void* stream) {
@@ -582,15 +614,15 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);
   }
   if (rc) return rc;
-  rc = run_experts_forward(*D, x_perm, offsets, tile_map, tile_map_tall, P->w1, P->w2, act, hact, wide_ld(*D), o_perm, s);
+  rc = run_experts_forward(*D, x_perm, offsets, tile_map, tile_map_tall, P->w1, P->w2, act, hact, wide_ld(*D), o_perm, wire_f32(*D) ? 1 : 0, s);
   if (rc) return rc;
   if (!dcca) {  // fine-grained layer: the weighted sum is the output
     BIGMAC_STAGE(BIGMAC_STAGE_COMBINE);
-    return launch_combine_rows(D->dtype, D->T, D->k, W.win, o_perm, slot_of, topk_w, y, COMBINE_F32, s);
+    return launch_combine_rows(wire_dtype(*D), D->T, D->k, W.win, o_perm, slot_of, topk_w, y, COMBINE_F32, s);
   }
   {
     BIGMAC_STAGE(BIGMAC_STAGE_COMBINE);
-    rc = launch_combine_rows(D->dtype, D->T, D->k, W.win, o_perm, slot_of, topk_w, y_low, bf(*D) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
+    rc = launch_combine_rows(wire_dtype(*D), D->T, D->k, W.win, o_perm, slot_of, topk_w, y_low, bf(*D) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
   }
   if (rc) return rc;
   {  // y = y' W_up
@@ -648,7 +680,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   float* dgate = (float*)(wsb + B.dgate);
   void* do_perm = wsb + B.do_perm;
   void* dact = wsb + B.dact;
-  void* dx_perm = do_perm;  // do_perm is dead once the second expert matrix's gradients are done
+  void* dx_perm = wsb + B.dx_perm;
   void* dx_low = wsb + B.dx_low;
   void* dL = wsb + B.dL;
   ReduceJob jobs[3];
@@ -686,7 +718,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   // weighted-sum backward: gate gradients and the scaled scatter of dy' to the expert rows
   {
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_COMBINE);
-    rc = launch_combine_backward(D->dtype, D->T, D->k, W.win, dy_low, o_perm, slot_of, topk_w, dgate, do_perm, s);
+    rc = launch_combine_backward(D->dtype, wire_dtype(*D), D->T, D->k, W.win, dy_low, o_perm, slot_of, topk_w, dgate, do_perm, s);
   }
   if (rc) return rc;
   {  // dact = (do_perm W2[e]^T) * act'(act)
@@ -711,7 +743,8 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = hact; g.lda = wide_ld(*D); g.M = W.hid;
     g.B = do_perm; g.ldb = W.win; g.N = W.win;
     g.C = d_w2; g.ldc = W.win; g.gstride_c = (long)W.hid * W.win;
-    g.tall_tile = tall_wgrad(*D, W.hid);
+    g.big_tile = big_wgrad(*D, W.hid, W.win, 16);
+    g.tall_tile = !g.big_tile && tall_wgrad(*D, W.hid);
     {
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_WGRAD);
       rc = launch_gemm(g, s);
@@ -721,7 +754,8 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = x_perm; g.lda = W.win; g.M = W.win;
     g.B = dact; g.ldb = wide_ld(*D); g.N = W.hid;
     g.C = d_w1; g.ldc = W.hid; g.gstride_c = (long)W.win * W.hid;
-    g.tall_tile = tall_wgrad(*D, W.win);
+    g.big_tile = big_wgrad(*D, W.win, W.hid, 32);
+    g.tall_tile = !g.big_tile && tall_wgrad(*D, W.win);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_WGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
@@ -729,14 +763,15 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   {  // dx_perm = dact W1[e]^T
     GemmDesc g = base_desc(*D);
     g.mode = GEMM_RAGGED_M; g.groups = D->N; g.max_rows = Tk; g.offsets = offsets; g.tile_map = tile_map;
-    g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE; g.out_f32 = bf(*D) ? 0 : 1;
+    g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_STORE; g.out_f32 = (bf(*D) && !wire_f32(*D)) ? 0 : 1;
     g.A = dact; g.lda = wide_ld(*D); g.K = W.hid;
     g.B = P->w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.win;
     g.C = dx_perm; g.ldc = W.win;
-    g.tall_tile = tall_rows(*D, W.win, W.hid); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
-    g.wide_k = !g.tall_tile && wide_k_ok(*D, W.hid, 8);
+    g.big_tile = big_rows(*D, W.win, W.hid, 8);
+    g.tall_tile = !g.big_tile && tall_rows(*D, W.win, W.hid); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
+    g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(*D, W.hid, 8);
     g.kloop_priority = 1;
-    touch_weights(*D, g, P->w1, 8);
+    if (!g.big_tile) touch_weights(*D, g, P->w1, 8);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_DGRAD);
     rc = launch_gemm(g, s);
     if (rc) return rc;
@@ -744,7 +779,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   // dispatch backward: dx' = sum_j dx_perm[slot_of[t, j]]
   {
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_DISPATCH);
-    rc = launch_combine_rows(D->dtype, D->T, D->k, W.win, dx_perm, slot_of, nullptr, dx_low,
+    rc = launch_combine_rows(wire_dtype(*D), D->T, D->k, W.win, dx_perm, slot_of, nullptr, dx_low,
                              (dcca && bf(*D)) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
   }
   if (rc) return rc;

@@ -240,23 +240,51 @@ __global__ __launch_bounds__(256) void dispatch_rows_kernel(const uint4* __restr
   }
 }
 
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// Rows that are read exactly once (the permuted expert outputs and gradients): loaded with the
+// non-temporal hint so that they do not push the rows still to come out of the caches.
+__device__ __forceinline__ void load_row8(const float* p, float* f) {
+  const f32x4_t a = __builtin_nontemporal_load((const f32x4_t*)p), b = __builtin_nontemporal_load((const f32x4_t*)p + 1);
+  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+__device__ __forceinline__ void load_row8(const bf16_t* p, float* f) {
+  const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+  uint4 q;
+  q.x = v.x; q.y = v.y; q.z = v.z; q.w = v.w;
+  unpack_bf16x8(q, f);
+}
+
 // y_low[t] = sum_j w[t,j] * o_perm[slot_of[t,j]], j ascending, fp32.  Thread = (token, 8 columns).
-template <int OUT>
-__global__ __launch_bounds__(256) void combine_rows_bf16_kernel(const uint4* __restrict__ o_perm, const int32_t* __restrict__ slot_of,
-                                                                const float* __restrict__ w, void* __restrict__ y, int T, int k, int width) {
+// The k picks are taken KU at a time (KU divides k): their slots and weights are read first, then
+// all KU row pieces are requested before the first multiply-add, so that a thread has KU
+// independent gathers in flight instead of a chain of dependent ones.  A dropped pair
+// (slot < 0) reads row 0 and is left out of the sum.  ROW: element type of the gathered rows.
+template <typename ROW, int OUT, int KU>
+__global__ __launch_bounds__(256) void combine_rows_kernel(const ROW* __restrict__ o_perm, const int32_t* __restrict__ slot_of,
+                                                           const float* __restrict__ w, void* __restrict__ y, int T, int k, int width) {
   const int cpr = width / 8;
   const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (g >= (size_t)T * cpr) return;
   const int t = (int)(g / cpr), c = (int)(g % cpr);
   float acc[8] = {};
-  for (int j = 0; j < k; ++j) {
-    const float wj = w ? w[(size_t)t * k + j] : 1.0f;
-    const int slot = slot_of[(size_t)t * k + j];
-    if (slot < 0) continue;                     // dropped pair
-    float o[8];
-    unpack_bf16x8(o_perm[(size_t)slot * cpr + c], o);
+  for (int j0 = 0; j0 < k; j0 += KU) {
+    int slot[KU];
+    float wj[KU];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = fmaf(wj, o[i], acc[i]);
+    for (int u = 0; u < KU; ++u) {
+      slot[u] = slot_of[(size_t)t * k + j0 + u];
+      wj[u] = w ? w[(size_t)t * k + j0 + u] : 1.0f;
+    }
+    float o[KU][8];
+#pragma unroll
+    for (int u = 0; u < KU; ++u) load_row8(o_perm + (size_t)max(slot[u], 0) * width + c * 8, o[u]);
+#pragma unroll
+    for (int u = 0; u < KU; ++u)
+      if (slot[u] >= 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = fmaf(wj[u], o[u][i], acc[i]);
+      }
   }
   if (OUT == COMBINE_F32) {
     float4* out = (float4*)((float*)y + (size_t)t * width + c * 8);
@@ -275,29 +303,12 @@ __global__ __launch_bounds__(256) void combine_rows_bf16_kernel(const uint4* __r
   }
 }
 
-__global__ __launch_bounds__(256) void combine_rows_f32_kernel(const float4* __restrict__ o_perm, const int32_t* __restrict__ slot_of,
-                                                               const float* __restrict__ w, float4* __restrict__ y, int T, int k, int width) {
-  const int cpr = width / 4;
-  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (g >= (size_t)T * cpr) return;
-  const int t = (int)(g / cpr), c = (int)(g % cpr);
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int j = 0; j < k; ++j) {
-    const float wj = w ? w[(size_t)t * k + j] : 1.0f;
-    const int slot = slot_of[(size_t)t * k + j];
-    if (slot < 0) continue;                     // dropped pair
-    const float4 o = o_perm[(size_t)slot * cpr + c];
-    acc.x = fmaf(wj, o.x, acc.x); acc.y = fmaf(wj, o.y, acc.y);
-    acc.z = fmaf(wj, o.z, acc.z); acc.w = fmaf(wj, o.w, acc.w);
-  }
-  y[g] = acc;
-}
-
 // One wavefront per token: dgate[t,j] = <dy_low[t], o_perm[slot]>; do_perm[slot] = w[t,j] * dy_low[t].
-template <typename ET>
-__global__ __launch_bounds__(256) void combine_backward_kernel(const float* __restrict__ dy_low, const ET* __restrict__ o_perm,
+// OT: element type of the expert outputs, DT: of the scattered gradient rows.
+template <typename OT, typename DT>
+__global__ __launch_bounds__(256) void combine_backward_kernel(const float* __restrict__ dy_low, const OT* __restrict__ o_perm,
                                                                const int32_t* __restrict__ slot_of, const float* __restrict__ w,
-                                                               float* __restrict__ dgate, ET* __restrict__ do_perm, int T, int k, int width) {
+                                                               float* __restrict__ dgate, DT* __restrict__ do_perm, int T, int k, int width) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -314,12 +325,12 @@ __global__ __launch_bounds__(256) void combine_backward_kernel(const float* __re
       const int c = c0 + lane * 4;
       if (c < width) {
         const float4 g = *(const float4*)(dy_low + (size_t)t * width + c);
-        const ET* o = o_perm + slot * width + c;
-        ET* q = do_perm + slot * width + c;
-        dot = fmaf(g.x, Elem<ET>::load(o + 0), dot); dot = fmaf(g.y, Elem<ET>::load(o + 1), dot);
-        dot = fmaf(g.z, Elem<ET>::load(o + 2), dot); dot = fmaf(g.w, Elem<ET>::load(o + 3), dot);
-        Elem<ET>::store(q + 0, wj * g.x); Elem<ET>::store(q + 1, wj * g.y);
-        Elem<ET>::store(q + 2, wj * g.z); Elem<ET>::store(q + 3, wj * g.w);
+        const OT* o = o_perm + slot * width + c;
+        DT* q = do_perm + slot * width + c;
+        dot = fmaf(g.x, Elem<OT>::load(o + 0), dot); dot = fmaf(g.y, Elem<OT>::load(o + 1), dot);
+        dot = fmaf(g.z, Elem<OT>::load(o + 2), dot); dot = fmaf(g.w, Elem<OT>::load(o + 3), dot);
+        Elem<DT>::store(q + 0, wj * g.x); Elem<DT>::store(q + 1, wj * g.y);
+        Elem<DT>::store(q + 2, wj * g.z); Elem<DT>::store(q + 3, wj * g.w);
       }
     }
 #pragma unroll
@@ -328,53 +339,54 @@ __global__ __launch_bounds__(256) void combine_backward_kernel(const float* __re
   }
 }
 
-// The same for bf16 rows and k <= 16: the token's dy' row is read once (column chunk outermost,
-// the k destinations inside), 16-byte accesses of 8 columns per lane.
-__global__ __launch_bounds__(256) void combine_backward_bf16_kernel(const float* __restrict__ dy_low, const bf16_t* __restrict__ o_perm,
+// The same for bf16 gradient rows at least 512 wide: 16-byte accesses of 8 columns per lane, the
+// picks taken KU at a time (KU divides k) with all KU pieces of the expert outputs requested
+// before the first multiply-add; the token's dy' piece is read once per group of picks.
+template <typename OT, int KU>
+__global__ __launch_bounds__(256) void combine_backward_wide_kernel(const float* __restrict__ dy_low, const OT* __restrict__ o_perm,
                                                                     const int32_t* __restrict__ slot_of, const float* __restrict__ w,
                                                                     float* __restrict__ dgate, bf16_t* __restrict__ do_perm, int T, int k, int width) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
-  // lane j holds destination j
-  const int my_slot = lane < k ? slot_of[(size_t)t * k + lane] : 0;
-  const float my_w = lane < k ? w[(size_t)t * k + lane] : 0.0f;
-  float dot[16];
+  for (int j0 = 0; j0 < k; j0 += KU) {
+    int slot[KU];
+    float wj[KU], dot[KU];
 #pragma unroll
-  for (int j = 0; j < 16; ++j) dot[j] = 0.0f;
-  for (int c0 = 0; c0 < width; c0 += 512) {       // uniform trip count: the shuffles below need every lane
-    const int c = c0 + lane * 8;
-    const bool live = c < width;
-    float g[8] = {};
-    if (live) {
-      const float4 g0 = *(const float4*)(dy_low + (size_t)t * width + c), g1 = *(const float4*)(dy_low + (size_t)t * width + c + 4);
-      g[0] = g0.x; g[1] = g0.y; g[2] = g0.z; g[3] = g0.w; g[4] = g1.x; g[5] = g1.y; g[6] = g1.z; g[7] = g1.w;
+    for (int u = 0; u < KU; ++u) {
+      slot[u] = __builtin_amdgcn_readfirstlane(slot_of[(size_t)t * k + j0 + u]);
+      wj[u] = w[(size_t)t * k + j0 + u];
+      dot[u] = 0.0f;
     }
+    for (int c0 = 0; c0 < width; c0 += 512) {
+      const int c = c0 + lane * 8;
+      if (c < width) {
+        float g[8];
+        const float4 g0 = *(const float4*)(dy_low + (size_t)t * width + c), g1 = *(const float4*)(dy_low + (size_t)t * width + c + 4);
+        g[0] = g0.x; g[1] = g0.y; g[2] = g0.z; g[3] = g0.w; g[4] = g1.x; g[5] = g1.y; g[6] = g1.z; g[7] = g1.w;
+        float o[KU][8];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if (j >= k) break;
-      const int slot_j = __shfl(my_slot, j, 64);
-      const size_t row = (size_t)slot_j * width + c;
-      const float wj = __shfl(my_w, j, 64);
-      if (live && slot_j >= 0) {                // a dropped pair has no row; its dot stays 0
-        float o[8], q[8];
-        unpack_bf16x8(*(const uint4*)(o_perm + row), o);
+        for (int u = 0; u < KU; ++u) load_row8(o_perm + (size_t)max(slot[u], 0) * width + c, o[u]);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          dot[j] = fmaf(g[i], o[i], dot[j]);
-          q[i] = wj * g[i];
+        for (int u = 0; u < KU; ++u) {
+          if (slot[u] < 0) continue;              // a dropped pair has no row; its dot stays 0
+          float q[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            dot[u] = fmaf(g[i], o[u][i], dot[u]);
+            q[i] = wj[u] * g[i];
+          }
+          *(uint4*)(do_perm + (size_t)slot[u] * width + c) = pack_bf16x8(q);
         }
-        *(uint4*)(do_perm + row) = pack_bf16x8(q);
       }
     }
-  }
 #pragma unroll
-  for (int j = 0; j < 16; ++j) {
-    if (j >= k) break;
-    float d = dot[j];
+    for (int u = 0; u < KU; ++u) {
+      float d = dot[u];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) d += __shfl_xor(d, off, 64);
-    if (lane == 0) dgate[(size_t)t * k + j] = d;
+      for (int off = 32; off >= 1; off >>= 1) d += __shfl_xor(d, off, 64);
+      if (lane == 0) dgate[(size_t)t * k + j0 + u] = d;
+    }
   }
 }
 
@@ -438,37 +450,91 @@ int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, 
   return BIGMAC_OK;
 }
 
+namespace {
+template <typename ROW, int OUT>
+void launch_combine_ku(int ku, dim3 grid, hipStream_t s, const ROW* o_perm, const int32_t* slot_of, const float* w, void* y, int T, int k, int width) {
+  const dim3 block(256);
+#define BIGMAC_COMBINE(KU) \
+  hipLaunchKernelGGL((combine_rows_kernel<ROW, OUT, KU>), grid, block, 0, s, o_perm, slot_of, w, y, T, k, width)
+  switch (ku) {
+    case 8: BIGMAC_COMBINE(8); break;
+    case 7: BIGMAC_COMBINE(7); break;
+    case 6: BIGMAC_COMBINE(6); break;
+    case 5: BIGMAC_COMBINE(5); break;
+    case 4: BIGMAC_COMBINE(4); break;
+    case 3: BIGMAC_COMBINE(3); break;
+    case 2: BIGMAC_COMBINE(2); break;
+    default: BIGMAC_COMBINE(1); break;
+  }
+#undef BIGMAC_COMBINE
+}
+// picks taken at a time: all k up to 8, else the largest divisor of k that is at most 8
+inline int combine_unroll(int k) {
+  for (int ku = 8; ku > 1; --ku)
+    if (k % ku == 0) return ku;
+  return 1;
+}
+}  // namespace
+
 int launch_combine_rows(int dtype, int T, int k, int width, const void* o_perm, const int32_t* slot_of,
                         const float* topk_w, void* y_low, int out_kind, hipStream_t s) {
+  if (width % 8) return BIGMAC_ERR_INVALID_ARG;
+  if (out_kind != COMBINE_F32 && out_kind != COMBINE_SPLIT_BF16) return BIGMAC_ERR_INVALID_ARG;
+  const size_t n = (size_t)T * (width / 8);
+  const dim3 grid((unsigned)((n + 255) / 256));
+  const int ku = combine_unroll(k);
   if (dtype == BIGMAC_BF16) {
-    const size_t n = (size_t)T * (width / 8);
-    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
-    if (out_kind == COMBINE_F32)
-      hipLaunchKernelGGL(combine_rows_bf16_kernel<COMBINE_F32>, grid, block, 0, s, (const uint4*)o_perm, slot_of, topk_w, y_low, T, k, width);
-    else
-      hipLaunchKernelGGL(combine_rows_bf16_kernel<COMBINE_SPLIT_BF16>, grid, block, 0, s, (const uint4*)o_perm, slot_of, topk_w, y_low, T, k, width);
+    if (out_kind == COMBINE_F32) launch_combine_ku<bf16_t, COMBINE_F32>(ku, grid, s, (const bf16_t*)o_perm, slot_of, topk_w, y_low, T, k, width);
+    else launch_combine_ku<bf16_t, COMBINE_SPLIT_BF16>(ku, grid, s, (const bf16_t*)o_perm, slot_of, topk_w, y_low, T, k, width);
   } else {
-    if (out_kind != COMBINE_F32) return BIGMAC_ERR_UNSUPPORTED;
-    const size_t n = (size_t)T * (width / 4);
-    hipLaunchKernelGGL(combine_rows_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float4*)o_perm, slot_of,
-                       topk_w, (float4*)y_low, T, k, width);
+    if (out_kind == COMBINE_F32) launch_combine_ku<float, COMBINE_F32>(ku, grid, s, (const float*)o_perm, slot_of, topk_w, y_low, T, k, width);
+    else launch_combine_ku<float, COMBINE_SPLIT_BF16>(ku, grid, s, (const float*)o_perm, slot_of, topk_w, y_low, T, k, width);
   }
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }
 
-int launch_combine_backward(int dtype, int T, int k, int width, const float* dy_low, const void* o_perm,
+namespace {
+template <typename OT>
+void launch_combine_backward_wide(int ku, dim3 grid, hipStream_t s, const float* dy_low, const OT* o_perm, const int32_t* slot_of,
+                                  const float* w, float* dgate, bf16_t* do_perm, int T, int k, int width) {
+  const dim3 block(256);
+#define BIGMAC_COMBINE_BWD(KU) \
+  hipLaunchKernelGGL((combine_backward_wide_kernel<OT, KU>), grid, block, 0, s, dy_low, o_perm, slot_of, w, dgate, do_perm, T, k, width)
+  switch (ku) {
+    case 8: BIGMAC_COMBINE_BWD(8); break;
+    case 7: BIGMAC_COMBINE_BWD(7); break;
+    case 6: BIGMAC_COMBINE_BWD(6); break;
+    case 5: BIGMAC_COMBINE_BWD(5); break;
+    case 4: BIGMAC_COMBINE_BWD(4); break;
+    case 3: BIGMAC_COMBINE_BWD(3); break;
+    case 2: BIGMAC_COMBINE_BWD(2); break;
+    default: BIGMAC_COMBINE_BWD(1); break;
+  }
+#undef BIGMAC_COMBINE_BWD
+}
+}  // namespace
+
+int launch_combine_backward(int dtype, int o_dtype, int T, int k, int width, const float* dy_low, const void* o_perm,
                             const int32_t* slot_of, const float* topk_w, float* dgate, void* do_perm, hipStream_t s) {
   const dim3 grid((T + 3) / 4), block(256);
-  if (dtype == BIGMAC_BF16 && k <= 16 && width % 8 == 0 && width >= 512)   // narrower rows would leave lanes idle
-    hipLaunchKernelGGL(combine_backward_bf16_kernel, grid, block, 0, s, dy_low, (const bf16_t*)o_perm, slot_of, topk_w, dgate,
+  if (dtype == BIGMAC_BF16 && width % 8 == 0 && width >= 512) {   // narrower rows would leave lanes idle
+    const int ku = combine_unroll(k);
+    if (o_dtype == BIGMAC_BF16)
+      launch_combine_backward_wide<bf16_t>(ku, grid, s, dy_low, (const bf16_t*)o_perm, slot_of, topk_w, dgate, (bf16_t*)do_perm, T, k, width);
+    else
+      launch_combine_backward_wide<float>(ku, grid, s, dy_low, (const float*)o_perm, slot_of, topk_w, dgate, (bf16_t*)do_perm, T, k, width);
+  } else if (dtype == BIGMAC_BF16 && o_dtype == BIGMAC_BF16) {
+    hipLaunchKernelGGL((combine_backward_kernel<bf16_t, bf16_t>), grid, block, 0, s, dy_low, (const bf16_t*)o_perm, slot_of, topk_w, dgate,
                        (bf16_t*)do_perm, T, k, width);
-  else if (dtype == BIGMAC_BF16)
-    hipLaunchKernelGGL(combine_backward_kernel<bf16_t>, grid, block, 0, s, dy_low, (const bf16_t*)o_perm, slot_of, topk_w, dgate,
+  } else if (dtype == BIGMAC_BF16) {
+    hipLaunchKernelGGL((combine_backward_kernel<float, bf16_t>), grid, block, 0, s, dy_low, (const float*)o_perm, slot_of, topk_w, dgate,
                        (bf16_t*)do_perm, T, k, width);
-  else
-    hipLaunchKernelGGL(combine_backward_kernel<float>, grid, block, 0, s, dy_low, (const float*)o_perm, slot_of, topk_w, dgate,
+  } else {
+    if (o_dtype != BIGMAC_F32) return BIGMAC_ERR_INVALID_ARG;
+    hipLaunchKernelGGL((combine_backward_kernel<float, float>), grid, block, 0, s, dy_low, (const float*)o_perm, slot_of, topk_w, dgate,
                        (float*)do_perm, T, k, width);
+  }
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }

@@ -9,13 +9,41 @@ from paper_2502_16927_amd import binding as B
 from paper_2502_16927_amd import synth
 
 TOL = 2e-2          # max-abs error relative to the RMS of the oracle tensor (outputs and gradients)
-# The layer stores x', act(x' W1) and the expert outputs in bf16 (the dispatched rows and the MFMA
-# operands).  Those three roundings alone - emulated on the CPU in fp64 with no GPU code, see
-# tests/test_precision_floor.py - put 0.29 % RMS of noise on y whose largest element over a few
-# hundred thousand reaches 2.1e-2 of the RMS at the widest shapes (d = 4096, r = 1024), where the
-# pre-activations are large enough for the GELU to amplify the rounding of x'.  For those
-# workloads the bar on y is 1.25 x TOL; it stays TOL for the others.
-TOL_WIDE = 1.25 * TOL
+# Weight gradients.  The bar is the plain one: each gradient tensor the interface hands out
+# (d_w1 [N, win, hid] as a whole, ...) against its RMS.  On top of it the block of every expert
+# (W1[e], W2[e], W_g[:, e]) whose gradient is a sum over enough rows is held to the same bar against
+# the RMS of the block itself (under skewed routing a popular expert's large gradient would
+# otherwise be the yardstick for all).  "Enough rows" counts effective rows, (sum_s p_s)^2 /
+# sum_s p_s^2 over the gate values p_s of the expert's rows: an element of the block is a sum of
+# per-row products weighted by p_s, and with few effective rows its largest values, and the
+# rounding errors of the bf16 operands on them, sit far above the block's RMS - the measure
+# breaks down, not the kernel.  A CPU emulation that only rounds the bf16-stored operands (no
+# GPU code) gives, at the GPT3-2.7B widths with top-8 gating, 0.025 / 0.030 / 0.041 of the RMS at
+# 512 / 256 / 128 rows per expert while the RMS of the error stays at 0.0031 throughout; the GPU
+# path measures the same (0.015-0.017 on whole experts of the uniform workloads, 0.020 at 700
+# effective rows of the skewed one, 0.026 at 480, 0.031 at 190, 0.040 at 19).  The edge-case shapes of the small tests (a few rows per expert, down to T = 1) are in
+# that regime as whole tensors; their expert gradients are judged against the largest element of
+# the block instead, and say so.
+MIN_EFFECTIVE_ROWS = 1024
+
+
+def effective_rows(idx: np.ndarray, gate: np.ndarray, N: int, mask: np.ndarray | None = None) -> np.ndarray:
+    """(sum p)^2 / sum p^2 of the gate values of each expert's rows ([T, k] routing from the oracle;
+    mask [T, k] or [T] selects the pairs that contribute).  0 for an expert without rows."""
+    w = np.asarray(gate, np.float64)
+    if mask is not None:
+        m = np.asarray(mask, np.float64)
+        w = w * (m[:, None] if m.ndim == 1 else m)
+    live = w > 0
+    s1 = np.bincount(idx[live], weights=w[live], minlength=N)
+    s2 = np.bincount(idx[live], weights=w[live] ** 2, minlength=N)
+    return np.where(s2 > 0, s1 * s1 / np.maximum(s2, 1e-300), 0.0)
+
+
+def expert_effective_rows(oracle, data: dict, wl, mask: np.ndarray | None = None) -> np.ndarray:
+    """effective_rows of the oracle's routing of this workload's tokens."""
+    idx, gate, _ = oracle.route(data["x"], data["w_gate"], data["gate_bias"], wl.k)
+    return effective_rows(idx, gate, wl.N, mask)
 
 
 def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
@@ -24,43 +52,33 @@ def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
     return float(np.abs(np.asarray(gpu, np.float64) - ref).max() / max(rms, 1e-30))
 
 
-def check_dx(gpu_rows: np.ndarray, ref_rows: np.ndarray, tol: float = TOL):
-    """dx on sampled tokens.  dx carries the gate gradient sum_j dlogit_j W_g[:, e_j], whose error is
-    a per-token error of dlogit (through the bf16-stored expert outputs) times a per-element
-    weight: a product of two Gaussians, with a far heavier tail than the other tensors.  A CPU
-    emulation of the pipeline that does nothing but round the stored tensors to bf16 (no GPU code)
-    shows the same tail: about 1 token in 300 above 2e-2 of the RMS at the GPT-XL shape.  The bar
-    is therefore: every sampled token within 1.5 x tol, and at most 1 % of them above tol."""
-    ref_rows = np.asarray(ref_rows, np.float64)
-    rms = float(np.sqrt(np.mean(ref_rows * ref_rows)))
-    per_token = np.abs(np.asarray(gpu_rows, np.float64) - ref_rows).max(axis=1) / rms
-    worst, over = float(per_token.max()), float(np.mean(per_token > tol))
-    assert worst < 1.5 * tol and over <= 0.01, f"dx: worst token {worst:.4f}, {over:.2%} of tokens above {tol}"
-    return worst, over
-
-
-def wgrad_err(gpu: np.ndarray, ref: np.ndarray, rows_per_expert: float) -> float:
-    """Error measure for a weight gradient.  With many rows per expert every element is a long
-    sum and the error is a small Gaussian fraction of the tensor's RMS: the 2e-2 bar applies as
-    it stands.  With only a few rows (below 256: degenerate test shapes, token samples) an element is a handful of
-    products whose largest values sit far above the RMS, and a bf16 rounding of 2^-9 relative
-    on such an element alone exceeds 2e-2 of the RMS; there the error is taken relative to the
-    largest element instead."""
-    if rows_per_expert >= 256:
-        return rel_err(gpu, ref)
+def rel_err_to_largest(gpu: np.ndarray, ref: np.ndarray) -> float:
     ref = np.asarray(ref, np.float64)
     return float(np.abs(np.asarray(gpu, np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
-def check_weight_grads(grads: dict, ref: dict, counts: np.ndarray, T: int, tol: float, dcca: bool = True, scale: float = 1.0):
-    """Every parameter matrix against the oracle.  The matrices of one expert (W1[e], W2[e] and
-    the expert's gating column W_g[:, e]) are parameters of their own: each is compared with the
-    RMS of its own gradient, so that under skewed routing a popular expert's large gradient does
-    not set the bar for the others.  An expert without rows must get an exactly zero gradient."""
+def check_dx(gpu_rows: np.ndarray, ref_rows: np.ndarray, tol: float = TOL) -> float:
+    """dx on sampled tokens: the largest error of any element against the RMS of the oracle rows."""
+    worst = rel_err(gpu_rows, ref_rows)
+    assert worst < tol, f"dx: max-abs/rms {worst:.4f} >= {tol}"
+    return worst
+
+
+def check_weight_grads(grads: dict, ref: dict, counts: np.ndarray, tol: float, dcca: bool = True, few_rows: bool = False,
+                       skewed: bool = False):
+    """Every weight gradient against the oracle: each tensor as a whole against its RMS, and the
+    block of every expert with enough rows against the block's own RMS.  counts: effective rows per
+    expert (effective_rows above; 0 = the expert has no rows).  few_rows=True (edge-case shapes with
+    a handful of rows per expert): the expert gradients d_w1, d_w2, d_w_gate are judged block by
+    block against the block's largest element instead (see above); the shared projections'
+    gradients, sums over all tokens, keep the RMS measure.  skewed=True (routing with a few very
+    popular experts): the expert gradients are judged block by block only - the RMS of the whole
+    tensor is then diluted by the many experts with hardly any rows and no yardstick for the popular
+    experts' blocks, whose own RMS is several times larger.  An expert without rows must get an
+    exactly zero gradient."""
     worst = {}
-    if dcca:
-        for n in ("d_w_down", "d_w_up"):
-            worst[n] = wgrad_err(grads[n], ref[n], T)
+    for n in (("d_w_down", "d_w_up") if dcca else ()) + (() if few_rows or skewed else ("d_w1", "d_w2", "d_w_gate")):
+        worst[n] = rel_err(grads[n], ref[n])
     for n in ("d_w1", "d_w2", "d_w_gate"):
         w = 0.0
         for e, c in enumerate(counts):
@@ -68,18 +86,26 @@ def check_weight_grads(grads: dict, ref: dict, counts: np.ndarray, T: int, tol: 
             r = ref[n][:, e] if n == "d_w_gate" else ref[n][e]
             if c == 0:
                 assert not np.any(g) and not np.any(r), f"{n}[{e}]: expert without rows has a gradient"
-                continue
-            err = wgrad_err(g, r, c)
-            if n == "d_w_gate":
-                # a gating column fed by a handful of rows is x_t times one scalar dlogit, itself a
-                # difference of gate gradients that can cancel: its own size is no yardstick, the
-                # whole matrix's RMS (the plain reading of the bar) is
-                err = min(err, float(np.abs(g - r).max() / np.sqrt(np.mean(np.asarray(ref[n], np.float64) ** 2))))
-            w = max(w, err)
-        worst[n] = w
-    for n, v in worst.items():
-        assert v < tol * scale, f"{n}: {v:.4f} >= {tol * scale}"
-    return worst
+            elif c >= MIN_EFFECTIVE_ROWS:
+                w = max(w, rel_err(g, r))
+            elif few_rows:
+                err = rel_err_to_largest(g, r)
+                if n == "d_w_gate":
+                    # a gating column fed by a handful of rows is x_t times one scalar dlogit, itself a
+                    # difference of gate gradients that can cancel: the column's own size is no yardstick
+                    # then, the whole matrix's RMS (the plain reading of the bar) is
+                    err = min(err, float(np.abs(g - r).max() / np.sqrt(np.mean(np.asarray(ref[n], np.float64) ** 2))))
+                w = max(w, err)
+        worst[n + (" (worst block, vs its largest element)" if few_rows else " (worst expert block)")] = w
+    bad = {n: round(v, 4) for n, v in worst.items() if not v < tol}
+    assert not bad, f"weight gradients above {tol}: {bad} (all: { {n: round(v, 4) for n, v in worst.items()} })"
+    return {n: round(v, 4) for n, v in worst.items()}
+
+
+def few_rows_per_expert(counts: np.ndarray) -> bool:
+    """True when some expert that has rows has fewer than MIN_EFFECTIVE_ROWS effective ones."""
+    c = np.asarray(counts)
+    return bool(np.any((c > 0) & (c < MIN_EFFECTIVE_ROWS)))
 
 
 def host(t: torch.Tensor) -> np.ndarray:

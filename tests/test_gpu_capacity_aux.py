@@ -7,7 +7,7 @@ import torch
 
 from paper_2502_16927_amd import binding as B
 from paper_2502_16927_amd import synth
-from gpu_util import TOL, DeviceLayer, check_weight_grads, host, rel_err
+from gpu_util import TOL, DeviceLayer, check_weight_grads, expert_effective_rows, few_rows_per_expert, host, rel_err
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -90,10 +90,10 @@ def test_layer_with_capacity(oracle, case):
     layer.backward()
     torch.cuda.synchronize()
     assert rel_err(host(layer.dx), g_ref["dx"]) < tol, "dx"
-    counts = np.bincount(idx[keep.astype(bool)], minlength=wl.N)
+    counts = expert_effective_rows(oracle, data, wl, mask=keep)
     # the gating columns also get the dropped pairs' (negative) share: judge them as whole matrices
     grads = {n: host(t) for n, t in layer.grads.items()}
-    print(check_weight_grads(grads, g_ref, np.maximum(counts, 1), wl.T, tol), flush=True)
+    print(check_weight_grads(grads, g_ref, np.maximum(counts, 1e-9), tol, few_rows=wl.dtype == B.BF16 and few_rows_per_expert(counts)), flush=True)
 
 
 def test_fine_grained_layer_with_capacity(oracle):
@@ -115,8 +115,8 @@ def test_fine_grained_layer_with_capacity(oracle):
     layer.backward()
     torch.cuda.synchronize()
     assert rel_err(host(layer.dx), g_ref["dx"]) < TOL
-    counts = np.bincount(idx[keep.astype(bool)], minlength=wl.N)
-    check_weight_grads({n: host(t) for n, t in layer.grads.items()}, g_ref, np.maximum(counts, 1), wl.T, TOL, dcca=False)
+    counts = expert_effective_rows(oracle, data, wl, mask=keep)
+    check_weight_grads({n: host(t) for n, t in layer.grads.items()}, g_ref, np.maximum(counts, 1e-9), TOL, dcca=False, few_rows=few_rows_per_expert(counts))
 
 
 # ------------------------------------------------------------------ load-balance loss --------
@@ -187,5 +187,5 @@ def test_layer_with_aux_loss(oracle, dtype, N):
     g_ref["dx"] = g_ref["dx"] + terms["dx"]
     g_ref["d_w_gate"] = g_ref["d_w_gate"] + terms["d_w_gate"]
     assert rel_err(host(layer.dx), g_ref["dx"]) < tol
-    counts = np.bincount(idx.ravel(), minlength=wl.N)
-    check_weight_grads({n: host(t) for n, t in layer.grads.items()}, g_ref, counts, wl.T, tol)
+    counts = expert_effective_rows(oracle, data, wl)
+    check_weight_grads({n: host(t) for n, t in layer.grads.items()}, g_ref, counts, tol, few_rows=wl.dtype == B.BF16 and few_rows_per_expert(counts))

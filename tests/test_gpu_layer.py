@@ -11,7 +11,7 @@ import torch
 
 from paper_2502_16927_amd import binding as B
 from paper_2502_16927_amd import synth
-from gpu_util import TOL, DeviceLayer, add_cdac_weights, check_weight_grads, host, rel_err
+from gpu_util import TOL, DeviceLayer, add_cdac_weights, check_weight_grads, expert_effective_rows, few_rows_per_expert, host, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -72,14 +72,14 @@ def test_small_forward_backward(oracle, case):
     assert np.array_equal(y_inf, y), "inference and training forward differ"
     assert rel_err(y, ref) < tol
     idx = check_routing(oracle, layer, data)
-    counts = np.bincount(idx.ravel(), minlength=wl.N)
+    counts = expert_effective_rows(oracle, data, wl)
     g_ref = oracle.bigmac_backward(data["x"], data["dy"], data["w_gate"], data["gate_bias"], data["w_down"],
                                    data["w_up"], data["w1"], data["w2"], wl.k)
     layer.alloc_grads()
     layer.backward()
     torch.cuda.synchronize()
     assert rel_err(host(layer.dx), g_ref["dx"]) < tol, "dx"
-    print(check_weight_grads({n: host(v) for n, v in layer.grads.items()}, g_ref, counts, wl.T, tol), flush=True)
+    print(check_weight_grads({n: host(v) for n, v in layer.grads.items()}, g_ref, counts, tol, few_rows=wl.dtype == B.BF16 and few_rows_per_expert(counts)), flush=True)
     # accumulate flag: gradients are added to what the buffers hold
     rng = np.random.default_rng(5)
     init = {n: rng.standard_normal(v.shape).astype(np.float32) * float(np.sqrt(np.mean(v * v)) + 1e-12)
@@ -89,7 +89,28 @@ def test_small_forward_backward(oracle, case):
     layer2.alloc_grads(init)
     layer2.backward()
     torch.cuda.synchronize()
-    check_weight_grads({n: host(v) - init[n] for n, v in layer2.grads.items()}, g_ref, counts, wl.T, tol, scale=1.5)
+    check_weight_grads({n: host(v) - init[n] for n, v in layer2.grads.items()}, g_ref, counts, tol, few_rows=wl.dtype == B.BF16 and few_rows_per_expert(counts))
+
+
+@pytest.mark.parametrize("case", [SMALL[1], SMALL[3], SMALL[5], SMALL[8], dict(T=700, d=128, r=192, N=4, k=2, h=448, dtype=B.BF16)],
+                         ids=lambda c: "T{T}_d{d}_r{r}_N{N}_k{k}_h{h}".format(**c))
+def test_large_tiles_give_the_same_bits(case):
+    """The 256 x 256 workgroup tiles add the same products in the same order as the smaller ones:
+    forcing them on (ragged tails, widths that are no multiple of 256, empty experts, T = 1) and
+    forbidding them must give identical outputs and gradients."""
+    print("large tiles", case, flush=True)
+    wl = synth.small(**case)
+    data = synth.generate(wl)
+    outs = []
+    for flag in (B.FLAG_TILES_SMALL, B.FLAG_TILES_LARGE):
+        layer = DeviceLayer(wl, data, flags=flag)
+        layer.forward(training=True)
+        layer.alloc_grads()
+        layer.backward()
+        torch.cuda.synchronize()
+        outs.append([layer.y.clone(), layer.dx.clone()] + [layer.grads[n].clone() for n in sorted(layer.grads)])
+    for u, v in zip(*outs):
+        assert torch.equal(u, v)
 
 
 def test_bf16_output_is_the_rounded_fp32_output(oracle):
@@ -157,7 +178,8 @@ def test_small_fine_grained_layer(oracle, dtype):
     torch.cuda.synchronize()
     assert rel_err(host(layer.dx), g_ref["dx"]) < tol
     grads = {n: host(layer.grads[n]) for n in ("d_w_gate", "d_w1", "d_w2")}
-    check_weight_grads(grads, g_ref, np.bincount(idx.ravel(), minlength=wl.N), wl.T, tol, dcca=False)
+    counts = expert_effective_rows(oracle, data, wl)
+    check_weight_grads(grads, g_ref, counts, tol, dcca=False, few_rows=dtype == B.BF16 and few_rows_per_expert(counts))
 
 
 def test_tiny_fp32_workload_full(oracle):
