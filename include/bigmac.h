@@ -69,7 +69,8 @@ enum {
   BIGMAC_ERR_INVALID_ARG = -1,
   BIGMAC_ERR_WORKSPACE = -2,
   BIGMAC_ERR_UNSUPPORTED = -3,
-  BIGMAC_ERR_HIP = -4
+  BIGMAC_ERR_HIP = -4,
+  BIGMAC_ERR_TOO_LARGE = -5   /* bigmac_dispatch_static: the problem exceeds the library's static scratch */
 };
 
 typedef struct {
@@ -145,6 +146,20 @@ int bigmac_aux_loss(const bigmac_dims *dims, const float *logits /*[T,N]*/, cons
 int bigmac_dispatch(const bigmac_dims *dims, const void *x_low, const int32_t *topk_idx,
                     void *x_perm, int32_t *expert_offsets, int32_t *slot_of, int32_t *src_of,
                     void *ws, size_t ws_bytes, void *stream);
+
+/* bigmac_dispatch for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and kernels as bigmac_dispatch, without `ws`: the counting sort's counters live in a 4 MiB array
+ * inside the library's device image (one copy per GPU, held until the process ends).  The call
+ * allocates and frees nothing.  It needs ceil(T*k / 1024) * N * 4 bytes of that array (T*k / 256
+ * chunks while that many times N stays within 32768) and returns BIGMAC_ERR_TOO_LARGE beyond 4 MiB
+ * (e.g. T*k = 2^23 pairs over 128 experts still fit).  All calls on one GPU share the array: calls
+ * that overlap in time on one GPU (different streams, or threads) race; calls on one stream do not.
+ * The first call on a device looks the array's address up (no allocation); make that call outside
+ * a graph capture. */
+int bigmac_dispatch_static(const bigmac_dims *dims, const void *x_low, const int32_t *topk_idx,
+                           void *x_perm, int32_t *expert_offsets, int32_t *slot_of, int32_t *src_of,
+                           void *stream);
 
 /* The experts of Eq. 4 (Eq. 3 for CDAC) on permuted rows: for the rows s of expert e,
  * o_perm[s, :] = act(x_perm[s, :] W1[e]) W2[e].  act_saved ([T*k, hid] dtype, the

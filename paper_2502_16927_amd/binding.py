@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.bigmac_route.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.bigmac_dispatch.restype = ci
         L.bigmac_dispatch.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bigmac_dispatch_static.restype = ci
+        L.bigmac_dispatch_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         L.bigmac_grouped_ffn.restype = ci
         L.bigmac_grouped_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.bigmac_combine.restype = ci
@@ -79,7 +81,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("bigmac_workspace_bytes", "bigmac_status_string", "bigmac_forward_matrix_flops", "bigmac_permute_bytes",
-           "bigmac_saved_layout", "bigmac_saved_aux_layout", "bigmac_aux_loss", "bigmac_route", "bigmac_dispatch", "bigmac_grouped_ffn", "bigmac_combine",
+           "bigmac_saved_layout", "bigmac_saved_aux_layout", "bigmac_aux_loss", "bigmac_route", "bigmac_dispatch", "bigmac_dispatch_static", "bigmac_grouped_ffn", "bigmac_combine",
            "bigmac_layer_forward", "bigmac_layer_backward", "bigmac_set_stage_events", "bigmac_stage_name",
            "bigmac_mfma_probe")
 STAGE_COUNT = 22
@@ -167,6 +169,11 @@ def bigmac_route(dims, x, w_gate, gate_bias, topk_idx, topk_w, logits_out=None, 
 def bigmac_dispatch(dims, x_low, topk_idx, x_perm, expert_offsets, slot_of, src_of, ws, stream=None):
     _check(lib().bigmac_dispatch(ctypes.byref(dims), _ptr(x_low), _ptr(topk_idx), _ptr(x_perm), _ptr(expert_offsets),
                                  _ptr(slot_of), _ptr(src_of), _ptr(ws), _nbytes(ws), _stream(stream)), "bigmac_dispatch")
+
+
+def bigmac_dispatch_static(dims, x_low, topk_idx, x_perm, expert_offsets, slot_of, src_of, stream=None):
+    _check(lib().bigmac_dispatch_static(ctypes.byref(dims), _ptr(x_low), _ptr(topk_idx), _ptr(x_perm), _ptr(expert_offsets),
+                                        _ptr(slot_of), _ptr(src_of), _stream(stream)), "bigmac_dispatch_static")
 
 
 def bigmac_grouped_ffn(dims, x_perm, expert_offsets, w1, w2, act_saved, o_perm, ws, stream=None):

@@ -413,6 +413,7 @@ const char* bigmac_status_string(int status) {
     case BIGMAC_ERR_WORKSPACE: return "workspace too small";
     case BIGMAC_ERR_UNSUPPORTED: return "unsupported combination";
     case BIGMAC_ERR_HIP: return "HIP launch failed";
+    case BIGMAC_ERR_TOO_LARGE: return "problem exceeds the static scratch of the allocation-free entry point";
     default: return "unknown status";
   }
 }

@@ -6,6 +6,13 @@
 #include "common.hpp"
 #include "tile_map.hpp"
 
+#include <atomic>
+
+// Scratch of the allocation-free dispatch (bigmac_dispatch_static): the per-chunk expert counters
+// of the counting sort.  One copy per GPU the library runs on, held until the process ends.
+#define BIGMAC_STATIC_SCRATCH_BYTES (4u << 20)
+static __device__ __align__(256) unsigned char scratch[BIGMAC_STATIC_SCRATCH_BYTES];
+
 namespace bigmac {
 
 namespace {
@@ -539,4 +546,41 @@ int launch_combine_backward(int dtype, int o_dtype, int T, int k, int width, con
   return BIGMAC_OK;
 }
 
+namespace {
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// stand-in for the symbol, not a device address: the address is asked for once per device (each
+// GPU holds its own copy at its own address) and kept.
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES];
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return BIGMAC_ERR_HIP;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BIGMAC_ERR_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // two first calls racing store the same address
+  }
+  *out = p;
+  return BIGMAC_OK;
+}
+}  // namespace
+
 }  // namespace bigmac
+
+extern "C" int bigmac_dispatch_static(const bigmac_dims* D, const void* x_low, const int32_t* topk_idx, void* x_perm,
+                                      int32_t* expert_offsets, int32_t* slot_of, int32_t* src_of, void* stream) {
+  using namespace bigmac;
+  int rc = check_dims(D);
+  if (rc) return rc;
+  if (!topk_idx || !expert_offsets || !slot_of || !src_of) return BIGMAC_ERR_INVALID_ARG;
+  if ((x_low == nullptr) != (x_perm == nullptr)) return BIGMAC_ERR_INVALID_ARG;
+  if (permutation_ws_bytes(D->T, D->k, D->N) > BIGMAC_STATIC_SCRATCH_BYTES) return BIGMAC_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  // every counter the sort reads is written by its first kernel in the same call: nothing to clear
+  rc = launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, expert_offsets, slot_of, src_of, ws, s);
+  if (rc || !x_low) return rc;
+  return launch_dispatch_rows(D->dtype, D->T, D->k, widths(*D).win, x_low, slot_of, x_perm, s);
+}
