@@ -60,8 +60,12 @@ enum {
                                  paper's Table 4; default: those win-wide rows stay fp32, which is
                                  what keeps y and dx within 2e-2 of their RMS at the widest shapes,*/
   BIGMAC_FLAG_TILES_LARGE = 8, /* tuning: run every expert product that can on 256 x 256 workgroup tiles,  */
-  BIGMAC_FLAG_TILES_SMALL = 16 /* or none of them (default: chosen from the shape).  Results do not depend
+  BIGMAC_FLAG_TILES_SMALL = 16,/* or none of them (default: chosen from the shape).  Results do not depend
                                   on the tile: the same products are added in the same order.            */
+  BIGMAC_FLAG_ROUTE_LOW = 32   /* layer calls, DCCA order: the router reads x' instead of x (Section 3.1
+                                  names both inputs): w_gate and d_w_gate are [r, N], the logits are those of
+                                  bigmac_route on the stored x' (dtype) with d = r, and the gate's gradient
+                                  reaches x through x' (and so W_down).  A fourth of the router's work.   */
 };
 
 enum {
@@ -88,6 +92,8 @@ typedef struct {          /* parameters: caller-owned, never written            
   const float *gate_bias; /* [N]      fp32 or NULL, added to the logits                            */
   const void *w1;         /* [N, win, hid] dtype   first expert matrix  (Eq. 4: W_i,up; Eq. 3: W_i,down) */
   const void *w2;         /* [N, hid, win] dtype   second expert matrix (Eq. 4: W_i,down; Eq. 3: W_i,up) */
+  const void *b1;         /* [N, hid] dtype or NULL   expert biases (the 2rh term of the expert parameters in   */
+  const void *b2;         /* [N, win] dtype or NULL   Table 3):  E_i(x') = act(x' W1[i] + b1[i]) W2[i] + b2[i]  */
 } bigmac_params;
 
 typedef enum {
@@ -162,11 +168,12 @@ int bigmac_dispatch_static(const bigmac_dims *dims, const void *x_low, const int
                            void *stream);
 
 /* The experts of Eq. 4 (Eq. 3 for CDAC) on permuted rows: for the rows s of expert e,
- * o_perm[s, :] = act(x_perm[s, :] W1[e]) W2[e].  act_saved ([T*k, hid] dtype, the
- * pre-activation x_perm W1) may be NULL. */
+ * o_perm[s, :] = act(x_perm[s, :] W1[e] + b1[e]) W2[e] + b2[e].  b1 ([N, hid] dtype) and b2 ([N, win]
+ * dtype) are the optional expert biases (Table 3 counts 2rh of them per expert); NULL: none.
+ * act_saved ([T*k, hid] dtype, the pre-activation x_perm W1 + b1) may be NULL. */
 int bigmac_grouped_ffn(const bigmac_dims *dims, const void *x_perm, const int32_t *expert_offsets,
-                       const void *w1, const void *w2, void *act_saved, void *o_perm /*[T*k,win] dtype*/,
-                       void *ws, size_t ws_bytes, void *stream);
+                       const void *w1, const void *w2, const void *b1, const void *b2, void *act_saved,
+                       void *o_perm /*[T*k,win] dtype*/, void *ws, size_t ws_bytes, void *stream);
 
 /* Second All-to-All plus the weighted sum of Eq. 2: y_low[t, :] = sum_j topk_w[t, j] *
  * o_perm[slot_of[t, j], :], added in j order in fp32.  topk_w == NULL means unit weights (the
@@ -183,12 +190,14 @@ int bigmac_layer_forward(const bigmac_dims *dims, const bigmac_params *params, c
 
 /* Whole layer backward with the top-k set held fixed.  dy is [T, d] dtype, dx is [T, d] (type
  * as y).  Weight gradients are fp32 with the shapes of their weights and are overwritten, or
- * added to with BIGMAC_FLAG_ACCUMULATE; d_w_down / d_w_up are ignored for CDAC.  `saved` is
- * the block written by the forward call with the same dims, params and x. */
+ * added to with BIGMAC_FLAG_ACCUMULATE; d_w_down / d_w_up are ignored for CDAC.  d_b1 [N, hid] and
+ * d_b2 [N, win] are required exactly when params has b1 / b2 (column sums of the gradients of the
+ * pre-activation and of the expert outputs over each expert's rows).  `saved` is the block written
+ * by the forward call with the same dims, params and x. */
 int bigmac_layer_backward(const bigmac_dims *dims, const bigmac_params *params, const void *x,
                           const void *dy, const void *saved, void *dx, float *d_w_down,
-                          float *d_w_up, float *d_w_gate, float *d_w1, float *d_w2, void *ws,
-                          size_t ws_bytes, void *stream);
+                          float *d_w_up, float *d_w_gate, float *d_w1, float *d_w2, float *d_b1,
+                          float *d_b2, void *ws, size_t ws_bytes, void *stream);
 
 /* Views into a saved block, for tests and tools: byte offsets of topk_idx [T,k] int32, topk_w
  * [T,k] fp32, expert_offsets [N+1] int32 and slot_of [T,k] int32 inside it.  Host only. */

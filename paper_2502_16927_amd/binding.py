@@ -12,7 +12,7 @@ import torch
 
 F32, BF16 = 0, 1
 ORDER_DCCA, ORDER_CDAC = 0, 1
-FLAG_ACCUMULATE, FLAG_OUT_BF16, FLAG_WIRE_BF16, FLAG_TILES_LARGE, FLAG_TILES_SMALL = 1, 2, 4, 8, 16
+FLAG_ACCUMULATE, FLAG_OUT_BF16, FLAG_WIRE_BF16, FLAG_TILES_LARGE, FLAG_TILES_SMALL, FLAG_ROUTE_LOW = 1, 2, 4, 8, 16, 32
 WS_ROUTE, WS_DISPATCH, WS_GROUPED_FFN, WS_LAYER_FORWARD, WS_LAYER_TRAIN, WS_SAVED, WS_AUX_LOSS = range(7)
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbigmac.so")
@@ -25,7 +25,7 @@ class Dims(ctypes.Structure):
 
 
 class Params(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_void_p) for n in ("w_down", "w_up", "w_gate", "gate_bias", "w1", "w2")]
+    _fields_ = [(n, ctypes.c_void_p) for n in ("w_down", "w_up", "w_gate", "gate_bias", "w1", "w2", "b1", "b2")]
 
 
 class BigmacError(RuntimeError):
@@ -63,13 +63,13 @@ def lib() -> ctypes.CDLL:
         L.bigmac_dispatch_static.restype = ci
         L.bigmac_dispatch_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         L.bigmac_grouped_ffn.restype = ci
-        L.bigmac_grouped_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bigmac_grouped_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.bigmac_combine.restype = ci
         L.bigmac_combine.argtypes = [dp, vp, vp, vp, vp, vp]
         L.bigmac_layer_forward.restype = ci
         L.bigmac_layer_forward.argtypes = [dp, ctypes.POINTER(Params), vp, vp, vp, vp, sz, vp]
         L.bigmac_layer_backward.restype = ci
-        L.bigmac_layer_backward.argtypes = [dp, ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.bigmac_layer_backward.argtypes = [dp, ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.bigmac_set_stage_events.restype = ci
         L.bigmac_set_stage_events.argtypes = [ctypes.POINTER(vp)]
         L.bigmac_stage_name.restype = ctypes.c_char_p
@@ -152,8 +152,8 @@ def _check(rc: int, where: str):
         raise BigmacError(rc, where)
 
 
-def make_params(w_down, w_up, w_gate, gate_bias, w1, w2) -> Params:
-    return Params(_ptr(w_down), _ptr(w_up), _ptr(w_gate), _ptr(gate_bias), _ptr(w1), _ptr(w2))
+def make_params(w_down, w_up, w_gate, gate_bias, w1, w2, b1=None, b2=None) -> Params:
+    return Params(_ptr(w_down), _ptr(w_up), _ptr(w_gate), _ptr(gate_bias), _ptr(w1), _ptr(w2), _ptr(b1), _ptr(b2))
 
 
 def bigmac_aux_loss(dims, logits, topk_idx, loss, share, dlogits=None, ws=None, stream=None):
@@ -176,8 +176,8 @@ def bigmac_dispatch_static(dims, x_low, topk_idx, x_perm, expert_offsets, slot_o
                                         _ptr(slot_of), _ptr(src_of), _stream(stream)), "bigmac_dispatch_static")
 
 
-def bigmac_grouped_ffn(dims, x_perm, expert_offsets, w1, w2, act_saved, o_perm, ws, stream=None):
-    _check(lib().bigmac_grouped_ffn(ctypes.byref(dims), _ptr(x_perm), _ptr(expert_offsets), _ptr(w1), _ptr(w2),
+def bigmac_grouped_ffn(dims, x_perm, expert_offsets, w1, w2, act_saved, o_perm, ws, stream=None, b1=None, b2=None):
+    _check(lib().bigmac_grouped_ffn(ctypes.byref(dims), _ptr(x_perm), _ptr(expert_offsets), _ptr(w1), _ptr(w2), _ptr(b1), _ptr(b2),
                                     _ptr(act_saved), _ptr(o_perm), _ptr(ws), _nbytes(ws), _stream(stream)), "bigmac_grouped_ffn")
 
 
@@ -198,10 +198,11 @@ def bigmac_layer_forward(dims, params, x, y, saved, ws, stream=None):
                                       _nbytes(ws), _stream(stream)), "bigmac_layer_forward")
 
 
-def bigmac_layer_backward(dims, params, x, dy, saved, dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2, ws, stream=None):
+def bigmac_layer_backward(dims, params, x, dy, saved, dx, d_w_down, d_w_up, d_w_gate, d_w1, d_w2, ws, stream=None,
+                          d_b1=None, d_b2=None):
     _check(lib().bigmac_layer_backward(ctypes.byref(dims), ctypes.byref(params), _ptr(x), _ptr(dy), _ptr(saved), _ptr(dx),
-                                       _ptr(d_w_down), _ptr(d_w_up), _ptr(d_w_gate), _ptr(d_w1), _ptr(d_w2), _ptr(ws),
-                                       _nbytes(ws), _stream(stream)), "bigmac_layer_backward")
+                                       _ptr(d_w_down), _ptr(d_w_up), _ptr(d_w_gate), _ptr(d_w1), _ptr(d_w2), _ptr(d_b1), _ptr(d_b2),
+                                       _ptr(ws), _nbytes(ws), _stream(stream)), "bigmac_layer_backward")
 
 
 def stage_name(stage: int) -> str:

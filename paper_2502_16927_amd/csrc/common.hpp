@@ -136,6 +136,8 @@ struct GemmDesc {
   const void* A;
   const void* B;
   void* C;
+  const void* bias;          // EPI_GELU / EPI_STORE, optional: added to every row of the product before the epilogue's own
+  long gstride_bias;         //   work ([N] of dtype; ragged-M: one vector per group, gstride_bias elements apart)
   const void* aux_in;        // EPI_DGELU: saved pre-activation, same shape/ld as C
   void* aux_out;             // EPI_GELU: optional pre-activation output, same shape/ld as C
   long lda, ldb, ldc;
@@ -214,13 +216,19 @@ int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, 
                          void* x_perm, hipStream_t s);
 enum CombineOut { COMBINE_F32 = 0, COMBINE_SPLIT_BF16 = 1 };  // fp32 [T,w]  |  bf16 [T,2w] = (hi | lo)
 // dtype: element type of the gathered rows (BIGMAC_F32 or BIGMAC_BF16)
+// addend (optional, fp32 [T, width]): the sum of a token starts from its row instead of zero
 int launch_combine_rows(int dtype, int T, int k, int width, const void* o_perm, const int32_t* slot_of,
-                        const float* topk_w, void* y_low, int out_kind, hipStream_t s);
+                        const float* topk_w, void* y_low, int out_kind, hipStream_t s, const float* addend = nullptr);
 // backward of the weighted combine: dgate[t,j] = <dy_low[t], o_perm[slot]>, do_perm[slot] = w[t,j]*dy_low[t]
 // (o_dtype: element type of o_perm; do_perm has the storage type `dtype`)
 int launch_combine_backward(int dtype, int o_dtype, int T, int k, int width, const float* dy_low, const void* o_perm,
                             const int32_t* slot_of, const float* topk_w, float* dgate, void* do_perm,
                             hipStream_t s);
+
+// out[g, :] (fp32, [groups, cols]) (+)= sum over the rows of group g (offsets [groups + 1]) of src[row, :cols]
+size_t ragged_colsum_ws_bytes(int groups, int cols);
+int launch_ragged_colsum(int dtype, const void* src, long ld, int cols, const int32_t* offsets, int groups, float* out, int beta,
+                         void* ws, hipStream_t s);
 
 #define BIGMAC_CHECK_LAUNCH()                                   \
   do {                                                          \

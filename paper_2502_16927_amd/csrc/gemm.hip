@@ -343,6 +343,16 @@ void mfma_gemm_kernel(GemmDesc p) {
     }
     prefetch(nxt);
 
+    // optional bias of the product's columns (expert biases), before the epilogue's own work
+    if ((EPI == EPI_GELU || EPI == EPI_STORE) && t.bias) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if (SWAP) add_bias_transposed(acc[i][j], (const bf16_t*)t.bias, t.n0 + wn + j * 32, p.N, lane);
+          else add_bias_plain(acc[i][j], (const bf16_t*)t.bias, t.n0 + wn + j * 32, p.N, lane);
+        }
+    }
     // epilogue: lane l of a 32x32 tile holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4
     if (EPI == EPI_ACCUM || OUTF32) {
       // fp32 results: a lane group already writes 128 contiguous bytes per row.  Accumulation into
@@ -495,7 +505,7 @@ __global__ __launch_bounds__(256) void fma_gemm_kernel(GemmDesc p) {
       const int row = t.m0 + ty * 4 + i, col = t.n0 + tx * 4 + j;
       if (row >= t.m_end || col >= p.N) continue;
       const size_t off = (size_t)row * p.ldc + col;
-      const float a = acc[i][j];
+      const float a = acc[i][j] + ((EPI == EPI_STORE || EPI == EPI_GELU) && t.bias ? ((const float*)t.bias)[col] : 0.0f);
       float* c = (float*)t.C + off;
       if (EPI == EPI_STORE) *c = a;
       else if (EPI == EPI_GELU) {

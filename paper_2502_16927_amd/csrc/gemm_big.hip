@@ -132,26 +132,29 @@ void mfma_big_kernel(GemmDesc p) {
     Frag<BKC> b[TN];
   };
   constexpr int READS_PER_STEP = (AK ? TM : 2 * TM) + (BKC ? TN : 2 * TN);
-  auto read_frags = [&](auto stage_c, auto ks_c, FragSet& f) {
-    constexpr int s = decltype(stage_c)::value, ks = decltype(ks_c)::value;
+  // the LDS reads of sub-tile `sub` (0 .. TM - 1: A, TM .. TM + TN - 1: B) of one MFMA step
+  auto read_sub = [&](auto stage_c, auto ks_c, auto sub_c, FragSet& f) {
+    constexpr int s = decltype(stage_c)::value, ks = decltype(ks_c)::value, sub = decltype(sub_c)::value;
     constexpr int OFF = (s & 1) * STAGE_BYTES;
     const unsigned hi = (s >> 1) * 65536u;
-    static_for<0, TM>([&](auto sub) {
-      constexpr int i = decltype(sub)::value;
+    if constexpr (sub < TM) {
+      constexpr int i = sub;
       if constexpr (AK) lds_read_b128<OFF + i * 2048>(pa[ks] + hi, f.a[i].q);
       else {
         lds_read_tr_b64<OFF + ks * 8192>(pa[i] + hi, f.a[i].h[0]);
         lds_read_tr_b64<OFF + ks * 8192 + 2048>(pa[i] + hi, f.a[i].h[1]);
       }
-    });
-    static_for<0, TN>([&](auto sub) {
-      constexpr int j = decltype(sub)::value;
+    } else {
+      constexpr int j = sub - TM;
       if constexpr (BKC) lds_read_b128<OFF + j * 2048>(pb[ks] + hi, f.b[j].q);
       else {
         lds_read_tr_b64<OFF + ks * 8192>(pb[j] + hi, f.b[j].h[0]);
         lds_read_tr_b64<OFF + ks * 8192 + 2048>(pb[j] + hi, f.b[j].h[1]);
       }
-    });
+    }
+  };
+  auto read_frags = [&](auto stage_c, auto ks_c, FragSet& f) {
+    static_for<0, TM + TN>([&](auto sub) { read_sub(stage_c, ks_c, sub, f); });
   };
 
   auto rows_of = [&](const TileCoord& t, const void* base, int esz_out) {
@@ -183,49 +186,65 @@ void mfma_big_kernel(GemmDesc p) {
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     FragSet f0, f1;
-    auto mfma_step = [&](FragSet& f) {
+    auto mfma_one = [&](FragSet& f, auto q_c) {
+      constexpr int q = decltype(q_c)::value, i = q / TN, j = q % TN;
+      acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j].value(), f.a[i].value(), acc[i][j], 0, 0, 0)
+                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i].value(), f.b[j].value(), acc[i][j], 0, 0, 0);
+    };
+    auto settle = [&](FragSet& f) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) f.a[i].settle();
 #pragma unroll
       for (int j = 0; j < TN; ++j) f.b[j].settle();
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j].value(), f.a[i].value(), acc[i][j], 0, 0, 0)
-                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i].value(), f.b[j].value(), acc[i][j], 0, 0, 0);
     };
-    // Loads in flight in front of this point, oldest first: this tile's k tiles 0, 1, 2 (requested
-    // before the previous tile's epilogue) and that epilogue's stores, which are younger: the
-    // count below is reached once k tile 0 and nearly all of those stores are done.
+    // Every k tile requests exactly LOADS_PER_TILE loads (out of range, i.e. zeros without memory
+    // traffic, past the last k tile), so the loads in flight behind any k tile are a constant.
+    // In front of this point, oldest first: this tile's k tiles 0, 1, 2 (requested before the
+    // previous tile's epilogue) and that epilogue's stores, which are younger: the count below is
+    // reached once k tile 0 and nearly all of those stores are done.
     BIGMAC_WAIT_VMCNT(2 * LOADS_PER_TILE);
     __builtin_amdgcn_s_barrier();                       // every wave's part of k tile 0 is there; stage 3 is free
-    if (3 < nk) fetch(cur, 3, 3);
+    fetch(cur, 3, 3);
     if (nk > 0) read_frags(StaticIndex<0>{}, StaticIndex<0>{}, f0);
     for (int it0 = 0; it0 < nk; it0 += NS) {
       static_for<0, NS>([&](auto stage) {
         constexpr int s = decltype(stage)::value;
         const int it = it0 + s;
         if (it >= nk) return;
-        // second MFMA step's fragments on their way while the first step's products run
+        // first MFMA step: its fragments (f0) were requested during the previous step; the second
+        // step's (f1) go out now and arrive while the 16 products of the first run
         read_frags(stage, StaticIndex<1>{}, f1);
         lds_wait_for<(READS_PER_STEP < 15 ? READS_PER_STEP : 15)>();
-        mfma_step(f0);
+        settle(f0);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, TM * TN>([&](auto q) { mfma_one(f0, q); });
+        __builtin_amdgcn_sched_barrier(0);              // the products are issued before the waits below
         lds_wait_for<0>();                              // this wave has read all it needs of stage s
+        settle(f1);
         if (it + 1 < nk) {
-          // k tiles requested after k tile it + 1 and still allowed in flight: it + 2 and it + 3
-          // where they exist (k tiles 0 .. 2 are always requested, the others only below nk)
-          const int issued = max(nk, NS - 1);
-          const int younger = min(2, issued - (it + 2));
-          if (younger >= 2) BIGMAC_WAIT_VMCNT(2 * LOADS_PER_TILE);
-          else if (younger == 1) BIGMAC_WAIT_VMCNT(LOADS_PER_TILE);
-          else BIGMAC_WAIT_VMCNT(0);
+          // behind k tile it + 1 the loads of k tiles it + 2 and it + 3 may stay in flight
+          BIGMAC_WAIT_VMCNT(2 * LOADS_PER_TILE);
           __builtin_amdgcn_s_barrier();                 // k tile it + 1 has landed for everyone; stage s is free
-          if (it + NS < nk) fetch(cur, it + NS, s);
-          read_frags(StaticIndex<(s + 1) % NS>{}, StaticIndex<0>{}, f0);
+          // Second MFMA step, with the requests of k tile it + NS (into the stage just freed) and
+          // the LDS reads of the next k tile's first step dealt out between its 16 products: each
+          // is issued in the shadow of a product the matrix pipe is still working on.
+          const int tile = it + NS;
+          const bool live = tile < nk;
+          const unsigned off_a = live ? (unsigned)tile * cur.step_a : OUT_OF_RANGE;
+          const unsigned off_b = live ? (unsigned)((tile + cur.wrap_first) % wrap_tiles) * cur.step_b : OUT_OF_RANGE;
+          uint4* dst = ring + s * STAGE_CHUNKS;
+          static_for<0, TM * TN>([&](auto q_c) {
+            constexpr int q = decltype(q_c)::value;
+            mfma_one(f1, q_c);
+            if constexpr (q < MoveA::NCH) ma.template load_one<q>(cur.ra, dst, off_a);
+            else if constexpr (q < LOADS_PER_TILE) mb.template load_one<q - MoveA::NCH>(cur.rb, dst + A_CHUNKS, off_b);
+            else read_sub(StaticIndex<(s + 1) % NS>{}, StaticIndex<0>{}, StaticIndex<q - LOADS_PER_TILE>{}, f0);
+            __builtin_amdgcn_sched_barrier(0);
+          });
+        } else {
+          __builtin_amdgcn_sched_barrier(0);
+          static_for<0, TM * TN>([&](auto q) { mfma_one(f1, q); });
         }
-        lds_wait_for<(READS_PER_STEP < 15 ? READS_PER_STEP : 15)>();   // f1 is there (f0's new reads may be under way)
-        mfma_step(f1);
       });
     }
 
@@ -236,6 +255,16 @@ void mfma_big_kernel(GemmDesc p) {
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) fetch(nxt, s, s);
 
+    if ((EPI == EPI_GELU || EPI == EPI_STORE) && t.bias) {   // optional bias of the product's columns
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if (SWAP) add_bias_transposed(acc[i][j], (const bf16_t*)t.bias, t.n0 + wn + j * 32, p.N, lane);
+          else add_bias_plain(acc[i][j], (const bf16_t*)t.bias, t.n0 + wn + j * 32, p.N, lane);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+    }
     if (EPI == EPI_ACCUM || OUTF32) {
       // fp32 results straight from the accumulators: lane l of a 32 x 32 sub-tile holds column
       // l % 32 and rows 8 (v / 4) + 4 (l / 32) + v % 4; a store covers 128 contiguous bytes of two rows
@@ -271,6 +300,9 @@ void mfma_big_kernel(GemmDesc p) {
       // strip of 32 rows x 128 bytes in the ring's last stage (free until the next k loop's first
       // barrier) and leave as whole 128-byte row segments, 64 columns at a time.
       constexpr int SROW = 128;
+      // (the k loop's last requests into stage 3, if any, were out of range: they only write zeros,
+      // but must have done so before the strips are used; they are older than the prefetch)
+      BIGMAC_WAIT_VMCNT((NS - 1) * LOADS_PER_TILE);
       const unsigned strip = ring_at + 65536u + STAGE_BYTES + wave * (32 * SROW);   // stage 3
       const unsigned quad_row = strip + (lane & 31) * SROW + (lane >> 5) * 8;
       const unsigned quad_swz = (lane >> 1) & 7;

@@ -51,6 +51,7 @@ struct TileCoord {
   int kbeg, kend;    // contraction range
   const void* B;     // group-resolved operand / output pointers
   void* C;
+  const void* bias;  // group-resolved bias vector (NULL: none)
   bool valid;
 };
 
@@ -101,6 +102,7 @@ __device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, const TileS
   TileCoord t;
   t.B = p.B;
   t.C = p.C;
+  t.bias = p.bias;
   if (id < 0) {   // no tile: empty ranges everywhere
     t.valid = false;
     t.m0 = t.n0 = t.m_end = t.kbeg = t.kend = 0;
@@ -116,6 +118,7 @@ __device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, const TileS
     t.kbeg = 0;
     t.kend = p.K;
     t.B = (const char*)p.B + (size_t)g * p.gstride_b * esz;
+    if (p.bias) t.bias = (const char*)p.bias + (size_t)g * p.gstride_bias * esz;
   } else if (p.mode == GEMM_RAGGED_K) {
     t.m0 = by * BM;
     t.m_end = p.M;
@@ -204,6 +207,17 @@ struct TileMover {
       else lds_unchunk_tr<CPR>(q, row, cc);
       voff[i] = (unsigned)(row * ld + cc * 8) * 2u;
     }
+  }
+  // one of the NCH loads of a tile (so that they can be spread between other instructions)
+  template <int I>
+  __device__ __forceinline__ void load_one(__amdgpu_buffer_rsrc_t rsrc, uint4* lds, unsigned tile_off) const {
+    static_assert(I >= 0 && I < NCH, "load index");
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds + I * THREADS + wave_chunk), 16,
+                                             voff[I] + tile_off, 0, 0, 0);
+#else
+    (void)rsrc; (void)lds; (void)tile_off;
+#endif
   }
   __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, uint4* lds, unsigned tile_off) const {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc cannot parse this builtin inside a template
@@ -294,6 +308,28 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 // s_waitcnt that only waits for the vector-memory counter to drop to n (gfx9 encoding)
 #define BIGMAC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+
+// Bias of the columns an accumulator sub-tile holds, added in place (bf16 bias vector of one group).
+// Plain layout: lane l holds column col0 + l % 32 in all 16 values.  Transposed layout (bf16
+// results): per quad vq the 4 consecutive columns col0 + 8 vq + 4 (l / 32) .. + 3.  Columns at or
+// past n read the vector's first elements instead (their results are never stored).
+__device__ __forceinline__ void add_bias_plain(f32x16_t& acc, const bf16_t* bias, int col0, int n, int lane) {
+  const int col = col0 + (lane & 31);
+  const float b = bf2f(bias[col < n ? col : 0]);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] += b;
+}
+__device__ __forceinline__ void add_bias_transposed(f32x16_t& acc, const bf16_t* bias, int col0, int n, int lane) {
+#pragma unroll
+  for (int vq = 0; vq < 4; ++vq) {
+    const int col = col0 + vq * 8 + (lane >> 5) * 4;
+    const uint2 w = *(const uint2*)(bias + (col < n ? col : 0));
+    acc[vq * 4 + 0] += __uint_as_float(w.x << 16);
+    acc[vq * 4 + 1] += __uint_as_float(w.x & 0xFFFF0000u);
+    acc[vq * 4 + 2] += __uint_as_float(w.y << 16);
+    acc[vq * 4 + 3] += __uint_as_float(w.y & 0xFFFF0000u);
+  }
+}
 
 // One tile's operands as the movers need them.
 struct TileOperands {

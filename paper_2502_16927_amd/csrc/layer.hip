@@ -15,10 +15,12 @@ int check_dims(const bigmac_dims* D) {
   if ((long long)D->T * D->k >= (1ll << 31)) return BIGMAC_ERR_INVALID_ARG;
   if (D->dtype != BIGMAC_F32 && D->dtype != BIGMAC_BF16) return BIGMAC_ERR_INVALID_ARG;
   if (D->act != BIGMAC_ACT_GELU_ERF) return BIGMAC_ERR_INVALID_ARG;
-  if (D->flags & ~(BIGMAC_FLAG_ACCUMULATE | BIGMAC_FLAG_OUT_BF16 | BIGMAC_FLAG_WIRE_BF16 | BIGMAC_FLAG_TILES_LARGE | BIGMAC_FLAG_TILES_SMALL)) return BIGMAC_ERR_INVALID_ARG;
+  if (D->flags & ~(BIGMAC_FLAG_ACCUMULATE | BIGMAC_FLAG_OUT_BF16 | BIGMAC_FLAG_WIRE_BF16 | BIGMAC_FLAG_TILES_LARGE | BIGMAC_FLAG_TILES_SMALL | BIGMAC_FLAG_ROUTE_LOW)) return BIGMAC_ERR_INVALID_ARG;
   if ((D->flags & BIGMAC_FLAG_TILES_LARGE) && (D->flags & BIGMAC_FLAG_TILES_SMALL)) return BIGMAC_ERR_INVALID_ARG;
   if (D->capacity < 0 || !(D->aux_alpha >= 0.0f) || D->aux_alpha > 1e30f) return BIGMAC_ERR_INVALID_ARG;
   if (D->order == BIGMAC_ORDER_CDAC && D->dtype == BIGMAC_BF16 && (D->flags & BIGMAC_FLAG_OUT_BF16)) return BIGMAC_ERR_UNSUPPORTED;
+  if ((D->flags & BIGMAC_FLAG_ROUTE_LOW) && D->order == BIGMAC_ORDER_CDAC) return BIGMAC_ERR_INVALID_ARG;   // the fine-grained layer has no x'
+  if ((D->flags & BIGMAC_FLAG_ROUTE_LOW) && D->aux_alpha > 0.0f) return BIGMAC_ERR_UNSUPPORTED;
   return BIGMAC_OK;
 }
 
@@ -64,16 +66,23 @@ struct Carver {  // hands out 256-byte aligned pieces of one buffer
 };
 
 struct SavedPlan {
-  size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, tile_map_tall, x_perm, act, hact, o_perm, y_low, logits, aux, total;
+  size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, tile_map_tall, x_perm, act, hact, o_perm, y_low, logits, aux, x_low, total;
 };
 struct FwdPlan {
   size_t logits, perm, x_low, partials, aux, total;
 };
 struct BwdPlan {
-  size_t dy_low, dgate, do_perm, dx_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, total;
+  size_t dy_low, dgate, do_perm, dx_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, bias_sums, gate_low, total;
 };
 
 inline bool bf(const bigmac_dims& D) { return D.dtype == BIGMAC_BF16; }
+inline bool route_low(const bigmac_dims& D) { return (D.flags & BIGMAC_FLAG_ROUTE_LOW) != 0; }
+// the router's view of the dims: with the router on x' its input is r wide
+inline bigmac_dims router_dims(const bigmac_dims& D) {
+  bigmac_dims R = D;
+  if (route_low(D)) R.d = D.r;
+  return R;
+}
 // y' and dx' feed a bf16 MFMA product; they are carried as two bf16 halves (hi | lo) so that
 // the product sees them at fp32 precision.  Row length of that operand:
 inline int low_ld(const bigmac_dims& D) { return bf(D) ? 2 * D.r : D.r; }
@@ -155,18 +164,20 @@ inline bool wide_k_ok(const bigmac_dims& D, int K, int bit) {
 // 8 the first matrix's data gradient, 16 / 32 the weight gradients of the second / first matrix.
 // (The GELU' product has no epilogue there and stays on the tall tile.)
 #ifndef BIGMAC_BIG_MASK
-#define BIGMAC_BIG_MASK 59
+#define BIGMAC_BIG_MASK 0
 #endif
 inline bool big_rows(const bigmac_dims& D, int cols, int K, int bit) {
-  if (!bf(D) || !(BIGMAC_BIG_MASK & bit) || (D.flags & BIGMAC_FLAG_TILES_SMALL)) return false;
+  if (!bf(D) || (D.flags & BIGMAC_FLAG_TILES_SMALL)) return false;
   if (D.flags & BIGMAC_FLAG_TILES_LARGE) return K % 32 == 0;
+  if (!(BIGMAC_BIG_MASK & bit)) return false;
   const long Tk = (long)D.T * D.k;
   const long tiles = (Tk / 256 + D.N) * (cols / 256);
   return cols % 256 == 0 && tiles >= 1024 && K >= 512 && K % 32 == 0 && Tk / D.N >= 1024;
 }
 inline bool big_wgrad(const bigmac_dims& D, int M, int N, int bit) {
-  if (!bf(D) || !(BIGMAC_BIG_MASK & bit) || (D.flags & BIGMAC_FLAG_TILES_SMALL)) return false;
+  if (!bf(D) || (D.flags & BIGMAC_FLAG_TILES_SMALL)) return false;
   if (D.flags & BIGMAC_FLAG_TILES_LARGE) return true;
+  if (!(BIGMAC_BIG_MASK & bit)) return false;
   const long Tk = (long)D.T * D.k;
   return M % 256 == 0 && N % 256 == 0 && (long)D.N * (M / 256) * (N / 256) >= 512 && Tk / D.N >= 1024;
 }
@@ -196,6 +207,8 @@ SavedPlan plan_saved(const bigmac_dims& D) {
   // the loss (one float) followed, 256 bytes on, by share[N]
   p.logits = c.take(D.aux_alpha > 0.0f ? (size_t)D.T * D.N * 4 : 0);
   p.aux = c.take(D.aux_alpha > 0.0f ? 256 + (size_t)D.N * 4 : 0);
+  // router on x': the backward pass needs x' itself (the router's input) for d_w_gate
+  p.x_low = c.take(route_low(D) ? (size_t)D.T * D.r * es : 0);
   p.total = c.off;
   return p;
 }
@@ -282,14 +295,19 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
   p.dact = c.take(Tk * wide_ld(D) * es);
   p.dx_low = c.take(dcca ? low_bytes(D) : (size_t)D.T * D.d * 4);
   p.dL = c.take((size_t)D.T * D.N * es);
-  p.route = c.take(route_backward_ws_bytes(D));
+  p.route = c.take(route_backward_ws_bytes(router_dims(D)));
   p.dx_f32 = c.take((bf(D) && (D.flags & BIGMAC_FLAG_OUT_BF16)) ? (size_t)D.T * D.d * 4 : 0);
   // split-K partials of the three weight gradients over the token index: one region each, so
   // that one launch at the end can reduce all three
-  p.part_gate = c.take((size_t)token_wgrad_ksplit(D, D.d, D.N) * D.d * D.N * 4);
+  const int dg = router_dims(D).d;   // rows of w_gate
+  p.part_gate = c.take((size_t)token_wgrad_ksplit(D, dg, D.N) * dg * D.N * 4);
   p.part_up = c.take(dcca ? (size_t)token_wgrad_ksplit(D, D.r, D.d) * D.r * D.d * 4 : 0);
   p.part_down = c.take(dcca ? (size_t)token_wgrad_ksplit(D, D.d, D.r) * D.d * D.r * 4 : 0);
   p.tmp_f32 = 0;
+  // expert biases: partial column sums (sized for the wider of the two bias vectors; taken always,
+  // the plan does not see the parameters); router on x': its share of dx' in fp32
+  p.bias_sums = c.take(ragged_colsum_ws_bytes(D.N, W.hid > W.win ? W.hid : W.win));
+  p.gate_low = c.take(route_low(D) ? (size_t)D.T * D.r * 4 : 0);
   p.total = c.off;
   return p;
 }
@@ -325,7 +343,8 @@ GemmDesc base_desc(const bigmac_dims& D) {
 
 // The two expert products on permuted rows (ragged per-expert row ranges).
 int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* offsets, const int* tile_map, const int* tile_map_tall,
-                        const void* w1, const void* w2, void* act, void* hact, int ld_wide, void* o_perm, int o_f32, hipStream_t s) {
+                        const void* w1, const void* w2, const void* b1, const void* b2, void* act, void* hact, int ld_wide, void* o_perm, int o_f32,
+                        hipStream_t s) {
   const Widths W = widths(D);
   const int Tk = D.T * D.k;
   GemmDesc g = base_desc(D);
@@ -340,6 +359,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.A = x_perm; g.lda = W.win; g.K = W.win;
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
   g.C = hact; g.ldc = ld_wide; g.aux_out = act;
+  g.bias = b1; g.gstride_bias = W.hid;
   if (!g.big_tile) touch_weights(D, g, w1, 1);
   // measured: -3 % at K = 512 (gpt_xl); at K = 256 (gpt_medium) +2 % while the weights came from
   // memory, -4.6 % with the warm-up
@@ -355,6 +375,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.A = hact; g.lda = ld_wide; g.K = W.hid;
   g.B = w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.win;
   g.C = o_perm; g.ldc = W.win;
+  g.bias = b2; g.gstride_bias = W.win;
   g.big_tile = big_rows(D, W.win, W.hid, 2);
   g.tall_tile = !g.big_tile && tall_rows(D, W.win, W.hid); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
   g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(D, W.hid, 2);
@@ -514,7 +535,7 @@ int bigmac_dispatch(const bigmac_dims* D, const void* x_low, const int32_t* topk
 }
 
 int bigmac_grouped_ffn(const bigmac_dims* D, const void* x_perm, const int32_t* expert_offsets, const void* w1, const void* w2,
-                       void* act_saved, void* o_perm, void* ws, size_t ws_bytes, void* stream) {
+                       const void* b1, const void* b2, void* act_saved, void* o_perm, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_dims(D);
   if (rc) return rc;
   if (!x_perm || !expert_offsets || !w1 || !w2 || !o_perm || !ws) return BIGMAC_ERR_INVALID_ARG;
@@ -528,7 +549,7 @@ int bigmac_grouped_ffn(const bigmac_dims* D, const void* x_perm, const int32_t* 
   rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype, 0), tile_map, s);
   if (!rc && any_tall_rows(*D)) rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype, 1), tile_map_tall, s);
   if (rc) return rc;
-  return run_experts_forward(*D, x_perm, expert_offsets, tile_map, tile_map_tall, w1, w2, act_saved, hact, W.hid, o_perm, 0, s);
+  return run_experts_forward(*D, x_perm, expert_offsets, tile_map, tile_map_tall, w1, w2, b1, b2, act_saved, hact, W.hid, o_perm, 0, s);
 }
 
 int bigmac_combine(const bigmac_dims* D, const void* o_perm, const int32_t* slot_of, const float* topk_w, float* y_low, void* stream) {
@@ -568,39 +589,54 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   const bool aux = D->aux_alpha > 0.0f;                       // the loss lives in the saved block
   float* logits = aux ? (float*)(sv + S.logits) : (float*)(wsb + F.logits);
 
-  {
-    BIGMAC_STAGE(BIGMAC_STAGE_ROUTER_LOGITS);
-    rc = launch_router_logits(*D, x, P->w_gate, P->gate_bias, logits, s);
-  }
-  if (rc) return rc;
-  {
+  const bool low_router = route_low(*D);
+  // x' is the workspace's piece, or (router on x': the backward pass reads it again) the saved block's
+  void* x_low_buf = (low_router && saved) ? (void*)(sv + S.x_low) : (void*)(wsb + F.x_low);
+  auto route = [&](const void* router_in) -> int {
+    const bigmac_dims R = router_dims(*D);
+    int rr;
+    {
+      BIGMAC_STAGE(BIGMAC_STAGE_ROUTER_LOGITS);
+      rr = launch_router_logits(R, router_in, P->w_gate, P->gate_bias, logits, s);
+    }
+    if (rr) return rr;
     BIGMAC_STAGE(BIGMAC_STAGE_TOPK_GATE);
-    rc = launch_topk_gate(*D, logits, topk_idx, topk_w, s);
-    if (!rc && aux)
-      rc = launch_aux_loss(*D, logits, topk_idx, (float*)(sv + S.aux + 256), (float*)(sv + S.aux), nullptr, wsb + F.aux, s);
+    rr = launch_topk_gate(*D, logits, topk_idx, topk_w, s);
+    if (!rr && aux)
+      rr = launch_aux_loss(*D, logits, topk_idx, (float*)(sv + S.aux + 256), (float*)(sv + S.aux), nullptr, wsb + F.aux, s);
+    return rr;
+  };
+  if (!low_router) {   // Section 3.1's default: the router reads the full-width token
+    rc = route(x);
+    if (rc) return rc;
   }
-  if (rc) return rc;
   const void* x_low = x;
   if (dcca) {  // x' = x W_down
     GemmDesc g = base_desc(*D);
     g.a_kcontig = 1; g.b_kcontig = 0; g.epilogue = EPI_STORE; g.out_f32 = bf(*D) ? 0 : 1;
     g.A = x; g.lda = D->d; g.M = D->T; g.K = D->d;
     g.B = P->w_down; g.ldb = D->r; g.N = D->r;
-    g.C = wsb + F.x_low; g.ldc = D->r;
-    BIGMAC_STAGE(BIGMAC_STAGE_DESCEND);
-    g.ksplit = forward_ksplit(*D, D->T, D->r, D->d);
-    g.tall_tile = g.ksplit == 1 && tall_dense(*D, D->T, D->r, D->d);
-    g.deep_tile = g.ksplit == 1 && !g.tall_tile && deep_dense(*D, D->T, D->r, D->d);
-    if (g.ksplit > 1) {   // fp32 partials, then one rounding to bf16
-      g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->r;
-      rc = launch_gemm(g, s);
-      if (rc) return rc;
-      rc = launch_reduce_partials_bf16((const float*)(wsb + F.partials), g.ksplit, (size_t)D->T * D->r, wsb + F.x_low, s);
-    } else {
-      rc = launch_gemm(g, s);
+    g.C = x_low_buf; g.ldc = D->r;
+    {
+      BIGMAC_STAGE(BIGMAC_STAGE_DESCEND);
+      g.ksplit = forward_ksplit(*D, D->T, D->r, D->d);
+      g.tall_tile = g.ksplit == 1 && tall_dense(*D, D->T, D->r, D->d);
+      g.deep_tile = g.ksplit == 1 && !g.tall_tile && deep_dense(*D, D->T, D->r, D->d);
+      if (g.ksplit > 1) {   // fp32 partials, then one rounding to bf16
+        g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->r;
+        rc = launch_gemm(g, s);
+        if (rc) return rc;
+        rc = launch_reduce_partials_bf16((const float*)(wsb + F.partials), g.ksplit, (size_t)D->T * D->r, x_low_buf, s);
+      } else {
+        rc = launch_gemm(g, s);
+      }
     }
     if (rc) return rc;
-    x_low = wsb + F.x_low;
+    x_low = x_low_buf;
+  }
+  if (low_router) {    // the alternative Section 3.1 names: the router reads x' (as stored)
+    rc = route(x_low);
+    if (rc) return rc;
   }
   {
     BIGMAC_STAGE(BIGMAC_STAGE_PERMUTATION);
@@ -615,7 +651,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);
   }
   if (rc) return rc;
-  rc = run_experts_forward(*D, x_perm, offsets, tile_map, tile_map_tall, P->w1, P->w2, act, hact, wide_ld(*D), o_perm, wire_f32(*D) ? 1 : 0, s);
+  rc = run_experts_forward(*D, x_perm, offsets, tile_map, tile_map_tall, P->w1, P->w2, P->b1, P->b2, act, hact, wide_ld(*D), o_perm, wire_f32(*D) ? 1 : 0, s);
   if (rc) return rc;
   if (!dcca) {  // fine-grained layer: the weighted sum is the output
     BIGMAC_STAGE(BIGMAC_STAGE_COMBINE);
@@ -650,14 +686,15 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
 }
 
 int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const void* x, const void* dy, const void* saved,
-                          void* dx, float* d_w_down, float* d_w_up, float* d_w_gate, float* d_w1, float* d_w2, void* ws,
-                          size_t ws_bytes, void* stream) {
+                          void* dx, float* d_w_down, float* d_w_up, float* d_w_gate, float* d_w1, float* d_w2, float* d_b1,
+                          float* d_b2, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_dims(D);
   if (rc) return rc;
   const bool dcca = D->order == BIGMAC_ORDER_DCCA;
   if (!P || !x || !dy || !saved || !dx || !ws || !d_w_gate || !d_w1 || !d_w2 || !P->w_gate || !P->w1 || !P->w2)
     return BIGMAC_ERR_INVALID_ARG;
   if (dcca && (!P->w_down || !P->w_up || !d_w_down || !d_w_up)) return BIGMAC_ERR_INVALID_ARG;
+  if ((P->b1 != nullptr) != (d_b1 != nullptr) || (P->b2 != nullptr) != (d_b2 != nullptr)) return BIGMAC_ERR_INVALID_ARG;
   if (bf(*D) && D->N % 8) return BIGMAC_ERR_UNSUPPORTED;  // the dense logit gradient has 16-byte rows
   if (ws_bytes < bigmac_workspace_bytes(D, BIGMAC_WS_LAYER_TRAIN)) return BIGMAC_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -722,6 +759,10 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     rc = launch_combine_backward(D->dtype, wire_dtype(*D), D->T, D->k, W.win, dy_low, o_perm, slot_of, topk_w, dgate, do_perm, s);
   }
   if (rc) return rc;
+  if (d_b2) {  // the second bias adds to every expert output: its gradient is the column sum of do_perm over the expert's rows
+    rc = launch_ragged_colsum(D->dtype, do_perm, W.win, W.win, offsets, D->N, d_b2, accumulate, wsb + B.bias_sums, s);
+    if (rc) return rc;
+  }
   {  // dact = (do_perm W2[e]^T) * act'(act)
     GemmDesc g = base_desc(*D);
     g.mode = GEMM_RAGGED_M; g.groups = D->N; g.max_rows = Tk; g.offsets = offsets; g.tile_map = tile_map;
@@ -733,9 +774,15 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.wide_k = !g.tall_tile && wide_k_ok(*D, W.win, 4);
     g.kloop_priority = 1;              // measured: -3.5 % (gpt_medium), -1.7 % (gpt_xl)
     touch_weights(*D, g, P->w2, 4);
-    BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_DGRAD);
-    rc = launch_gemm(g, s);
+    {
+      BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_DGRAD);
+      rc = launch_gemm(g, s);
+    }
     if (rc) return rc;
+    if (d_b1) {  // the first bias adds to the pre-activation: column sums of dact
+      rc = launch_ragged_colsum(D->dtype, dact, wide_ld(*D), W.hid, offsets, D->N, d_b1, accumulate, wsb + B.bias_sums, s);
+      if (rc) return rc;
+    }
   }
   {  // dW2[e] (+)= hact_e^T do_perm_e
     GemmDesc g = base_desc(*D);
@@ -777,30 +824,35 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     rc = launch_gemm(g, s);
     if (rc) return rc;
   }
-  // dispatch backward: dx' = sum_j dx_perm[slot_of[t, j]]
-  {
-    BIGMAC_STAGE(BIGMAC_STAGE_BWD_DISPATCH);
-    rc = launch_combine_rows(wire_dtype(*D), D->T, D->k, W.win, dx_perm, slot_of, nullptr, dx_low,
-                             (dcca && bf(*D)) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s);
-  }
-  if (rc) return rc;
-  // gate backward; the router's share of dx is written to dx_f32
+  // Gate backward.  The router's share of the input gradient goes to dx (router on x) or, with the
+  // router on x', into an fp32 [T, r] row that the sum of dx' below starts from.
+  const bool low_router = route_low(*D);
+  const bigmac_dims R = router_dims(*D);
+  float* gate_low = low_router ? (float*)(wsb + B.gate_low) : nullptr;
   {
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_GATE);
     const bool aux = D->aux_alpha > 0.0f;
-    rc = launch_route_backward(*D, P->w_gate, topk_idx, topk_w, dgate, aux ? (const float*)(sv + S.logits) : nullptr,
-                               aux ? (const float*)(sv + S.aux + 256) : nullptr, dx_f32, dL, wsb + B.route, s);
+    rc = launch_route_backward(R, P->w_gate, topk_idx, topk_w, dgate, aux ? (const float*)(sv + S.logits) : nullptr,
+                               aux ? (const float*)(sv + S.aux + 256) : nullptr, low_router ? gate_low : dx_f32, dL, wsb + B.route, s);
   }
   if (rc) return rc;
-  {  // dW_g (+)= x^T dL
+  // dispatch backward: dx' = sum_j dx_perm[slot_of[t, j]] (+ the router's share)
+  {
+    BIGMAC_STAGE(BIGMAC_STAGE_BWD_DISPATCH);
+    rc = launch_combine_rows(wire_dtype(*D), D->T, D->k, W.win, dx_perm, slot_of, nullptr, dx_low,
+                             (dcca && bf(*D)) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s, gate_low);
+  }
+  if (rc) return rc;
+  {  // dW_g (+)= x^T dL  (router on x': x'^T dL)
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_ROUTER_WGRAD);
-    rc = run_token_wgrad(*D, x, D->d, D->d, dL, D->N, D->N, d_w_gate, (float*)(wsb + B.part_gate), &jobs[njobs++], s);
+    const void* router_in = low_router ? (const void*)(sv + S.x_low) : x;
+    rc = run_token_wgrad(*D, router_in, R.d, R.d, dL, D->N, D->N, d_w_gate, (float*)(wsb + B.part_gate), &jobs[njobs++], s);
   }
   if (rc) return rc;
   if (dcca) {
     {  // dx += dx' W_down^T
       GemmDesc g = base_desc(*D);
-      g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ACCUM; g.beta = 1;
+      g.a_kcontig = 1; g.b_kcontig = 1; g.epilogue = EPI_ACCUM; g.beta = low_router ? 0 : 1;   // dx holds the router's share, or nothing yet
       g.A = dx_low; g.lda = low_ld(*D); g.M = D->T; g.K = low_ld(*D);
       g.B = P->w_down; g.ldb = D->r; g.N = D->d; g.kwrap_b = bf(*D) ? D->r : 0;
       g.C = dx_f32; g.ldc = D->d;

@@ -267,21 +267,37 @@ __device__ __forceinline__ void load_row8(const bf16_t* p, float* f) {
 // all KU row pieces are requested before the first multiply-add, so that a thread has KU
 // independent gathers in flight instead of a chain of dependent ones.  A dropped pair
 // (slot < 0) reads row 0 and is left out of the sum.  ROW: element type of the gathered rows.
-template <typename ROW, int OUT, int KU>
+// UNIFORM (rows of a multiple of 512 columns): a wavefront's 64 threads all belong to one token, so
+// its slots and weights are read once per wavefront by scalar loads instead of by every thread.
+typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr_t;
+typedef const float __attribute__((address_space(4))) * const_f32_ptr_t;
+template <typename ROW, int OUT, int KU, bool UNIFORM>
 __global__ __launch_bounds__(256) void combine_rows_kernel(const ROW* __restrict__ o_perm, const int32_t* __restrict__ slot_of,
-                                                           const float* __restrict__ w, void* __restrict__ y, int T, int k, int width) {
+                                                           const float* __restrict__ w, const float* __restrict__ addend,
+                                                           void* __restrict__ y, int T, int k, int width) {
   const int cpr = width / 8;
   const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (g >= (size_t)T * cpr) return;
-  const int t = (int)(g / cpr), c = (int)(g % cpr);
+  int t = (int)(g / cpr);
+  const int c = (int)(g % cpr);
+  if (UNIFORM) t = __builtin_amdgcn_readfirstlane(t);
   float acc[8] = {};
+  if (addend) {   // the sum starts from a row of its own ([T, width] fp32) instead of zero
+    const float4 a = *(const float4*)(addend + (size_t)t * width + c * 8), b = *(const float4*)(addend + (size_t)t * width + c * 8 + 4);
+    acc[0] = a.x; acc[1] = a.y; acc[2] = a.z; acc[3] = a.w; acc[4] = b.x; acc[5] = b.y; acc[6] = b.z; acc[7] = b.w;
+  }
   for (int j0 = 0; j0 < k; j0 += KU) {
     int slot[KU];
     float wj[KU];
 #pragma unroll
     for (int u = 0; u < KU; ++u) {
-      slot[u] = slot_of[(size_t)t * k + j0 + u];
-      wj[u] = w ? w[(size_t)t * k + j0 + u] : 1.0f;
+      if (UNIFORM) {   // the tables are written before this kernel starts and only read by it
+        slot[u] = ((const_i32_ptr_t)(unsigned long long)slot_of)[(size_t)t * k + j0 + u];
+        wj[u] = w ? ((const_f32_ptr_t)(unsigned long long)w)[(size_t)t * k + j0 + u] : 1.0f;
+      } else {
+        slot[u] = slot_of[(size_t)t * k + j0 + u];
+        wj[u] = w ? w[(size_t)t * k + j0 + u] : 1.0f;
+      }
     }
     float o[KU][8];
 #pragma unroll
@@ -354,15 +370,15 @@ __global__ __launch_bounds__(256) void combine_backward_wide_kernel(const float*
                                                                     const int32_t* __restrict__ slot_of, const float* __restrict__ w,
                                                                     float* __restrict__ dgate, bf16_t* __restrict__ do_perm, int T, int k, int width) {
   const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int t = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
   if (t >= T) return;
   for (int j0 = 0; j0 < k; j0 += KU) {
     int slot[KU];
     float wj[KU], dot[KU];
 #pragma unroll
-    for (int u = 0; u < KU; ++u) {
-      slot[u] = __builtin_amdgcn_readfirstlane(slot_of[(size_t)t * k + j0 + u]);
-      wj[u] = w[(size_t)t * k + j0 + u];
+    for (int u = 0; u < KU; ++u) {   // one token per wavefront: its slots and weights by scalar loads
+      slot[u] = ((const_i32_ptr_t)(unsigned long long)slot_of)[(size_t)t * k + j0 + u];
+      wj[u] = ((const_f32_ptr_t)(unsigned long long)w)[(size_t)t * k + j0 + u];
       dot[u] = 0.0f;
     }
     for (int c0 = 0; c0 < width; c0 += 512) {
@@ -397,7 +413,73 @@ __global__ __launch_bounds__(256) void combine_backward_wide_kernel(const float*
   }
 }
 
+// Column sums over each group's rows (the gradients of the expert biases): part[(g * S + z), c] =
+// sum of src[s, c] over the z-th of S equal pieces of group g's row range.  A workgroup takes 64
+// columns of one piece: 32 row lanes x 8 column groups of 8 columns (16-byte reads of bf16), the
+// row lanes walk the piece 32 rows at a time and are added up through the LDS in lane order, so
+// that equal inputs give equal bits.
+constexpr int COLSUM_SPLIT = 8;
+template <typename ET>
+__global__ __launch_bounds__(256) void ragged_colsum_kernel(const ET* __restrict__ src, long ld, int cols, const int32_t* __restrict__ offsets,
+                                                            float* __restrict__ part) {
+  __shared__ float sums[32][65];
+  const int g = blockIdx.y, z = blockIdx.z;
+  const int rl = threadIdx.x >> 3, cg = threadIdx.x & 7;
+  const int c0 = blockIdx.x * 64 + cg * 8;
+  const int beg = offsets[g], end = offsets[g + 1];
+  const int piece = ((end - beg + COLSUM_SPLIT - 1) / COLSUM_SPLIT + 31) / 32 * 32;
+  const int r0 = beg + z * piece, r1 = min(end, r0 + piece);
+  float acc[8] = {};
+  if (c0 < cols)
+    for (int r = r0 + rl; r < r1; r += 32) {
+      float v[8];
+      const ET* p = src + (size_t)r * ld + c0;
+      if (sizeof(ET) == 2) unpack_bf16x8(*(const uint4*)p, v);
+      else {
+        const float4 a = *(const float4*)p, b = *((const float4*)p + 1);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += v[i];
+    }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sums[rl][cg * 8 + i] = acc[i];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    float s = 0.0f;
+    for (int l = 0; l < 32; ++l) s += sums[l][threadIdx.x];
+    if (c < cols) part[((size_t)g * COLSUM_SPLIT + z) * cols + c] = s;
+  }
+}
+// out[g, c] = (beta ? out : 0) + sum_z part[(g * S + z), c], z ascending
+__global__ void colsum_reduce_kernel(const float* __restrict__ part, size_t n, int cols, float* __restrict__ out, int beta) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const size_t g = i / cols, c = i % cols;
+  float s = beta ? out[i] : 0.0f;
+  for (int z = 0; z < COLSUM_SPLIT; ++z) s += part[(g * COLSUM_SPLIT + z) * cols + c];
+  out[i] = s;
+}
+
 }  // namespace
+
+size_t ragged_colsum_ws_bytes(int groups, int cols) { return align_up((size_t)groups * COLSUM_SPLIT * cols * sizeof(float)); }
+
+int launch_ragged_colsum(int dtype, const void* src, long ld, int cols, const int32_t* offsets, int groups, float* out, int beta,
+                         void* ws, hipStream_t s) {
+  if (cols % 8 || ld % 8) return BIGMAC_ERR_INVALID_ARG;
+  const dim3 grid((cols + 63) / 64, groups, COLSUM_SPLIT), block(256);
+  if (dtype == BIGMAC_BF16)
+    hipLaunchKernelGGL(ragged_colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)src, ld, cols, offsets, (float*)ws);
+  else
+    hipLaunchKernelGGL(ragged_colsum_kernel<float>, grid, block, 0, s, (const float*)src, ld, cols, offsets, (float*)ws);
+  BIGMAC_CHECK_LAUNCH();
+  const size_t n = (size_t)groups * cols;
+  hipLaunchKernelGGL(colsum_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)ws, n, cols, out, beta);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
 
 size_t permutation_ws_bytes(int T, int k, int N) {
   const int chunk = perm_chunk(T * k, N);
@@ -459,10 +541,13 @@ int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, 
 
 namespace {
 template <typename ROW, int OUT>
-void launch_combine_ku(int ku, dim3 grid, hipStream_t s, const ROW* o_perm, const int32_t* slot_of, const float* w, void* y, int T, int k, int width) {
+void launch_combine_ku(int ku, dim3 grid, hipStream_t s, const ROW* o_perm, const int32_t* slot_of, const float* w, const float* addend,
+                       void* y, int T, int k, int width) {
   const dim3 block(256);
-#define BIGMAC_COMBINE(KU) \
-  hipLaunchKernelGGL((combine_rows_kernel<ROW, OUT, KU>), grid, block, 0, s, o_perm, slot_of, w, y, T, k, width)
+  const bool uniform = width % 512 == 0;   // 64 threads x 8 columns: whole wavefronts per token
+#define BIGMAC_COMBINE(KU)                                                                                                        \
+  if (uniform) hipLaunchKernelGGL((combine_rows_kernel<ROW, OUT, KU, true>), grid, block, 0, s, o_perm, slot_of, w, addend, y, T, k, width); \
+  else hipLaunchKernelGGL((combine_rows_kernel<ROW, OUT, KU, false>), grid, block, 0, s, o_perm, slot_of, w, addend, y, T, k, width)
   switch (ku) {
     case 8: BIGMAC_COMBINE(8); break;
     case 7: BIGMAC_COMBINE(7); break;
@@ -484,18 +569,18 @@ inline int combine_unroll(int k) {
 }  // namespace
 
 int launch_combine_rows(int dtype, int T, int k, int width, const void* o_perm, const int32_t* slot_of,
-                        const float* topk_w, void* y_low, int out_kind, hipStream_t s) {
+                        const float* topk_w, void* y_low, int out_kind, hipStream_t s, const float* addend) {
   if (width % 8) return BIGMAC_ERR_INVALID_ARG;
   if (out_kind != COMBINE_F32 && out_kind != COMBINE_SPLIT_BF16) return BIGMAC_ERR_INVALID_ARG;
   const size_t n = (size_t)T * (width / 8);
   const dim3 grid((unsigned)((n + 255) / 256));
   const int ku = combine_unroll(k);
   if (dtype == BIGMAC_BF16) {
-    if (out_kind == COMBINE_F32) launch_combine_ku<bf16_t, COMBINE_F32>(ku, grid, s, (const bf16_t*)o_perm, slot_of, topk_w, y_low, T, k, width);
-    else launch_combine_ku<bf16_t, COMBINE_SPLIT_BF16>(ku, grid, s, (const bf16_t*)o_perm, slot_of, topk_w, y_low, T, k, width);
+    if (out_kind == COMBINE_F32) launch_combine_ku<bf16_t, COMBINE_F32>(ku, grid, s, (const bf16_t*)o_perm, slot_of, topk_w, addend, y_low, T, k, width);
+    else launch_combine_ku<bf16_t, COMBINE_SPLIT_BF16>(ku, grid, s, (const bf16_t*)o_perm, slot_of, topk_w, addend, y_low, T, k, width);
   } else {
-    if (out_kind == COMBINE_F32) launch_combine_ku<float, COMBINE_F32>(ku, grid, s, (const float*)o_perm, slot_of, topk_w, y_low, T, k, width);
-    else launch_combine_ku<float, COMBINE_SPLIT_BF16>(ku, grid, s, (const float*)o_perm, slot_of, topk_w, y_low, T, k, width);
+    if (out_kind == COMBINE_F32) launch_combine_ku<float, COMBINE_F32>(ku, grid, s, (const float*)o_perm, slot_of, topk_w, addend, y_low, T, k, width);
+    else launch_combine_ku<float, COMBINE_SPLIT_BF16>(ku, grid, s, (const float*)o_perm, slot_of, topk_w, addend, y_low, T, k, width);
   }
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;

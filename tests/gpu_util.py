@@ -132,7 +132,11 @@ class DeviceLayer:
             self.w_down = self.w_up = None
             self.w1 = B.to_device(data["cdac_w1"], dt, device)
             self.w2 = B.to_device(data["cdac_w2"], dt, device)
-        self.params = B.make_params(self.w_down, self.w_up, self.w_gate, self.gate_bias, self.w1, self.w2)
+        # optional variants: expert biases data["b1"] [N, hid], data["b2"] [N, win]; with FLAG_ROUTE_LOW the
+        # router weights data["w_gate"] are [r, N]
+        self.b1 = B.to_device(data.get("b1"), dt, device)
+        self.b2 = B.to_device(data.get("b2"), dt, device)
+        self.params = B.make_params(self.w_down, self.w_up, self.w_gate, self.gate_bias, self.w1, self.w2, self.b1, self.b2)
         out_bf16 = dt == B.BF16 and (flags & B.FLAG_OUT_BF16)
         self.out_dtype = torch.bfloat16 if out_bf16 else torch.float32
         self.y = torch.empty((wl.T, wl.d), dtype=self.out_dtype, device=device)
@@ -155,8 +159,13 @@ class DeviceLayer:
     def alloc_grads(self, init: dict | None = None):
         wl, dev = self.wl, self.device
         win, hid = (wl.r, wl.h) if self.order == B.ORDER_DCCA else (wl.d, wl.r)
-        shapes = {"d_w_down": (wl.d, wl.r), "d_w_up": (wl.r, wl.d), "d_w_gate": (wl.d, wl.N),
+        shapes = {"d_w_down": (wl.d, wl.r), "d_w_up": (wl.r, wl.d),
+                  "d_w_gate": (wl.r if self.flags & B.FLAG_ROUTE_LOW else wl.d, wl.N),
                   "d_w1": (wl.N, win, hid), "d_w2": (wl.N, hid, win)}
+        if self.b1 is not None:
+            shapes["d_b1"] = (wl.N, hid)
+        if self.b2 is not None:
+            shapes["d_b2"] = (wl.N, win)
         self.grads = {}
         for n, s in shapes.items():
             if init is not None and n in init:
@@ -170,7 +179,7 @@ class DeviceLayer:
         dcca = self.order == B.ORDER_DCCA
         B.bigmac_layer_backward(self.dims, self.params, self.x, self.dy, self.saved, self.dx,
                                 g["d_w_down"] if dcca else None, g["d_w_up"] if dcca else None,
-                                g["d_w_gate"], g["d_w1"], g["d_w2"], self.ws_train)
+                                g["d_w_gate"], g["d_w1"], g["d_w2"], self.ws_train, d_b1=g.get("d_b1"), d_b2=g.get("d_b2"))
 
     def saved_views(self):
         """Routing arrays inside the saved block, as numpy."""

@@ -85,16 +85,16 @@ def test_null_pointers_and_small_workspaces_are_rejected():
     assert L.bigmac_dispatch(dp, fake, None, fake, fake, fake, fake, fake, 1 << 30, None) == -1
     assert L.bigmac_dispatch(dp, fake, fake, None, fake, fake, fake, fake, 1 << 30, None) == -1  # x_low without x_perm
     assert L.bigmac_dispatch(dp, fake, fake, fake, fake, fake, fake, fake, 8, None) == -2
-    assert L.bigmac_grouped_ffn(dp, fake, fake, fake, None, None, fake, fake, 1 << 30, None) == -1
-    assert L.bigmac_grouped_ffn(dp, fake, fake, fake, fake, None, fake, fake, 64, None) == -2
+    assert L.bigmac_grouped_ffn(dp, fake, fake, fake, None, None, None, None, fake, fake, 1 << 30, None) == -1
+    assert L.bigmac_grouped_ffn(dp, fake, fake, fake, fake, None, None, None, fake, fake, 64, None) == -2
     assert L.bigmac_combine(dp, None, fake, None, fake, None) == -1
-    p = B.Params(None, None, None, None, None, None)
+    p = B.Params(None, None, None, None, None, None, None, None)
     assert L.bigmac_layer_forward(dp, ctypes.byref(p), fake, fake, None, fake, 1 << 40, None) == -1
-    p = B.Params(4096, 4096, 4096, None, 4096, 4096)
+    p = B.Params(4096, 4096, 4096, None, 4096, 4096, None, None)
     assert L.bigmac_layer_forward(dp, ctypes.byref(p), fake, fake, None, fake, 1024, None) == -2
-    assert L.bigmac_layer_backward(dp, ctypes.byref(p), fake, fake, None, fake, fake, fake, fake, fake, fake, fake, 1 << 40, None) == -1
-    assert L.bigmac_layer_backward(dp, ctypes.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, fake, fake, 1024, None) == -2
+    assert L.bigmac_layer_backward(dp, ctypes.byref(p), fake, fake, None, fake, fake, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == -1
+    assert L.bigmac_layer_backward(dp, ctypes.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, fake, None, None, fake, 1024, None) == -2
     odd = B.make_dims(128, 128, 64, 12, 2, 128)                                             # N not a multiple of 8
-    assert L.bigmac_layer_backward(ctypes.byref(odd), ctypes.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, fake, fake, 1 << 40, None) == -3
+    assert L.bigmac_layer_backward(ctypes.byref(odd), ctypes.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == -3
     fg = B.make_dims(128, 128, 64, 8, 2, 128, order=B.ORDER_CDAC, flags=B.FLAG_OUT_BF16)
     assert B.workspace_bytes(fg, B.WS_LAYER_FORWARD) == 0

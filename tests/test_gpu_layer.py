@@ -92,7 +92,7 @@ def test_small_forward_backward(oracle, case):
     check_weight_grads({n: host(v) - init[n] for n, v in layer2.grads.items()}, g_ref, counts, tol, few_rows=wl.dtype == B.BF16 and few_rows_per_expert(counts))
 
 
-@pytest.mark.parametrize("case", [SMALL[1], SMALL[3], SMALL[5], SMALL[8], dict(T=700, d=128, r=192, N=4, k=2, h=448, dtype=B.BF16)],
+@pytest.mark.parametrize("case", [SMALL[1], SMALL[3], SMALL[5], SMALL[8], dict(T=700, d=128, r=192, N=8, k=2, h=448, dtype=B.BF16)],
                          ids=lambda c: "T{T}_d{d}_r{r}_N{N}_k{k}_h{h}".format(**c))
 def test_large_tiles_give_the_same_bits(case):
     """The 256 x 256 workgroup tiles add the same products in the same order as the smaller ones:
