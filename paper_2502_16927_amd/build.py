@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libbigmac.so")
-SOURCES = ["gemm.hip", "gemm_big.hip", "route.hip", "permute.hip", "layer.hip"]
+SOURCES = ["gemm.hip", "route.hip", "permute.hip", "layer.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          # hipcc must not form packed fp32 instructions on its own
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -154,16 +154,25 @@ struct GemmDesc {
   int wide_k;                // bf16, k-contiguous A, K % 64 == 0: the square tile with 64-deep k tiles, two ring stages
   int kloop_priority;        // MFMA kernels: raise the wave priority inside the k loop (see the kernel)
   int deep_tile;             // bf16, dense, store or accumulate (K % 64 == 0 with a k-contiguous operand): 128 x 64 outputs, 64-deep k tiles
-  int big_tile;              // bf16, no GELU' epilogue: 256 x 256 outputs, one workgroup per CU (gemm_big.hip; ragged-M: tile map of 256-row tiles)
+  int big_tile;              // bf16: 256 x 256 outputs by eight wavefronts, one workgroup per CU (ragged-M: tile map of 256-row tiles)
+  unsigned* claim;           // MFMA kernels, optional: zeroed tile counters of this launch (ClaimScope hands them out; see tile order in gemm_core.hpp)
   const void* touch;         // MFMA kernels, optional: a region (device) every line of which is read once as the kernel starts,
   size_t touch_bytes;        //   so that its first use in a k loop meets the caches and not the memory (0 = off)
+};
+// Tile counters for the MFMA kernels' dynamic tile order: one slot per launch, one counter per XCD
+// (64 bytes apart).  An entry point opens a scope over a piece of its workspace; the scope clears
+// the piece with a fill kernel on the stream, and every launch_gemm of this thread inside the scope
+// takes the next slot (launches beyond the last slot run in the static order).
+constexpr int CLAIM_SLOTS = 48, CLAIM_SLOT_INTS = 8 * 16;
+constexpr size_t CLAIM_BYTES = (size_t)CLAIM_SLOTS * CLAIM_SLOT_INTS * 4;
+struct ClaimScope {
+  ClaimScope(void* region, hipStream_t s);
+  ~ClaimScope();
+  int status;   // BIGMAC_OK, or the fill kernel's launch error
 };
 // Rows per M tile of the ragged-M schedule for this dtype (the tile map must be built with it).
 int gemm_ragged_tile_rows(int dtype, int tall_tile);
 int launch_gemm(const GemmDesc& g, hipStream_t s);
-// the 256 x 256 tile kernel (launch_gemm hands products with big_tile set to it)
-bool gemm_big_supported(const GemmDesc& g);
-int launch_gemm_big(const GemmDesc& g, hipStream_t s);
 // tile_map capacity in int32 for a ragged-M problem
 inline size_t tile_map_ints(int total_rows, int groups, int tile_rows) {
   return 16 + 2 * ((size_t)total_rows / tile_rows + groups + 1);

@@ -5,7 +5,8 @@
 // in the same orientation they have in memory (so global reads are row-contiguous for every
 // transposition) with XOR swizzles against bank conflicts; operands whose contraction index is
 // not the fast one in memory are fetched with the gfx950 LDS transpose read (ds_read_b64_tr_b16).
-// Two workgroup tiles, 128 x 128 and 256 x 128, the latter for products with many tiles and a long K.
+// Three workgroup tiles: 128 x 128; 256 x 128 for products with many tiles and a long K; 256 x 256
+// (eight wavefronts, one workgroup per CU) for the per-expert row products with K of 2048 and more.
 // fp32 storage: a plain tiled FMA kernel (only the tiny fp32 workload uses it).
 #include "gemm_core.hpp"
 
@@ -21,7 +22,7 @@ namespace bigmac {
 // counter waits below and the compiler's own ones are derived from.
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32, int NS = BIGMAC_TILE_STAGES>
 __global__ __launch_bounds__(64 * WAVES_M* WAVES_N)
-    __attribute__((amdgpu_waves_per_eu(BM > BIGMAC_TILE_BM || BK > BIGMAC_TILE_BK ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU)))
+    __attribute__((amdgpu_waves_per_eu(BM > BIGMAC_TILE_BM || BK > BIGMAC_TILE_BK ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU)))   // (eight wavefronts, one block per CU: also 2)
 void mfma_gemm_kernel(GemmDesc p) {
   constexpr int THREADS = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -37,7 +38,10 @@ void mfma_gemm_kernel(GemmDesc p) {
   // the counter waits written out below.
   constexpr int STAGE_CHUNKS = A_CHUNKS + B_CHUNKS;
   constexpr int STAGE_BYTES = STAGE_CHUNKS * 16;
-  static_assert((NS - 1) * STAGE_BYTES + 8192 <= 65536, "fragment reads address the ring through 16-bit instruction offsets");
+  // Fragment reads address a stage through the 16-bit instruction offset where the whole ring is
+  // within its reach; in a larger ring the stage's start is added to the address register instead.
+  constexpr bool NEAR_RING = (NS - 1) * STAGE_BYTES + 8192 <= 65536;
+  static_assert(NEAR_RING || STAGE_BYTES + 8192 <= 65536, "a stage must be within reach of the instruction offset");
   __shared__ uint4 ring[NS * STAGE_CHUNKS];
   const unsigned ring_at = lds_address(ring);
   constexpr unsigned OUT_OF_RANGE = 0x80000000u;
@@ -215,6 +219,15 @@ void mfma_gemm_kernel(GemmDesc p) {
   TileOperands cur = operands(id);
   prefetch(cur);
   request_aux(cur.t, 0);
+  // Tile order (see TileClaim): the first tile is this workgroup's slot, every later one is claimed.
+  __shared__ int claim_box;
+  TileClaim claim(p.claim, stride, &claim_box);
+  claim.request();
+  claim.publish();
+  // the tile after this one is resolved (its table entries read) a whole k loop ahead of its use
+  pos = claim.next(pos);
+  int nid = tile_at(ts, pos);
+  TileOperands nxt = operands(nid);
 
   while (true) {
     const TileCoord t = cur.t;
@@ -252,22 +265,24 @@ void mfma_gemm_kernel(GemmDesc p) {
         // soon as its fragments are there, while those of the later steps are still arriving
         Frag<AK> fa[KS][TM];
         Frag<BKC> fb[KS][TN];
+        constexpr int S_IMM = NEAR_RING ? s * STAGE_BYTES : 0;
+        constexpr unsigned S_REG = NEAR_RING ? 0u : (unsigned)(s * STAGE_BYTES);
         static_for<0, KS>([&](auto kstep) {
           constexpr int ks = decltype(kstep)::value;
           static_for<0, TM>([&](auto sub) {
             constexpr int i = decltype(sub)::value;
-            if constexpr (AK) lds_read_b128<s * STAGE_BYTES + i * 32 * (BK / 8) * 16>(pa[ks][0][0], fa[ks][i].q);
+            if constexpr (AK) lds_read_b128<S_IMM + i * 32 * (BK / 8) * 16>(pa[ks][0][0] + S_REG, fa[ks][i].q);
             else {
-              lds_read_tr_b64<s * STAGE_BYTES>(pa[ks][0][i], fa[ks][i].h[0]);
-              lds_read_tr_b64<s * STAGE_BYTES>(pa[ks][1][i], fa[ks][i].h[1]);
+              lds_read_tr_b64<S_IMM>(pa[ks][0][i] + S_REG, fa[ks][i].h[0]);
+              lds_read_tr_b64<S_IMM>(pa[ks][1][i] + S_REG, fa[ks][i].h[1]);
             }
           });
           static_for<0, TN>([&](auto sub) {
             constexpr int j = decltype(sub)::value;
-            if constexpr (BKC) lds_read_b128<s * STAGE_BYTES + j * 32 * (BK / 8) * 16>(pb[ks][0][0], fb[ks][j].q);
+            if constexpr (BKC) lds_read_b128<S_IMM + j * 32 * (BK / 8) * 16>(pb[ks][0][0] + S_REG, fb[ks][j].q);
             else {
-              lds_read_tr_b64<s * STAGE_BYTES>(pb[ks][0][j], fb[ks][j].h[0]);
-              lds_read_tr_b64<s * STAGE_BYTES>(pb[ks][1][j], fb[ks][j].h[1]);
+              lds_read_tr_b64<S_IMM>(pb[ks][0][j] + S_REG, fb[ks][j].h[0]);
+              lds_read_tr_b64<S_IMM>(pb[ks][1][j] + S_REG, fb[ks][j].h[1]);
             }
           });
         });
@@ -296,10 +311,8 @@ void mfma_gemm_kernel(GemmDesc p) {
 
     // Once every wave has left the k loop the ring is free, and nothing is in flight into its
     // last stage (the last k step waited for everything that was requested into it).
-    pos += stride;
-    id = tile_at(ts, pos);
-    const TileOperands nxt = operands(id);
     __builtin_amdgcn_s_barrier();
+    claim.request();                                     // (everyone has read the box)
     // bf16 epilogue staging, in the ring's last stage: the prefetch below fills stages
     // 0 .. NS - 2, and the last stage is requested again only behind the first barrier of the next
     // k loop.  A staged row is 128 bytes = 8 chunks of 16; chunk c of row r sits at position
@@ -447,8 +460,13 @@ void mfma_gemm_kernel(GemmDesc p) {
     }
     BIGMAC_TRACE_AT(cur_id, 3);
     BIGMAC_TRACE_AT(cur_id, 4);
-    if (id < 0) break;
+    if (nid < 0) break;
+    claim.publish();
     cur = nxt;
+    id = nid;
+    pos = claim.next(pos);
+    nid = tile_at(ts, pos);
+    nxt = operands(nid);
   }
 }
 
@@ -613,14 +631,14 @@ namespace {
 // One-dimensional launch, a multiple of the 8 XCDs.  `persistent`: at most two workgroups per CU
 // (256 CUs), each walking several tiles; otherwise one workgroup per tile (surplus ones exit).
 template <int BM, int BN>
-dim3 grid_for(const GemmDesc& g, bool persistent) {
+dim3 grid_for(const GemmDesc& g, bool persistent, int blocks_per_cu = 0) {
   long gx = (g.N + BN - 1) / BN, gy, gz = 1;
   if (g.mode == GEMM_RAGGED_M) gy = g.max_rows / BM + g.groups + 1;
   else gy = (g.M + BM - 1) / BM;
   if (g.mode == GEMM_RAGGED_K) gz = g.groups;
   if (g.mode == GEMM_DENSE) gz = g.ksplit;
   long blocks = (gx * gy * gz + 7) / 8 * 8;
-  const long resident = 256 * (BM > BIGMAC_TILE_BM ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU);
+  const long resident = 256 * (blocks_per_cu ? blocks_per_cu : BM > BIGMAC_TILE_BM ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU);
   if (persistent && blocks > resident) blocks = resident;
   return dim3((unsigned)blocks, 1, 1);
 }
@@ -642,6 +660,30 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
     default: return BIGMAC_ERR_INVALID_ARG;
   }
 #undef BIGMAC_MFMA
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
+// 256 x 256 outputs by eight wavefronts (each 128 x 64, as in the tall tile), one workgroup per
+// CU, 32-deep k tiles in a ring of four 32 KB stages.  Per flop it asks the L2 for two thirds of
+// the operand bytes the tall tile does (see the comment at launch_gemm).
+template <bool AK, bool BKC>
+int launch_mfma_wide(const GemmDesc& g, hipStream_t s) {
+  constexpr int BM = 256, BN = 256, BK = 32;
+  dim3 grid = grid_for<BM, BN>(g, true, 1), block(512);
+#define BIGMAC_MFMA_WIDE(EPI, OUTF32) \
+  hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 2, 4, AK, BKC, EPI, OUTF32, 4>), grid, block, 0, s, g)
+  switch (g.epilogue) {
+    case EPI_STORE:
+      if (g.out_f32) BIGMAC_MFMA_WIDE(EPI_STORE, true);
+      else BIGMAC_MFMA_WIDE(EPI_STORE, false);
+      break;
+    case EPI_GELU: BIGMAC_MFMA_WIDE(EPI_GELU, false); break;
+    case EPI_DGELU: BIGMAC_MFMA_WIDE(EPI_DGELU, false); break;
+    case EPI_ACCUM: BIGMAC_MFMA_WIDE(EPI_ACCUM, true); break;
+    default: return BIGMAC_ERR_INVALID_ARG;
+  }
+#undef BIGMAC_MFMA_WIDE
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
 }
@@ -741,7 +783,30 @@ double launch_mfma_probe(int blocks, int iters, float* sink, hipStream_t s) {
   return (double)blocks * 4 * iters * 16 * (2.0 * 32 * 32 * 16);
 }
 
-int launch_gemm(const GemmDesc& g, hipStream_t s) {
+namespace {
+struct ClaimPool { unsigned* base; int next; };
+thread_local ClaimPool claim_pool = {nullptr, 0};
+__global__ void clear_claims_kernel(unsigned* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+}  // namespace
+ClaimScope::ClaimScope(void* region, hipStream_t s) {
+  const int n = CLAIM_SLOTS * CLAIM_SLOT_INTS;
+  hipLaunchKernelGGL(clear_claims_kernel, dim3((n + 255) / 256), dim3(256), 0, s, (unsigned*)region, n);
+  status = hipGetLastError() == hipSuccess ? BIGMAC_OK : BIGMAC_ERR_HIP;
+  claim_pool = {status == BIGMAC_OK ? (unsigned*)region : nullptr, 0};
+}
+ClaimScope::~ClaimScope() { claim_pool = {nullptr, 0}; }
+
+int launch_gemm(const GemmDesc& desc, hipStream_t s) {
+  GemmDesc g = desc;
+  // The claimed order for the ragged-M products only.  Measured on zipf_stress: the four per-expert
+  // row products 13-19 % faster with it; the ragged-K weight gradients 40 % slower (the tiles of a
+  // group all cost the same, and with the fixed stride every workgroup of an XCD is on the same
+  // group and k range at once, which the claimed order breaks up); dense products level or 1-3 % slower.
+  if (!g.claim && g.dtype == BIGMAC_BF16 && g.mode == GEMM_RAGGED_M && claim_pool.base && claim_pool.next < CLAIM_SLOTS)
+    g.claim = claim_pool.base + (size_t)CLAIM_SLOT_INTS * claim_pool.next++;
   // host-side shape checks: the kernels move 16-byte chunks and 64-wide k tiles
   if (g.N <= 0 || (g.mode != GEMM_RAGGED_M && g.M <= 0) || (g.mode != GEMM_RAGGED_K && g.K <= 0)) return BIGMAC_ERR_INVALID_ARG;
   if (g.mode != GEMM_DENSE && (!g.offsets || g.groups <= 0)) return BIGMAC_ERR_INVALID_ARG;
@@ -756,7 +821,15 @@ int launch_gemm(const GemmDesc& g, hipStream_t s) {
   }
   if (g.mode == GEMM_DENSE && g.ksplit < 1) return BIGMAC_ERR_INVALID_ARG;
   const int combo = g.a_kcontig * 2 + g.b_kcontig;
-  if (g.big_tile) return launch_gemm_big(g, s);
+  if (g.big_tile) {
+    if (g.dtype != BIGMAC_BF16 || g.tall_tile || g.wide_k || g.deep_tile || g.touch_bytes) return BIGMAC_ERR_INVALID_ARG;
+    switch (combo) {
+      case 2: return launch_mfma_wide<true, false>(g, s);
+      case 3: return launch_mfma_wide<true, true>(g, s);
+      case 0: return launch_mfma_wide<false, false>(g, s);
+      default: return BIGMAC_ERR_UNSUPPORTED;
+    }
+  }
   if (g.dtype == BIGMAC_BF16) {
     if (g.wide_k) {
       if (g.mode == GEMM_RAGGED_K || g.tall_tile || g.deep_tile || !g.a_kcontig || g.K % 64) return BIGMAC_ERR_INVALID_ARG;

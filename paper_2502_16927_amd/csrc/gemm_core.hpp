@@ -1,4 +1,4 @@
-// Building blocks shared by the matrix-product kernels (gemm.hip, gemm_big.hip): tile enumeration
+// Building blocks of the matrix-product kernels (gemm.hip): tile enumeration
 // over the 8 XCDs, operand tiles moved from global memory straight into LDS, swizzled LDS layouts
 // and the assembly LDS accesses of the MFMA operand fragments.  gfx950 only.
 #pragma once
@@ -81,6 +81,41 @@ __device__ __forceinline__ int tile_at(const TileSpace& ts, int pos) {
   const int id = ts.first + pos;
   return id < ts.last ? id : -1;
 }
+// Tile order in time.  Every XCD owns a run of consecutive tiles, row tile by row tile, so tiles
+// that follow each other share an operand panel (the A rows of a row tile, and every gx-th tile the
+// B columns).  Those panels are re-read from the XCD's L2 only while the tiles that share them run
+// close together in time.  With a fixed stride (workgroup w takes tiles w, w + n, w + 2n, ...)
+// nothing keeps them together: a workgroup that got short tiles (ragged groups) runs ahead for
+// good, after a few rounds the workgroups of an XCD are whole tiles apart, and each fetches its
+// panels from memory again (measured on zipf_stress: 4-5 times the operand bytes came from HBM, and
+// the products ran at the speed of that traffic).  So after its first tile a workgroup claims the
+// XCD's next unstarted tile from a counter: tiles start in index order whatever each one costs,
+// the ones that share a panel start within a fraction of a tile's duration of each other, and a
+// panel's lines are touched again before they leave the L2.
+// The claim runs one tile ahead of its use: the atomic is requested by one lane as a tile's epilogue
+// starts, its result is put into LDS when that epilogue ends (publish), and read by everyone after
+// the next tile's k loop (next).  Counter null: the fixed stride.
+struct TileClaim {
+  unsigned* ctr;
+  int stride;
+  int* box;
+  int got;
+  __device__ __forceinline__ TileClaim(unsigned* claim, int stride_, int* box_)
+      : ctr(claim ? claim + (blockIdx.x & 7) * 16 : nullptr), stride(stride_), box(box_), got(0) {}
+  __device__ __forceinline__ void request() {
+    if (ctr && threadIdx.x == 0) got = (int)__hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __device__ __forceinline__ void publish() {
+    if (ctr && threadIdx.x == 0) *box = stride + got;
+  }
+  // position of the next tile in the XCD's run; a barrier of the workgroup lies between this call and the next request()
+  __device__ __forceinline__ int next(int pos) {
+    if (!ctr) return pos + stride;
+    __syncthreads();
+    return __builtin_amdgcn_readfirstlane(*box);
+  }
+};
+
 // Ragged-K problems (one output matrix per group, contraction over that group's rows): a tile of
 // a group with many rows costs many k tiles, one of a small group almost none, so equal tile
 // counts per XCD can leave one XCD with a multiple of the average work (skewed routing).  The
@@ -207,17 +242,6 @@ struct TileMover {
       else lds_unchunk_tr<CPR>(q, row, cc);
       voff[i] = (unsigned)(row * ld + cc * 8) * 2u;
     }
-  }
-  // one of the NCH loads of a tile (so that they can be spread between other instructions)
-  template <int I>
-  __device__ __forceinline__ void load_one(__amdgpu_buffer_rsrc_t rsrc, uint4* lds, unsigned tile_off) const {
-    static_assert(I >= 0 && I < NCH, "load index");
-#if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds + I * THREADS + wave_chunk), 16,
-                                             voff[I] + tile_off, 0, 0, 0);
-#else
-    (void)rsrc; (void)lds; (void)tile_off;
-#endif
   }
   __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, uint4* lds, unsigned tile_off) const {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc cannot parse this builtin inside a template

@@ -69,10 +69,10 @@ struct SavedPlan {
   size_t topk_idx, topk_w, offsets, slot_of, src_of, tile_map, tile_map_tall, x_perm, act, hact, o_perm, y_low, logits, aux, x_low, total;
 };
 struct FwdPlan {
-  size_t logits, perm, x_low, partials, aux, total;
+  size_t logits, perm, x_low, partials, aux, claims, total;
 };
 struct BwdPlan {
-  size_t dy_low, dgate, do_perm, dx_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, bias_sums, gate_low, total;
+  size_t dy_low, dgate, do_perm, dx_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, bias_sums, gate_low, claims, total;
 };
 
 inline bool bf(const bigmac_dims& D) { return D.dtype == BIGMAC_BF16; }
@@ -158,32 +158,23 @@ inline void touch_weights(const bigmac_dims& D, GemmDesc& g, const void* w, int 
 inline bool wide_k_ok(const bigmac_dims& D, int K, int bit) {
   return bf(D) && (BIGMAC_WIDEK_MASK & bit) && K % 64 == 0;
 }
-// Which products run on 256 x 256 tiles with one workgroup per CU (gemm_big.hip): the products
-// bound by the matrix cores - many tiles, a long K, experts with a thousand rows and more on
-// average - whose output width divides into 256-column tiles.  Bits: 1 expert-up, 2 expert-down,
-// 8 the first matrix's data gradient, 16 / 32 the weight gradients of the second / first matrix.
-// (The GELU' product has no epilogue there and stays on the tall tile.)
-#ifndef BIGMAC_BIG_MASK
-#define BIGMAC_BIG_MASK 0
-#endif
-inline bool big_rows(const bigmac_dims& D, int cols, int K, int bit) {
-  if (!bf(D) || (D.flags & BIGMAC_FLAG_TILES_SMALL)) return false;
-  if (D.flags & BIGMAC_FLAG_TILES_LARGE) return K % 32 == 0;
-  if (!(BIGMAC_BIG_MASK & bit)) return false;
-  const long Tk = (long)D.T * D.k;
-  const long tiles = (Tk / 256 + D.N) * (cols / 256);
-  return cols % 256 == 0 && tiles >= 1024 && K >= 512 && K % 32 == 0 && Tk / D.N >= 1024;
-}
-inline bool big_wgrad(const bigmac_dims& D, int M, int N, int bit) {
+// Which products run on 256 x 256 tiles (eight wavefronts, one workgroup per CU): the per-expert
+// row products that qualify for the tall tile and have K >= 2048.  Per flop that tile asks the L2
+// for two thirds of the operand bytes of the tall one, and these products run at the rate their
+// operands arrive at; its epilogue is not overlapped by another workgroup's k loop, which is what
+// a shorter K does not pay for.  Measured (tall -> 256 x 256): zipf_stress expert-down and the
+// first matrix's data gradient (K = 2048) 1.27 -> 1.19 ms and 1.36 -> 1.27 ms, gpt_xl 0.287 ->
+// 0.275 ms and level; expert-up at K = 512 / 1024 3-6 % slower; the ragged-K weight gradients
+// 5-7 % slower, so they take it only under BIGMAC_FLAG_TILES_LARGE.
+inline bool big_rows(const bigmac_dims& D, int cols, int K) {
   if (!bf(D) || (D.flags & BIGMAC_FLAG_TILES_SMALL)) return false;
   if (D.flags & BIGMAC_FLAG_TILES_LARGE) return true;
-  if (!(BIGMAC_BIG_MASK & bit)) return false;
-  const long Tk = (long)D.T * D.k;
-  return M % 256 == 0 && N % 256 == 0 && (long)D.N * (M / 256) * (N / 256) >= 512 && Tk / D.N >= 1024;
+  return K >= 2048 && cols % 256 == 0 && tall_rows(D, cols, K);
 }
+inline bool big_wgrad(const bigmac_dims& D) { return bf(D) && (D.flags & BIGMAC_FLAG_TILES_LARGE) && !(D.flags & BIGMAC_FLAG_TILES_SMALL); }
 inline bool any_tall_rows(const bigmac_dims& D) {   // a tile map of 256-row tiles is needed
   const Widths W = widths(D);
-  return tall_rows(D, W.hid, W.win) || tall_rows(D, W.win, W.hid) || big_rows(D, W.hid, W.win, 1) || big_rows(D, W.win, W.hid, 2 | 8);
+  return tall_rows(D, W.hid, W.win) || tall_rows(D, W.win, W.hid) || big_rows(D, W.hid, W.win) || big_rows(D, W.win, W.hid);
 }
 
 SavedPlan plan_saved(const bigmac_dims& D) {
@@ -240,6 +231,7 @@ FwdPlan plan_fwd(const bigmac_dims& D) {
   p.x_low = c.take(D.order == BIGMAC_ORDER_DCCA ? (size_t)D.T * D.r * esize(D.dtype) : 0);
   p.partials = c.take(forward_partials_bytes(D));
   p.aux = c.take(D.aux_alpha > 0.0f ? aux_loss_ws_bytes(D) : 0);
+  p.claims = c.take(CLAIM_BYTES);
   p.total = c.off;
   return p;
 }
@@ -308,6 +300,7 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
   // the plan does not see the parameters); router on x': its share of dx' in fp32
   p.bias_sums = c.take(ragged_colsum_ws_bytes(D.N, W.hid > W.win ? W.hid : W.win));
   p.gate_low = c.take(route_low(D) ? (size_t)D.T * D.r * 4 : 0);
+  p.claims = c.take(CLAIM_BYTES);
   p.total = c.off;
   return p;
 }
@@ -315,7 +308,8 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
 size_t ffn_ws_bytes(const bigmac_dims& D) {
   const Widths W = widths(D);
   const size_t Tk = (size_t)D.T * D.k;
-  return align_up(Tk * W.hid * esize(D.dtype)) + 2 * align_up(tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype, 0)) * 4);
+  return align_up(Tk * W.hid * esize(D.dtype)) + 2 * align_up(tile_map_ints((int)Tk, D.N, gemm_ragged_tile_rows(D.dtype, 0)) * 4) +
+         align_up(CLAIM_BYTES);
 }
 
 template <typename ET>
@@ -353,7 +347,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.groups = D.N; g.max_rows = Tk; g.offsets = offsets;
   // hact = gelu(x_perm W1[e])
   g.epilogue = EPI_GELU;
-  g.big_tile = big_rows(D, W.hid, W.win, 1);
+  g.big_tile = big_rows(D, W.hid, W.win);
   g.tall_tile = !g.big_tile && tall_rows(D, W.hid, W.win); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
   g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(D, W.win, 1);
   g.A = x_perm; g.lda = W.win; g.K = W.win;
@@ -376,7 +370,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.B = w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.win;
   g.C = o_perm; g.ldc = W.win;
   g.bias = b2; g.gstride_bias = W.win;
-  g.big_tile = big_rows(D, W.win, W.hid, 2);
+  g.big_tile = big_rows(D, W.win, W.hid);
   g.tall_tile = !g.big_tile && tall_rows(D, W.win, W.hid); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
   g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(D, W.hid, 2);
   g.kloop_priority = 1;
@@ -546,6 +540,8 @@ int bigmac_grouped_ffn(const bigmac_dims* D, const void* x_perm, const int32_t* 
   void* hact = ws;
   int* tile_map = (int*)((char*)ws + align_up(Tk * W.hid * esize(D->dtype)));
   int* tile_map_tall = (int*)((char*)tile_map + align_up(tile_map_ints((int)Tk, D->N, gemm_ragged_tile_rows(D->dtype, 0)) * 4));
+  ClaimScope claims((char*)tile_map_tall + align_up(tile_map_ints((int)Tk, D->N, gemm_ragged_tile_rows(D->dtype, 0)) * 4), s);
+  if (claims.status) return claims.status;
   rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype, 0), tile_map, s);
   if (!rc && any_tall_rows(*D)) rc = launch_build_tile_map(expert_offsets, D->N, gemm_ragged_tile_rows(D->dtype, 1), tile_map_tall, s);
   if (rc) return rc;
@@ -573,6 +569,8 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   const SavedPlan S = plan_saved(*D);
   char* wsb = (char*)ws;
   char* sv = saved ? (char*)saved : wsb + F.total;  // inference keeps the same pieces in the workspace
+  ClaimScope claims(wsb + F.claims, s);
+  if (claims.status) return claims.status;
   int32_t* topk_idx = (int32_t*)(sv + S.topk_idx);
   float* topk_w = (float*)(sv + S.topk_w);
   int32_t* offsets = (int32_t*)(sv + S.offsets);
@@ -703,6 +701,8 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   const BwdPlan B = plan_bwd(*D);
   const char* sv = (const char*)saved;
   char* wsb = (char*)ws;
+  ClaimScope claims(wsb + B.claims, s);
+  if (claims.status) return claims.status;
   const int32_t* topk_idx = (const int32_t*)(sv + S.topk_idx);
   const float* topk_w = (const float*)(sv + S.topk_w);
   const int32_t* offsets = (const int32_t*)(sv + S.offsets);
@@ -770,10 +770,11 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = do_perm; g.lda = W.win; g.K = W.win;
     g.B = P->w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.hid;
     g.C = dact; g.ldc = wide_ld(*D); g.aux_in = act;
-    g.tall_tile = tall_rows(*D, W.hid, W.win); g.tile_map = g.tall_tile ? tile_map_tall : tile_map;
-    g.wide_k = !g.tall_tile && wide_k_ok(*D, W.win, 4);
+    g.big_tile = big_rows(*D, W.hid, W.win);
+    g.tall_tile = !g.big_tile && tall_rows(*D, W.hid, W.win); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
+    g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(*D, W.win, 4);
     g.kloop_priority = 1;              // measured: -3.5 % (gpt_medium), -1.7 % (gpt_xl)
-    touch_weights(*D, g, P->w2, 4);
+    if (!g.big_tile) touch_weights(*D, g, P->w2, 4);
     {
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_DGRAD);
       rc = launch_gemm(g, s);
@@ -791,7 +792,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = hact; g.lda = wide_ld(*D); g.M = W.hid;
     g.B = do_perm; g.ldb = W.win; g.N = W.win;
     g.C = d_w2; g.ldc = W.win; g.gstride_c = (long)W.hid * W.win;
-    g.big_tile = big_wgrad(*D, W.hid, W.win, 16);
+    g.big_tile = big_wgrad(*D);
     g.tall_tile = !g.big_tile && tall_wgrad(*D, W.hid);
     {
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_DOWN_WGRAD);
@@ -802,7 +803,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = x_perm; g.lda = W.win; g.M = W.win;
     g.B = dact; g.ldb = wide_ld(*D); g.N = W.hid;
     g.C = d_w1; g.ldc = W.hid; g.gstride_c = (long)W.win * W.hid;
-    g.big_tile = big_wgrad(*D, W.win, W.hid, 32);
+    g.big_tile = big_wgrad(*D);
     g.tall_tile = !g.big_tile && tall_wgrad(*D, W.win);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_WGRAD);
     rc = launch_gemm(g, s);
@@ -815,7 +816,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.A = dact; g.lda = wide_ld(*D); g.K = W.hid;
     g.B = P->w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.win;
     g.C = dx_perm; g.ldc = W.win;
-    g.big_tile = big_rows(*D, W.win, W.hid, 8);
+    g.big_tile = big_rows(*D, W.win, W.hid);
     g.tall_tile = !g.big_tile && tall_rows(*D, W.win, W.hid); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
     g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(*D, W.hid, 8);
     g.kloop_priority = 1;

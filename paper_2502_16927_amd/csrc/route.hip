@@ -170,8 +170,18 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
   __shared__ uint4 xring[S * XL * 256];             // (a tile of fewer than 256 chunks is padded: the surplus lanes load out of range)
   __shared__ uint4 wring[S * WL * 256];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int tb = blockIdx.x * TOKENS, t0 = tb + wave * TB;
-  int n0 = blockIdx.y * (SL * R_NB);
+  // Workgroup -> (token block, expert slices).  The workgroups that share a token block (one per
+  // group of SL slices) get linear indices 8 apart: consecutive indices go round the 8 XCDs, so
+  // these land on one XCD at about the same time and the block's token rows come from memory
+  // once, then from that XCD's L2; every XCD keeps all of w_gate.  (With the slice index as the
+  // slow grid dimension the token rows were fetched once per slice group and the router columns
+  // did not stay in the L2 behind them: 8 times the algorithmic bytes at d = 4096, N = 128.)
+  const int slice_groups = (N + SL * R_NB - 1) / (SL * R_NB);
+  const int lin = (int)(blockIdx.x >> 3);
+  const int token_block = (lin / slice_groups) * 8 + (int)(blockIdx.x & 7);
+  const int tb = token_block * TOKENS, t0 = tb + wave * TB;
+  if (tb >= T) return;
+  int n0 = (lin % slice_groups) * (SL * R_NB);
   const int nq = d / 64, ntiles = (nq + QQT - 1) / QQT;
   const int rows = min(TOKENS, T - tb);
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)(x + (size_t)tb * d), 0, (int)((size_t)rows * d * sizeof(XT)), 0x00020000);
@@ -773,7 +783,8 @@ int launch_router_logits(const bigmac_dims& D, const void* x, const float* w_gat
   const int tb = groups8 >= 1024 ? 8 : (groups8 * 4 >= 512 ? 2 : 1);
   const int sl = tb == 8 && gy >= 2 && (long)((D.T + 31) / 32) * ((gy + 1) / 2) >= 512 ? ROUTER_SLICES : 1;
 #define BIGMAC_ROUTER(XT, TBV, SLV)                                                                                  \
-  hipLaunchKernelGGL((router_logits_pipelined_kernel<XT, TBV, SLV>), dim3((D.T + 4 * TBV - 1) / (4 * TBV), (gy + SLV - 1) / SLV), block, 0, s, \
+  hipLaunchKernelGGL((router_logits_pipelined_kernel<XT, TBV, SLV>),                                                  \
+                     dim3((((D.T + 4 * TBV - 1) / (4 * TBV) + 7) / 8) * 8 * ((gy + SLV - 1) / SLV)), block, 0, s,     \
                      (const XT*)x, w_gate, bias, logits, D.T, D.d, D.N)
   if (D.dtype == BIGMAC_BF16) {
     if (tb == 8 && sl == 2) BIGMAC_ROUTER(bf16_t, 8, 2);
