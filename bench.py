@@ -26,11 +26,17 @@ PEAK_ALU_F32 = 157.3e12    # flop/s, published fp32 vector peak (unpacked v_fmac
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, the
 # factors a plain 512 MiB copy gives: `bench.py --calibrate-copy`), for the kernels that can
-# dominate the default workload.  A counter run cannot be part of a timed run; these are the
-# figures of the committed summary of those runs (gpt_medium_hbm_traffic under profiles/).
-MEASURED_TRAFFIC = {
+# dominate a workload.  A counter run cannot be part of a timed run; these are the figures of
+# the committed summaries of those runs (the *_hbm_traffic files under profiles/).
+MEASURED_TRAFFIC = {   # stage -> (MiB read, MiB written) per launch
     ("gpt_medium", "dcca"): {"source": "profiles/gpt_medium_hbm_traffic.md",
-                             "bwd_down_dgrad": (195.9 + 128.0) * 1048576, "expert_up": (98.8 + 256.1) * 1048576},
+                             "bwd_down_dgrad": (195.9, 128.0), "expert_up": (98.8, 256.1)},
+    ("zipf_stress", "dcca"): {"source": "profiles/zipf_stress_hbm_traffic.md",
+                              "expert_up": (3159.0, 2048.6), "expert_down": (2082.8, 1024.2), "bwd_down_dgrad": (4398.1, 1024.6),
+                              "bwd_down_wgrad": (5274.6, 1024.3), "bwd_up_wgrad": (4218.5, 1024.1), "bwd_up_dgrad": (2121.3, 1024.2)},
+    ("gpt_xl", "dcca"): {"source": "profiles/gpt_xl_hbm_traffic.md",
+                         "expert_up": (262.5, 768.3), "expert_down": (586.0, 192.1), "bwd_down_dgrad": (638.0, 384.2),
+                         "bwd_down_wgrad": (558.6, 256.0), "bwd_up_wgrad": (484.2, 256.0), "bwd_up_dgrad": (589.5, 192.0)},
 }
 
 
@@ -281,7 +287,7 @@ def main():
         roofline = roofline_of(dom, kind, flops, nbytes, stage_ms[dom] * 1e-3)
         if not args.tokens and not variant:
             measured = MEASURED_TRAFFIC.get((wl.name, args.order), {})
-            roofline["traffic"] = measured.get(dom)
+            roofline["traffic"] = sum(measured[dom]) * 1048576 if dom in measured else None
             roofline["traffic_source"] = measured.get("source") if dom in measured else None
         # every stage against both of its rooflines: matrix (or fp32 vector) rate and HBM bytes
         for n, ms in stage_ms.items():

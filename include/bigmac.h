@@ -19,14 +19,18 @@
  *    logits and all weight gradients are always fp32.  All accumulation is fp32.
  *  - Widths: win = dispatch width (r for DCCA, d for CDAC), hid = expert hidden width (h for
  *    DCCA, r for CDAC).  d, r, h must be multiples of 64; 1 <= k <= N <= 1024; k <= 64; T*k < 2^31.
+ *    With bf16 storage bigmac_layer_backward also needs N % 8 == 0 (the dense logit gradient is
+ *    moved in 16-byte pieces of its N-wide rows): BIGMAC_ERR_UNSUPPORTED otherwise.  A matrix
+ *    product whose tiles would span 2 GiB or more of one operand (T*k rows of the widest
+ *    [rows, hidden] tensor in bf16) is refused with BIGMAC_ERR_TOO_LARGE.
  *  - The caller owns every buffer (inputs, outputs, workspace, saved block).  The library
  *    allocates nothing, keeps no state and never synchronises: a call only enqueues kernels on
  *    `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns.  Nothing
  *    on the path is read back by the host; per-expert counts stay on the device.
  *  - Return value: 0 on success; negative on failure, in which case nothing was launched by the
  *    failing step: BIGMAC_ERR_INVALID_ARG (NULL required pointer, bad dimension or enum),
- *    BIGMAC_ERR_WORKSPACE (workspace too small), BIGMAC_ERR_UNSUPPORTED, BIGMAC_ERR_HIP (a
- *    launch failed).  Inputs are assumed finite; NaN/Inf logits give unspecified routing.
+ *    BIGMAC_ERR_WORKSPACE (workspace too small), BIGMAC_ERR_UNSUPPORTED, BIGMAC_ERR_TOO_LARGE (a
+ *    size beyond a stated limit), BIGMAC_ERR_HIP (a launch failed).  Inputs are assumed finite; NaN/Inf logits give unspecified routing.
  *  - Routing is dropless (Section 3.3) unless dims.capacity > 0: every (token, choice) pair
  *    keeps a row, the rows of an expert are contiguous and ordered by token,
  *    expert_offsets[N] = T*k.

@@ -820,6 +820,16 @@ int launch_gemm(const GemmDesc& desc, hipStream_t s) {
     if ((g.a_kcontig || g.b_kcontig) && g.mode == GEMM_RAGGED_K) return BIGMAC_ERR_UNSUPPORTED;  // k ranges start anywhere
   }
   if (g.mode == GEMM_DENSE && g.ksplit < 1) return BIGMAC_ERR_INVALID_ARG;
+  if (g.dtype == BIGMAC_BF16) {
+    // A tile's operand is one buffer addressed by 32-bit byte offsets whose top bit marks "out of
+    // range".  Operands whose rows are the k index span (k range) x pitch bytes per tile: the whole
+    // K of a dense product, at most all rows of a ragged-K one (max_rows, when the caller gives it).
+    const size_t krows = g.mode == GEMM_RAGGED_K ? (size_t)(g.max_rows > 0 ? g.max_rows : 0) : (size_t)g.K;
+    const size_t limit = 1ull << 31;
+    if ((!g.a_kcontig && krows * (size_t)g.lda * 2 >= limit) || (!g.b_kcontig && krows * (size_t)g.ldb * 2 >= limit) ||
+        (g.a_kcontig && 256ull * (size_t)g.lda * 2 >= limit) || (g.b_kcontig && 256ull * (size_t)g.ldb * 2 >= limit))
+      return BIGMAC_ERR_TOO_LARGE;
+  }
   const int combo = g.a_kcontig * 2 + g.b_kcontig;
   if (g.big_tile) {
     if (g.dtype != BIGMAC_BF16 || g.tall_tile || g.wide_k || g.deep_tile || g.touch_bytes) return BIGMAC_ERR_INVALID_ARG;

@@ -787,7 +787,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   }
   {  // dW2[e] (+)= hact_e^T do_perm_e
     GemmDesc g = base_desc(*D);
-    g.mode = GEMM_RAGGED_K; g.groups = D->N; g.offsets = offsets; g.tile_map = tile_map;
+    g.mode = GEMM_RAGGED_K; g.groups = D->N; g.max_rows = Tk; g.offsets = offsets; g.tile_map = tile_map;
     g.a_kcontig = 0; g.b_kcontig = 0; g.epilogue = EPI_ACCUM; g.beta = accumulate;
     g.A = hact; g.lda = wide_ld(*D); g.M = W.hid;
     g.B = do_perm; g.ldb = W.win; g.N = W.win;

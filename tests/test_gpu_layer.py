@@ -113,6 +113,35 @@ def test_large_tiles_give_the_same_bits(case):
         assert torch.equal(u, v)
 
 
+def test_all_bf16_wire_format(oracle):
+    """BIGMAC_FLAG_WIRE_BF16 (Table 4's BF16 transfers taken literally: expert outputs and the gradient
+    of the dispatched rows rounded to bf16 between the expert products and the combine kernels):
+    same routing, same saved activations; y, dx and the gradients stay at the bar on this shape
+    and within a bf16 rounding's reach of the default (fp32) wire format."""
+    wl = synth.small(T=1024, d=256, r=128, N=8, k=2, h=256)
+    data = synth.generate(wl)
+    ref_y = oracle_forward(oracle, data, wl.k)
+    outs = []
+    for flags in (0, B.FLAG_WIRE_BF16):
+        layer = DeviceLayer(wl, data, flags=flags)
+        y = layer.forward(training=True)
+        layer.alloc_grads()
+        layer.backward()
+        torch.cuda.synchronize()
+        outs.append({"y": host(y), "dx": host(layer.dx), **{n: host(g) for n, g in layer.grads.items()}})
+    a, b = outs
+    assert rel_err(a["y"], ref_y) < TOL and rel_err(b["y"], ref_y) < TOL, (rel_err(a["y"], ref_y), rel_err(b["y"], ref_y))
+    worst = {}
+    for n in a:
+        if n in ("y", "dx", "d_w_gate"):                                # what sees O or dx_perm: the flag changes it ...
+            assert not np.array_equal(a[n], b[n]), n
+        if n in ("d_w1", "d_w2"):                                       # (the expert products' own operands are bf16 either way)
+            assert np.array_equal(a[n], b[n]), n
+        worst[n] = rel_err(b[n], a[n])
+        assert worst[n] < TOL, (n, worst[n])                            # ... by no more than a few bf16 roundings
+    print("all-bf16 wire format against the default: max-abs/rms", {n: round(v, 4) for n, v in worst.items()}, flush=True)
+
+
 def test_bf16_output_is_the_rounded_fp32_output(oracle):
     wl = synth.small(T=200, d=128, r=64, N=8, k=2, h=128)
     data = synth.generate(wl)
