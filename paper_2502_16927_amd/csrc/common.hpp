@@ -227,7 +227,7 @@ enum CombineOut { COMBINE_F32 = 0, COMBINE_SPLIT_BF16 = 1 };  // fp32 [T,w]  |  
 // dtype: element type of the gathered rows (BIGMAC_F32 or BIGMAC_BF16)
 // addend (optional, fp32 [T, width]): the sum of a token starts from its row instead of zero
 int launch_combine_rows(int dtype, int T, int k, int width, const void* o_perm, const int32_t* slot_of,
-                        const float* topk_w, void* y_low, int out_kind, hipStream_t s, const float* addend = nullptr);
+                        const float* topk_w, void* y_low, int out_kind, hipStream_t s, const float* addend = nullptr, int stream_out = 0);
 // backward of the weighted combine: dgate[t,j] = <dy_low[t], o_perm[slot]>, do_perm[slot] = w[t,j]*dy_low[t]
 // (o_dtype: element type of o_perm; do_perm has the storage type `dtype`)
 int launch_combine_backward(int dtype, int o_dtype, int T, int k, int width, const float* dy_low, const void* o_perm,

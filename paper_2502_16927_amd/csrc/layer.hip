@@ -841,7 +841,8 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
   {
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_DISPATCH);
     rc = launch_combine_rows(wire_dtype(*D), D->T, D->k, W.win, dx_perm, slot_of, nullptr, dx_low,
-                             (dcca && bf(*D)) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s, gate_low);
+                             (dcca && bf(*D)) ? COMBINE_SPLIT_BF16 : COMBINE_F32, s, gate_low,
+                             /*stream_out=*/low_bytes(*D) >= (32u << 20));   // (smaller results are read back from the caches)
   }
   if (rc) return rc;
   {  // dW_g (+)= x^T dL  (router on x': x'^T dL)
