@@ -128,6 +128,10 @@ def main():
     ap.add_argument("--tiles", default="auto", choices=["auto", "large", "small"],
                     help="tuning: force the 256 x 256 workgroup tiles on every expert product that can take them, or forbid them")
     ap.add_argument("--tokens", type=int, default=0, help="override T (decode sweep)")
+    ap.add_argument("--forward-only", action="store_true", help="time the inference forward of the workload (no saved block, no backward)")
+    ap.add_argument("--no-fused-dispatch", action="store_true",
+                    help="forward-only runs: dispatch the rows first instead of reading them through the index in the "
+                         "expert-up product (BIGMAC_FLAG_NO_FUSED_DISPATCH)")
     ap.add_argument("--order", default="dcca", choices=["dcca", "cdac"])
     ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of the oracle timing sample (0: skip)")
     ap.add_argument("--no-stage-events", action="store_true")
@@ -190,15 +194,15 @@ def main():
     if args.tokens:
         wl = wl.with_T(args.tokens)
     cdac = args.order == "cdac"
-    training = wl.backward
+    training = wl.backward and not args.forward_only
     dev = "cuda:0"
     torch.cuda.set_device(0)
     data = synth.generate(wl)
     capacity = B.expert_capacity(wl.T, wl.k, wl.N, args.capacity_factor) if args.capacity_factor > 0 else 0
     tile_flag = {"auto": 0, "large": B.FLAG_TILES_LARGE, "small": B.FLAG_TILES_SMALL}[args.tiles]
-    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA, flags=(B.FLAG_WIRE_BF16 if args.wire_bf16 else 0) | tile_flag,
+    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA, flags=(B.FLAG_WIRE_BF16 if args.wire_bf16 else 0) | tile_flag | (B.FLAG_NO_FUSED_DISPATCH if args.no_fused_dispatch else 0),
                      capacity=capacity, aux_alpha=args.aux_alpha)
-    variant = capacity > 0 or args.aux_alpha > 0 or args.wire_bf16      # not the headline configuration
+    variant = capacity > 0 or args.aux_alpha > 0 or args.wire_bf16 or args.forward_only or args.no_fused_dispatch   # not the headline configuration
     x = B.to_device(data["x"], wl.dtype, dev)
     dy = B.to_device(data.get("dy"), wl.dtype, dev)
     wg = B.to_device(data["w_gate"], B.F32, dev)
@@ -314,7 +318,8 @@ def main():
                    "h": wl.h, "pass": "fwd+bwd" if training else "fwd",
                    **({"capacity_factor": args.capacity_factor, "capacity": capacity} if capacity else {}),
                    **({"aux_alpha": args.aux_alpha} if args.aux_alpha > 0 else {}),
-                   **({"wire": "bf16"} if args.wire_bf16 else {}), **({"tiles": args.tiles} if args.tiles != "auto" else {})},
+                   **({"wire": "bf16"} if args.wire_bf16 else {}), **({"tiles": args.tiles} if args.tiles != "auto" else {}),
+                   **({"dispatch": "separate kernel"} if args.no_fused_dispatch else {})},
         "timed": timed,
         **({"block_ms_per_step": [round(v, 4) for v in block_ms], "block_ms_median": round(sorted(block_ms)[len(block_ms) // 2], 4),
             "block_ms_min": round(min(block_ms), 4)} if not args.no_graph else {}),

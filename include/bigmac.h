@@ -66,10 +66,14 @@ enum {
   BIGMAC_FLAG_TILES_LARGE = 8, /* tuning: run every expert product that can on 256 x 256 workgroup tiles,  */
   BIGMAC_FLAG_TILES_SMALL = 16,/* or none of them (default: chosen from the shape).  Results do not depend
                                   on the tile: the same products are added in the same order.            */
-  BIGMAC_FLAG_ROUTE_LOW = 32   /* layer calls, DCCA order: the router reads x' instead of x (Section 3.1
+  BIGMAC_FLAG_ROUTE_LOW = 32,  /* layer calls, DCCA order: the router reads x' instead of x (Section 3.1
                                   names both inputs): w_gate and d_w_gate are [r, N], the logits are those of
                                   bigmac_route on the stored x' (dtype) with d = r, and the gate's gradient
                                   reaches x through x' (and so W_down).  A fourth of the router's work.   */
+  BIGMAC_FLAG_NO_FUSED_DISPATCH = 64  /* forward-only layer calls with dtype BF16 read the expert-up product's
+                                  rows straight from x' (x in the CDAC order) through src_of and write no
+                                  permuted copy; with this flag they dispatch first, as a training forward
+                                  does.  Same results bit for bit (tests and measurements).               */
 };
 
 enum {

@@ -12,7 +12,7 @@ import torch
 
 F32, BF16 = 0, 1
 ORDER_DCCA, ORDER_CDAC = 0, 1
-FLAG_ACCUMULATE, FLAG_OUT_BF16, FLAG_WIRE_BF16, FLAG_TILES_LARGE, FLAG_TILES_SMALL, FLAG_ROUTE_LOW = 1, 2, 4, 8, 16, 32
+FLAG_ACCUMULATE, FLAG_OUT_BF16, FLAG_WIRE_BF16, FLAG_TILES_LARGE, FLAG_TILES_SMALL, FLAG_ROUTE_LOW, FLAG_NO_FUSED_DISPATCH = 1, 2, 4, 8, 16, 32, 64
 WS_ROUTE, WS_DISPATCH, WS_GROUPED_FFN, WS_LAYER_FORWARD, WS_LAYER_TRAIN, WS_SAVED, WS_AUX_LOSS = range(7)
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbigmac.so")

@@ -155,6 +155,8 @@ struct GemmDesc {
   int kloop_priority;        // MFMA kernels: raise the wave priority inside the k loop (see the kernel)
   int deep_tile;             // bf16, dense, store or accumulate (K % 64 == 0 with a k-contiguous operand): 128 x 64 outputs, 64-deep k tiles
   int big_tile;              // bf16: 256 x 256 outputs by eight wavefronts, one workgroup per CU (ragged-M: tile map of 256-row tiles)
+  const int* gather;         // ragged-M MFMA kernels with a k-contiguous A, GELU or store epilogue: row m of the product is row gather[m] / gather_div of A (device [max_rows]); NULL: A holds the rows in order
+  int gather_rows, gather_div; //   rows of A behind the index; the index is divided by gather_div first (flat (row, pick) pairs)
   unsigned* claim;           // MFMA kernels, optional: zeroed tile counters of this launch (ClaimScope hands them out; see tile order in gemm_core.hpp)
   const void* touch;         // MFMA kernels, optional: a region (device) every line of which is read once as the kernel starts,
   size_t touch_bytes;        //   so that its first use in a k loop meets the caches and not the memory (0 = off)

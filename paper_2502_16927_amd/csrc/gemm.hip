@@ -20,7 +20,7 @@ namespace bigmac {
 // happen are pushed out of their buffer's range instead of being branched around): the number of
 // instructions in flight behind any load is then a compile-time constant, which is what the
 // counter waits below and the compiler's own ones are derived from.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32, int NS = BIGMAC_TILE_STAGES>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32, int NS = BIGMAC_TILE_STAGES, bool GATHER = false>
 __global__ __launch_bounds__(64 * WAVES_M* WAVES_N)
     __attribute__((amdgpu_waves_per_eu(BM > BIGMAC_TILE_BM || BK > BIGMAC_TILE_BK ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU)))   // (eight wavefronts, one block per CU: also 2)
 void mfma_gemm_kernel(GemmDesc p) {
@@ -64,6 +64,40 @@ void mfma_gemm_kernel(GemmDesc p) {
   MoveB mb;
   ma.init(p.lda);
   mb.init(p.ldb);
+  // GATHER (ragged-M, k-contiguous A): row m of the product is row gather[m] / gather_div of A
+  // (the index holds flat (token, pick) pairs, gather_div picks per token), so the rows an
+  // expert works on are read where they lie instead of from a permuted copy (the dispatch step
+  // folded into this product's operand loads).  A lane's chunks keep their place in the tile;
+  // what changes from tile to tile is the memory row behind each of them: its index is read one
+  // tile ahead (gather_request) and turned into the mover's offsets once the k loop of the tile
+  // before is over (gather_apply).  Tile rows past the group's end read row gather[..] = 0 of A
+  // (an index beyond the table's range arrives as zero): finite values that only reach output rows
+  // the epilogue does not store.
+  static_assert(!GATHER || AK, "gathered rows are k-contiguous rows of A");
+  int gather_row[GATHER ? MoveA::NCH : 1];
+  unsigned gather_col[GATHER ? MoveA::NCH : 1], gather_idx[GATHER ? MoveA::NCH : 1];
+  if (GATHER) {
+#pragma unroll
+    for (int i = 0; i < MoveA::NCH; ++i) {
+      int row, cc;
+      lds_unchunk_kc<MoveA::CPR>(i * THREADS + (int)threadIdx.x, row, cc);
+      gather_row[i] = row;
+      gather_col[i] = (unsigned)cc * 16u;
+    }
+  }
+  auto gather_request = [&](const TileCoord& t) {
+    if (GATHER) {
+      const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc((void*)p.gather, 0, t.valid ? t.m_end * 4 : 0, 0x00020000);
+#pragma unroll
+      for (int i = 0; i < MoveA::NCH; ++i) gather_idx[i] = __builtin_amdgcn_raw_buffer_load_b32(rg, (unsigned)(t.m0 + gather_row[i]) * 4u, 0, 0);
+    }
+  };
+  auto gather_apply = [&]() {
+    if (GATHER) {
+#pragma unroll
+      for (int i = 0; i < MoveA::NCH; ++i) ma.voff[i] = (gather_idx[i] / (unsigned)p.gather_div) * (unsigned)(p.lda * 2) + gather_col[i];
+    }
+  };
   const int wrap_tiles = p.kwrap_b ? p.kwrap_b / BK : 0x7FFFFFFF;
 
   TileSpace ts = tile_space<BM, BN>(p);
@@ -78,7 +112,10 @@ void mfma_gemm_kernel(GemmDesc p) {
     o.nk = (klen + BK - 1) / BK;
     o.wrap_first = p.kwrap_b ? (t.kbeg / BK) % (p.kwrap_b / BK) : 0;
     const bf16_t* A = (const bf16_t*)p.A;
-    if (AK) {
+    if (GATHER) {   // all of A: the rows come through the index
+      o.ra = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, t.valid && klen > 0 ? (int)(((size_t)(p.gather_rows - 1) * p.lda + klen) * 2) : 0, 0x00020000);
+      o.step_a = BK * 2u;
+    } else if (AK) {
       const int rows = min(t.m_end - t.m0, BM);
       o.ra = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (size_t)t.m0 * p.lda + t.kbeg), 0,
                                                rows > 0 && klen > 0 ? (int)(((size_t)(rows - 1) * p.lda + klen) * 2) : 0, 0x00020000);
@@ -217,6 +254,8 @@ void mfma_gemm_kernel(GemmDesc p) {
   int id = tile_at(ts, pos);
   if (id < 0) return;
   TileOperands cur = operands(id);
+  gather_request(cur.t);
+  gather_apply();
   prefetch(cur);
   request_aux(cur.t, 0);
   // Tile order (see TileClaim): the first tile is this workgroup's slot, every later one is claimed.
@@ -228,6 +267,7 @@ void mfma_gemm_kernel(GemmDesc p) {
   pos = claim.next(pos);
   int nid = tile_at(ts, pos);
   TileOperands nxt = operands(nid);
+  gather_request(nxt.t);
 
   while (true) {
     const TileCoord t = cur.t;
@@ -313,6 +353,7 @@ void mfma_gemm_kernel(GemmDesc p) {
     // last stage (the last k step waited for everything that was requested into it).
     __builtin_amdgcn_s_barrier();
     claim.request();                                     // (everyone has read the box)
+    gather_apply();                                      // the mover's rows are now those of the next tile
     // bf16 epilogue staging, in the ring's last stage: the prefetch below fills stages
     // 0 .. NS - 2, and the last stage is requested again only behind the first barrier of the next
     // k loop.  A staged row is 128 bytes = 8 chunks of 16; chunk c of row r sits at position
@@ -467,6 +508,7 @@ void mfma_gemm_kernel(GemmDesc p) {
     pos = claim.next(pos);
     nid = tile_at(ts, pos);
     nxt = operands(nid);
+    gather_request(nxt.t);
   }
 }
 
@@ -649,6 +691,18 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
   dim3 grid = grid_for<BM, BN>(g, true), block(64 * WMs * WNs);
 #define BIGMAC_MFMA(EPI, OUTF32) \
   hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI, OUTF32>), grid, block, 0, s, g)
+  if constexpr (AK && !BKC) {
+    if (g.gather) {   // gathered rows: the two epilogues of the expert-up product
+      if (g.epilogue == EPI_GELU)
+        hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI_GELU, false, BIGMAC_TILE_STAGES, true>), grid, block, 0, s, g);
+      else if (g.epilogue == EPI_STORE && !g.out_f32)
+        hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI_STORE, false, BIGMAC_TILE_STAGES, true>), grid, block, 0, s, g);
+      else
+        return BIGMAC_ERR_UNSUPPORTED;
+      BIGMAC_CHECK_LAUNCH();
+      return BIGMAC_OK;
+    }
+  }
   switch (g.epilogue) {
     case EPI_STORE:
       if (g.out_f32) BIGMAC_MFMA(EPI_STORE, true);
@@ -673,6 +727,16 @@ int launch_mfma_wide(const GemmDesc& g, hipStream_t s) {
   dim3 grid = grid_for<BM, BN>(g, true, 1), block(512);
 #define BIGMAC_MFMA_WIDE(EPI, OUTF32) \
   hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 2, 4, AK, BKC, EPI, OUTF32, 4>), grid, block, 0, s, g)
+  if constexpr (AK && !BKC) {
+    if (g.gather) {
+      if (g.epilogue == EPI_GELU) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 2, 4, AK, BKC, EPI_GELU, false, 4, true>), grid, block, 0, s, g);
+      else if (g.epilogue == EPI_STORE && !g.out_f32)
+        hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 2, 4, AK, BKC, EPI_STORE, false, 4, true>), grid, block, 0, s, g);
+      else return BIGMAC_ERR_UNSUPPORTED;
+      BIGMAC_CHECK_LAUNCH();
+      return BIGMAC_OK;
+    }
+  }
   switch (g.epilogue) {
     case EPI_STORE:
       if (g.out_f32) BIGMAC_MFMA_WIDE(EPI_STORE, true);
@@ -831,6 +895,11 @@ int launch_gemm(const GemmDesc& desc, hipStream_t s) {
       return BIGMAC_ERR_TOO_LARGE;
   }
   const int combo = g.a_kcontig * 2 + g.b_kcontig;
+  if (g.gather) {   // see the kernel: ragged-M rows of a k-contiguous A through an index, B not k-contiguous
+    if (g.dtype != BIGMAC_BF16 || g.mode != GEMM_RAGGED_M || combo != 2 || g.wide_k || g.deep_tile || g.gather_rows <= 0 || g.gather_div <= 0 ||
+        (size_t)g.gather_rows * (size_t)g.lda * 2 >= (1ull << 31))
+      return BIGMAC_ERR_UNSUPPORTED;
+  }
   if (g.big_tile) {
     if (g.dtype != BIGMAC_BF16 || g.tall_tile || g.wide_k || g.deep_tile || g.touch_bytes) return BIGMAC_ERR_INVALID_ARG;
     switch (combo) {

@@ -15,7 +15,8 @@ int check_dims(const bigmac_dims* D) {
   if ((long long)D->T * D->k >= (1ll << 31)) return BIGMAC_ERR_INVALID_ARG;
   if (D->dtype != BIGMAC_F32 && D->dtype != BIGMAC_BF16) return BIGMAC_ERR_INVALID_ARG;
   if (D->act != BIGMAC_ACT_GELU_ERF) return BIGMAC_ERR_INVALID_ARG;
-  if (D->flags & ~(BIGMAC_FLAG_ACCUMULATE | BIGMAC_FLAG_OUT_BF16 | BIGMAC_FLAG_WIRE_BF16 | BIGMAC_FLAG_TILES_LARGE | BIGMAC_FLAG_TILES_SMALL | BIGMAC_FLAG_ROUTE_LOW)) return BIGMAC_ERR_INVALID_ARG;
+  if (D->flags & ~(BIGMAC_FLAG_ACCUMULATE | BIGMAC_FLAG_OUT_BF16 | BIGMAC_FLAG_WIRE_BF16 | BIGMAC_FLAG_TILES_LARGE | BIGMAC_FLAG_TILES_SMALL | BIGMAC_FLAG_ROUTE_LOW |
+                   BIGMAC_FLAG_NO_FUSED_DISPATCH)) return BIGMAC_ERR_INVALID_ARG;
   if ((D->flags & BIGMAC_FLAG_TILES_LARGE) && (D->flags & BIGMAC_FLAG_TILES_SMALL)) return BIGMAC_ERR_INVALID_ARG;
   if (D->capacity < 0 || !(D->aux_alpha >= 0.0f) || D->aux_alpha > 1e30f) return BIGMAC_ERR_INVALID_ARG;
   if (D->order == BIGMAC_ORDER_CDAC && D->dtype == BIGMAC_BF16 && (D->flags & BIGMAC_FLAG_OUT_BF16)) return BIGMAC_ERR_UNSUPPORTED;
@@ -338,7 +339,7 @@ GemmDesc base_desc(const bigmac_dims& D) {
 // The two expert products on permuted rows (ragged per-expert row ranges).
 int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* offsets, const int* tile_map, const int* tile_map_tall,
                         const void* w1, const void* w2, const void* b1, const void* b2, void* act, void* hact, int ld_wide, void* o_perm, int o_f32,
-                        hipStream_t s) {
+                        hipStream_t s, const int* gather = nullptr) {
   const Widths W = widths(D);
   const int Tk = D.T * D.k;
   GemmDesc g = base_desc(D);
@@ -349,8 +350,9 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.epilogue = EPI_GELU;
   g.big_tile = big_rows(D, W.hid, W.win);
   g.tall_tile = !g.big_tile && tall_rows(D, W.hid, W.win); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
-  g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(D, W.win, 1);
+  g.wide_k = !g.tall_tile && !g.big_tile && !gather && wide_k_ok(D, W.win, 1);
   g.A = x_perm; g.lda = W.win; g.K = W.win;
+  g.gather = gather; g.gather_rows = D.T; g.gather_div = D.k;   // with an index, x_perm is the [T, win] rows before the dispatch
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
   g.C = hact; g.ldc = ld_wide; g.aux_out = act;
   g.bias = b1; g.gstride_bias = W.hid;
@@ -365,6 +367,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   }
   if (rc) return rc;
   // o_perm = hact W2[e]
+  g.gather = nullptr; g.gather_rows = 0;
   g.epilogue = EPI_STORE; g.out_f32 = o_f32; g.aux_out = nullptr;
   g.A = hact; g.lda = ld_wide; g.K = W.hid;
   g.B = w2; g.ldb = W.win; g.gstride_b = (long)W.hid * W.win; g.N = W.win;
@@ -644,12 +647,17 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     rc = launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s, &maps);
     if (rc) return rc;
   }
-  {
+  // Forward-only calls on bf16 storage fold the dispatch into the expert-up product: its A rows are
+  // read from x' (or x) through src_of and no permuted copy is written.  A training forward
+  // keeps the copy: the backward pass contracts over its rows.
+  const bool fuse_dispatch = !saved && bf(*D) && !(D->flags & BIGMAC_FLAG_NO_FUSED_DISPATCH);
+  if (!fuse_dispatch) {
     BIGMAC_STAGE(BIGMAC_STAGE_DISPATCH);
     rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);
   }
   if (rc) return rc;
-  rc = run_experts_forward(*D, x_perm, offsets, tile_map, tile_map_tall, P->w1, P->w2, P->b1, P->b2, act, hact, wide_ld(*D), o_perm, wire_f32(*D) ? 1 : 0, s);
+  rc = run_experts_forward(*D, fuse_dispatch ? x_low : x_perm, offsets, tile_map, tile_map_tall, P->w1, P->w2, P->b1, P->b2, act, hact, wide_ld(*D), o_perm,
+                           wire_f32(*D) ? 1 : 0, s, fuse_dispatch ? src_of : nullptr);
   if (rc) return rc;
   if (!dcca) {  // fine-grained layer: the weighted sum is the output
     BIGMAC_STAGE(BIGMAC_STAGE_COMBINE);

@@ -56,7 +56,7 @@ def test_closed_forms_of_table_3():
 
 BAD_DIMS = [
     dict(T=0), dict(d=100), dict(r=32), dict(h=65), dict(k=0), dict(k=9, N=8), dict(N=2048), dict(k=65, N=128),
-    dict(dtype=7), dict(act=3), dict(order=2), dict(flags=64), dict(T=1 << 29, k=8),
+    dict(dtype=7), dict(act=3), dict(order=2), dict(flags=128), dict(T=1 << 29, k=8),
 ]
 
 

@@ -113,6 +113,27 @@ def test_large_tiles_give_the_same_bits(case):
         assert torch.equal(u, v)
 
 
+@pytest.mark.parametrize("order", [B.ORDER_DCCA, B.ORDER_CDAC])
+@pytest.mark.parametrize("tiles", [0, B.FLAG_TILES_LARGE])
+def test_dispatch_folded_into_the_expert_product(order, tiles):
+    """A forward-only call reads the rows of the expert-up product from x' (x in the fine-grained
+    order) through src_of instead of dispatching them first.  Same bits as with the dispatch
+    (BIGMAC_FLAG_NO_FUSED_DISPATCH) and as the training forward: ragged and empty experts,
+    a capacity that drops pairs, every tile shape."""
+    wl = synth.small(T=1100, d=256, r=128, N=24, k=4, h=256, zipf_s=1.5)
+    data = synth.generate(wl)
+    if order == B.ORDER_CDAC:
+        data = add_cdac_weights(data)
+    for capacity in (0, B.expert_capacity(wl.T, wl.k, wl.N, 0.7)):
+        outs = []
+        for flags, training in ((tiles, False), (tiles | B.FLAG_NO_FUSED_DISPATCH, False), (tiles, True)):
+            layer = DeviceLayer(wl, data, order=order, flags=flags, capacity=capacity)
+            outs.append(host(layer.forward(training=training)).copy())
+        assert np.isfinite(outs[0]).all() and np.abs(outs[0]).max() > 0
+        assert np.array_equal(outs[0], outs[1]), "folded dispatch differs from the dispatched forward"
+        assert np.array_equal(outs[0], outs[2]), "inference differs from the training forward"
+
+
 def test_all_bf16_wire_format(oracle):
     """BIGMAC_FLAG_WIRE_BF16 (Table 4's BF16 transfers taken literally: expert outputs and the gradient
     of the dispatched rows rounded to bf16 between the expert products and the combine kernels):
