@@ -143,6 +143,12 @@ def main():
                     help="fixed expert capacity ceil(f T k / N) instead of dropless routing (the paper's training runs: 1.2)")
     ap.add_argument("--aux-alpha", type=float, default=0.0,
                     help="coefficient of the load-balance loss (the paper's training runs: 0.001); 0 = off")
+    ap.add_argument("--gather-ceiling", action="store_true",
+                    help="only run the library's read-only gather probe (bigmac_gather_probe): what the device moves for the "
+                         "combine kernels' access pattern without any write, rows in order and shuffled")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="only time the vendor library's bf16 GEMM (torch.bmm / torch.matmul) at the expert-product shapes of "
+                         "--workload with evenly loaded experts: the rate tuned kernels reach on this device at these shapes")
     ap.add_argument("--mfma-peak", action="store_true",
                     help="only time the matrix-core rate probe (register-resident 32x32x16 bf16 MFMAs): the "
                          "achievable dense bf16 peak of this device, printed beside the published one")
@@ -189,7 +195,56 @@ def main():
                           "probe": "32x32x16 bf16, 4 accumulators per wavefront, %d workgroups x 4 wavefronts" % blocks}))
         return
 
+    def timed_ms(fn, reps=5):
+        best = float("inf")
+        fn()
+        torch.cuda.synchronize()
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best
+
+    if args.gather_ceiling:
+        torch.cuda.set_device(0)
+        rows, row_bytes = 262144, 4096          # the fp32 rows of zipf_stress's combine: 1 GiB
+        table = torch.ones(rows * row_bytes // 4, dtype=torch.float32, device="cuda:0")
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        rng = np.random.default_rng(1)
+        out = {"rows": rows, "row_bytes": row_bytes}
+        for name, order in (("in_order", np.arange(rows, dtype=np.int32)), ("shuffled", rng.permutation(rows).astype(np.int32))):
+            od = torch.from_numpy(order).to("cuda:0")
+            for streaming in (0, 1):
+                ms = timed_ms(lambda: B.bigmac_gather_probe(table, od, rows, row_bytes, streaming, sink))
+                out["%s_%s_tbps" % (name, "non_temporal" if streaming else "plain")] = round(rows * row_bytes / (ms * 1e-3) / 1e12, 3)
+        src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        out["plain_copy_tbps_read_plus_written"] = round(2 * (512 << 20) / (timed_ms(lambda: dst.copy_(src)) * 1e-3) / 1e12, 3)
+        print(json.dumps(out))
+        return
+
     wl = synth.WORKLOADS.get(args.workload) or synth.NEXT_WORKLOADS[args.workload]
+    if args.vendor_gemm:
+        torch.cuda.set_device(0)
+        win, hid = (wl.d, wl.r) if args.order == "cdac" else (wl.r, wl.h)
+        per = max(8, (wl.T * wl.k // wl.N) // 8 * 8)     # rows per expert, evenly loaded
+        a = torch.randn(wl.N, per, win, device="cuda:0", dtype=torch.bfloat16)
+        w1 = torch.randn(wl.N, win, hid, device="cuda:0", dtype=torch.bfloat16) * 0.02
+        h = torch.randn(wl.N, per, hid, device="cuda:0", dtype=torch.bfloat16)
+        w2 = torch.randn(wl.N, hid, win, device="cuda:0", dtype=torch.bfloat16) * 0.02
+        flops = 2.0 * wl.N * per * win * hid
+        up, down = timed_ms(lambda: torch.bmm(a, w1)), timed_ms(lambda: torch.bmm(h, w2))
+        a2, h2 = a.view(wl.N * per, win), h.view(wl.N * per, hid)
+        up1, down1 = timed_ms(lambda: torch.matmul(a2, w1[0])), timed_ms(lambda: torch.matmul(h2, w2[0]))
+        print(json.dumps({"workload": wl.name, "experts": wl.N, "rows_per_expert": per, "win": win, "hid": hid,
+                          "bmm_up_ms": round(up, 4), "bmm_up_tflops": round(flops / up / 1e9, 1),
+                          "bmm_down_ms": round(down, 4), "bmm_down_tflops": round(flops / down / 1e9, 1),
+                          "one_weight_matmul_up_tflops": round(flops / up1 / 1e9, 1), "one_weight_matmul_down_tflops": round(flops / down1 / 1e9, 1),
+                          "note": "plain products, bf16 results, no activation, no saved pre-activation, no ragged groups"}))
+        return
     if args.workload == "vanilla_moe":
         args.order = "cdac"   # the vanilla layer is a CDAC-order layer with a wide hidden dimension
     if args.tokens:

@@ -257,6 +257,18 @@ int bigmac_set_stage_events(void *const *events);
  * written (keeps the arithmetic alive); *flops (host) receives the flops of the launch.  The
  * caller times the launch.  blocks in [1, 65536], iters in [1, 2^20]; else BIGMAC_ERR_INVALID_ARG. */
 int bigmac_mfma_probe(int blocks, int iters, float *sink /*device*/, double *flops /*host*/, void *stream);
+
+/* Measurement aid: what the device moves for the access pattern of the combine kernels without
+ * any write in the mix, the ceiling their HBM fractions are set against.  Enqueues one kernel in
+ * the combine kernels' launch shape (a thread per group of 8 rows and 32 bytes of the row) that
+ * reads, for every m in [0, rows), all row_bytes bytes of row order[m] of `table` - 8 independent
+ * 32-byte loads per thread, `streaming` != 0: with the non-temporal hint - and stores nothing.
+ * table: device, rows * row_bytes bytes; order: device int32 [rows], a permutation of [0, rows)
+ * or any indices below rows; sink: device, one uint32, never written.  rows a multiple of 8,
+ * row_bytes a multiple of 32, rows * row_bytes < 2^40; else BIGMAC_ERR_INVALID_ARG.  The caller
+ * times the launch; it reads rows * row_bytes bytes. */
+int bigmac_gather_probe(const void *table, const int32_t *order, int64_t rows, int64_t row_bytes, int streaming,
+                        uint32_t *sink, void *stream);
 const char *bigmac_stage_name(int stage);
 
 #ifdef __cplusplus

@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.bigmac_set_stage_events.argtypes = [ctypes.POINTER(vp)]
         L.bigmac_stage_name.restype = ctypes.c_char_p
         L.bigmac_stage_name.argtypes = [ci]
+        L.bigmac_gather_probe.restype = ci
+        L.bigmac_gather_probe.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int64, ci, vp, vp]
         L.bigmac_mfma_probe.restype = ci
         L.bigmac_mfma_probe.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
         _lib = L
@@ -83,7 +85,7 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ("bigmac_workspace_bytes", "bigmac_status_string", "bigmac_forward_matrix_flops", "bigmac_permute_bytes",
            "bigmac_saved_layout", "bigmac_saved_aux_layout", "bigmac_aux_loss", "bigmac_route", "bigmac_dispatch", "bigmac_dispatch_static", "bigmac_grouped_ffn", "bigmac_combine",
            "bigmac_layer_forward", "bigmac_layer_backward", "bigmac_set_stage_events", "bigmac_stage_name",
-           "bigmac_mfma_probe")
+           "bigmac_mfma_probe", "bigmac_gather_probe")
 STAGE_COUNT = 22
 
 
@@ -184,6 +186,11 @@ def bigmac_grouped_ffn(dims, x_perm, expert_offsets, w1, w2, act_saved, o_perm, 
 def bigmac_combine(dims, o_perm, slot_of, topk_w, y_low, stream=None):
     _check(lib().bigmac_combine(ctypes.byref(dims), _ptr(o_perm), _ptr(slot_of), _ptr(topk_w), _ptr(y_low),
                                 _stream(stream)), "bigmac_combine")
+
+
+def bigmac_gather_probe(table, order, rows, row_bytes, streaming, sink, stream=None) -> None:
+    _check(lib().bigmac_gather_probe(_ptr(table), _ptr(order), int(rows), int(row_bytes), int(bool(streaming)), _ptr(sink), _stream(stream)),
+           "bigmac_gather_probe")
 
 
 def bigmac_mfma_probe(blocks, iters, sink, stream=None) -> float:

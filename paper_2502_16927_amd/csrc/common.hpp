@@ -223,6 +223,7 @@ size_t permutation_ws_bytes(int T, int k, int N);
 struct TileMapJobs;
 int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* topk_idx, int32_t* expert_offsets,
                              int32_t* slot_of, int32_t* src_of, void* ws, hipStream_t s, const TileMapJobs* tile_maps = nullptr);
+int launch_gather_probe(const void* table, const int32_t* order, long rows, long row_bytes, int streaming, unsigned* sink, hipStream_t s);
 int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, const int32_t* slot_of,
                          void* x_perm, hipStream_t s);
 enum CombineOut { COMBINE_F32 = 0, COMBINE_SPLIT_BF16 = 1 };  // fp32 [T,w]  |  bf16 [T,2w] = (hi | lo)

@@ -449,6 +449,13 @@ double bigmac_permute_bytes(const bigmac_dims* D) {
   return 4.0 * (double)D->T * D->k * widths(*D).win * esize(D->dtype);
 }
 
+int bigmac_gather_probe(const void* table, const int32_t* order, int64_t rows, int64_t row_bytes, int streaming, uint32_t* sink, void* stream) {
+  if (!table || !order || !sink || rows <= 0 || rows % 8 || row_bytes <= 0 || row_bytes % 32 || rows > (1ll << 31) - 8 || row_bytes > (1ll << 24) ||
+      rows * row_bytes >= (1ll << 40))
+    return BIGMAC_ERR_INVALID_ARG;
+  return launch_gather_probe(table, order, (long)rows, (long)row_bytes, streaming, sink, (hipStream_t)stream);
+}
+
 int bigmac_mfma_probe(int blocks, int iters, float* sink, double* flops, void* stream) {
   if (blocks <= 0 || blocks > 65536 || iters <= 0 || iters > (1 << 20) || !sink || !flops) return BIGMAC_ERR_INVALID_ARG;
   const double f = launch_mfma_probe(blocks, iters, sink, (hipStream_t)stream);

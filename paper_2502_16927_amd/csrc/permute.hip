@@ -535,6 +535,41 @@ int launch_build_permutation(int T, int k, int N, int capacity, const int32_t* t
   return BIGMAC_OK;
 }
 
+namespace {
+// read-only counterpart of combine_rows_kernel (see bigmac_gather_probe)
+template <bool STREAMING>
+__global__ __launch_bounds__(256) void gather_probe_kernel(const u32x4_t* __restrict__ table, const int32_t* __restrict__ order, long groups,
+                                                           int row16, unsigned* sink) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int per = row16 / 2;
+  if (g >= (size_t)groups * per) return;
+  const size_t grp = g / per;
+  const int c = (int)(g % per);
+  u32x4_t v[8][2];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const u32x4_t* p = table + (size_t)order[grp * 8 + u] * row16 + c * 2;
+    if (STREAMING) { v[u][0] = __builtin_nontemporal_load(p); v[u][1] = __builtin_nontemporal_load(p + 1); }
+    else { v[u][0] = p[0]; v[u][1] = p[1]; }
+  }
+  unsigned acc = 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) acc ^= v[u][0].x ^ v[u][1].w;
+  if (acc == 0x9e3779b9u && sink[0] == 0x7f4a7c15u) sink[0] = acc;   // (keeps the loads alive; rows of real data never meet both)
+}
+}  // namespace
+
+int launch_gather_probe(const void* table, const int32_t* order, long rows, long row_bytes, int streaming, unsigned* sink, hipStream_t s) {
+  const long groups = rows / 8;
+  const int row16 = (int)(row_bytes / 16);
+  const size_t n = (size_t)groups * (row16 / 2);
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (streaming) hipLaunchKernelGGL(gather_probe_kernel<true>, grid, block, 0, s, (const u32x4_t*)table, order, groups, row16, sink);
+  else hipLaunchKernelGGL(gather_probe_kernel<false>, grid, block, 0, s, (const u32x4_t*)table, order, groups, row16, sink);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
 int launch_dispatch_rows(int dtype, int T, int k, int width, const void* x_low, const int32_t* slot_of,
                          void* x_perm, hipStream_t s) {
   const int cpr = width * esize(dtype) / 16;

@@ -178,6 +178,22 @@ def test_bf16_output_is_the_rounded_fp32_output(oracle):
         assert torch.equal(a.grads[n], b.grads[n])
 
 
+def test_gather_probe_runs_and_rejects_bad_sizes():
+    """The measurement aid behind the permutes' ceiling: a read-only kernel, so all there is to check is
+    that it runs over the table it is given and that sizes it cannot take are refused before any launch."""
+    rows, row_bytes = 4096, 1024
+    table = torch.ones(rows * row_bytes // 4, dtype=torch.float32, device="cuda:0")
+    order = torch.randperm(rows, device="cuda:0").to(torch.int32)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for streaming in (0, 1):
+        B.bigmac_gather_probe(table, order, rows, row_bytes, streaming, sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0
+    for bad_rows, bad_bytes in ((rows + 4, row_bytes), (rows, row_bytes + 16), (0, row_bytes), (rows, 0)):
+        with pytest.raises(RuntimeError):
+            B.bigmac_gather_probe(table, order, bad_rows, bad_bytes, 0, sink)
+
+
 def test_run_to_run_determinism():
     wl = synth.small(T=700, d=256, r=128, N=16, k=4, h=256, zipf_s=1.2)
     data = synth.generate(wl)
