@@ -141,8 +141,60 @@ __device__ inline void build_tile_map_block(const int* offsets, int groups, int 
   }
   __syncthreads();
   const bool balanced = worst_run * 64 > total * 9;
+  // Skewed routing.  Runs of *whole* groups are preferred to runs of equal cost: all tiles of a
+  // group cost the same, so with whole groups the workgroups of an XCD move from group to group
+  // together and read the group's operand panels through the L2 once, while a run that starts
+  // inside a group puts two groups of different cost into every round of the stride, the
+  // workgroups drift apart for the rest of the launch and re-read the panels from memory
+  // (measured on zipf_stress: the two weight-gradient products 1.31 -> 1.19 ms and 1.30 -> 1.24 ms
+  // although the fullest run is then 1.12 times the average).  The smallest cap for which eight
+  // runs of whole groups, each at most the cap, cover all groups is found by bisection (a run's
+  // end by bisection in the inclusive sums); the cut is used when that cap is within 1.2 times
+  // the average share.
+  __shared__ int whole_cut[9];
+  __shared__ int whole_ok;
+  __shared__ int largest_cost;
+  if (g == 0) largest_cost = 0;
+  __syncthreads();
+  if (cost > 0) atomicMax(&largest_cost, cost);
+  __syncthreads();
+  if (g == 0) {
+    auto run_end = [&](int i, long long cap) {        // largest j with cost of groups [i, j) <= cap
+      const long long base = i ? incl[i - 1] : 0;
+      int lo = i, hi = groups;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (incl[mid - 1] - base <= cap) lo = mid;
+        else hi = mid - 1;
+      }
+      return lo;
+    };
+    auto fits = [&](long long cap) {
+      int i = 0;
+      for (int x = 0; x < 8 && i < groups; ++x) i = run_end(i, cap);
+      return i >= groups;
+    };
+    long long lo = largest_cost > total / 8 ? largest_cost : total / 8, hi = total;
+    while (lo < hi) {
+      const long long mid = (lo + hi) >> 1;
+      if (fits(mid)) hi = mid;
+      else lo = mid + 1;
+    }
+    int i = 0;
+    whole_cut[0] = 0;
+    for (int x = 1; x <= 8; ++x) {
+      i = i < groups ? run_end(i, lo) : groups;
+      whole_cut[x] = x == 8 ? groups : i;
+    }
+    whole_ok = lo * 40 <= total * 6;                  // cap <= 1.2 x total / 8
+  }
+  __syncthreads();
 #pragma unroll 1
   for (int x = 0; x <= 8; ++x) {
+    if (balanced && whole_ok) {
+      if (g == 0) tile_map[1 + x] = whole_cut[x] << 16;
+      continue;
+    }
     if (!balanced) {
       if (g == 0) tile_map[1 + x] = (int)(((long long)groups * x << 16) / 8);
       continue;
