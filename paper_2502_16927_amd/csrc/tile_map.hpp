@@ -147,10 +147,11 @@ __device__ inline void build_tile_map_block(const int* offsets, int groups, int 
   // inside a group puts two groups of different cost into every round of the stride, the
   // workgroups drift apart for the rest of the launch and re-read the panels from memory
   // (measured on zipf_stress: the two weight-gradient products 1.31 -> 1.19 ms and 1.30 -> 1.24 ms
-  // although the fullest run is then 1.12 times the average).  The smallest cap for which eight
-  // runs of whole groups, each at most the cap, cover all groups is found by bisection (a run's
-  // end by bisection in the inclusive sums); the cut is used when that cap is within 1.2 times
-  // the average share.
+  // although the fullest run is then 1.12 times the average).  64 candidate caps between the
+  // even share and 1.2 times it are tried at once, one per lane of the first wavefront (greedy
+  // runs of whole groups, each at most the cap, a run's end found by bisection in the inclusive
+  // sums); the smallest cap whose eight runs cover all groups gives the cut, and if none does
+  // the cut of equal cost stays.
   __shared__ int whole_cut[9];
   __shared__ int whole_ok;
   __shared__ int largest_cost;
@@ -158,7 +159,9 @@ __device__ inline void build_tile_map_block(const int* offsets, int groups, int 
   __syncthreads();
   if (cost > 0) atomicMax(&largest_cost, cost);
   __syncthreads();
-  if (g == 0) {
+  if (g == 0) whole_ok = 0;
+  __syncthreads();
+  if (g < 64) {   // the first wavefront: 64 candidate caps between the even share and 1.2 times it, one per lane
     auto run_end = [&](int i, long long cap) {        // largest j with cost of groups [i, j) <= cap
       const long long base = i ? incl[i - 1] : 0;
       int lo = i, hi = groups;
@@ -169,24 +172,24 @@ __device__ inline void build_tile_map_block(const int* offsets, int groups, int 
       }
       return lo;
     };
-    auto fits = [&](long long cap) {
-      int i = 0;
-      for (int x = 0; x < 8 && i < groups; ++x) i = run_end(i, cap);
-      return i >= groups;
-    };
-    long long lo = largest_cost > total / 8 ? largest_cost : total / 8, hi = total;
-    while (lo < hi) {
-      const long long mid = (lo + hi) >> 1;
-      if (fits(mid)) hi = mid;
-      else lo = mid + 1;
-    }
+    const long long share = (total + 7) / 8;
+    const long long lo = largest_cost > share ? largest_cost : share, hi = total * 6 / 40;   // 1.2 x total / 8
+    const long long cap = lo + (hi > lo ? (hi - lo) * g / 63 : 0);
+    int cut[9];
+    cut[0] = 0;
     int i = 0;
-    whole_cut[0] = 0;
+#pragma unroll
     for (int x = 1; x <= 8; ++x) {
-      i = i < groups ? run_end(i, lo) : groups;
-      whole_cut[x] = x == 8 ? groups : i;
+      i = i < groups ? run_end(i, cap) : groups;
+      cut[x] = i;
     }
-    whole_ok = lo * 40 <= total * 6;                  // cap <= 1.2 x total / 8
+    const bool fits = hi >= lo && i >= groups;
+    const unsigned long long mask = __ballot(fits);
+    if (mask && g == __builtin_ctzll(mask)) {          // the smallest cap that fits
+#pragma unroll
+      for (int x = 0; x <= 8; ++x) whole_cut[x] = x == 8 ? groups : cut[x];
+      whole_ok = 1;
+    }
   }
   __syncthreads();
 #pragma unroll 1
