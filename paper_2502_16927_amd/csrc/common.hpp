@@ -175,9 +175,10 @@ struct ClaimScope {
 // Rows per M tile of the ragged-M schedule for this dtype (the tile map must be built with it).
 int gemm_ragged_tile_rows(int dtype, int tall_tile);
 int launch_gemm(const GemmDesc& g, hipStream_t s);
-// tile_map capacity in int32 for a ragged-M problem
+// tile_map capacity in int32 for a ragged-M problem: header, the group order of the ragged-K
+// schedule (one int per group), then a (group, first row) pair per M tile
 inline size_t tile_map_ints(int total_rows, int groups, int tile_rows) {
-  return 16 + 2 * ((size_t)total_rows / tile_rows + groups + 1);
+  return 16 + (size_t)groups + 2 * ((size_t)total_rows / tile_rows + groups + 1);
 }
 double launch_mfma_probe(int blocks, int iters, float* sink, hipStream_t s);   // returns the flops issued, < 0 on a launch error
 int launch_build_tile_map(const int* offsets, int groups, int tile_rows, int* tile_map, hipStream_t s);

@@ -119,10 +119,12 @@ struct TileClaim {
 // Ragged-K problems (one output matrix per group, contraction over that group's rows): a tile of
 // a group with many rows costs many k tiles, one of a small group almost none, so equal tile
 // counts per XCD can leave one XCD with a multiple of the average work (skewed routing).  The
-// tile map therefore carries nine split points that cut the group sequence into eight runs of
-// equal cost (cost of a group = its k tiles + a constant for set-up and epilogue, see
-// build_tile_map_kernel), each as group * 65536 + 16-bit fraction of that group; every group has
-// the same number of tiles, so a split point turns into a tile index for any tile shape.
+// tile map therefore carries an order of the groups and nine split points that cut that sequence
+// into eight runs of equal cost (cost of a group = its k tiles + a constant for set-up and
+// epilogue, see build_tile_map_block), each as position * 65536 + 16-bit fraction of the group at
+// that position; every group has the same number of tiles, so a split point turns into a tile
+// index for any tile shape.  Under skew the order puts the groups of one XCD next to each other
+// (whole groups, dealt out largest first to the least loaded XCD) and the fractions are zero.
 static_assert(TILE_MAP_K_ROWS == BIGMAC_TILE_BK, "the tile map prices groups in k tiles of the square tile");
 __device__ __forceinline__ void balance_ragged_k(const GemmDesc& p, TileSpace& ts) {
   const int tiles_per_group = ts.gx * ts.gy;
@@ -147,19 +149,21 @@ __device__ __forceinline__ TileCoord resolve_tile(const GemmDesc& p, const TileS
   t.valid = true;
   t.n0 = bx * BN;
   if (p.mode == GEMM_RAGGED_M) {
-    int g = table_at(p.tile_map, TILE_MAP_HEADER + 2 * by);
-    t.m0 = table_at(p.tile_map, TILE_MAP_HEADER + 1 + 2 * by);
+    int g = table_at(p.tile_map, TILE_MAP_HEADER + p.groups + 2 * by);
+    t.m0 = table_at(p.tile_map, TILE_MAP_HEADER + p.groups + 1 + 2 * by);
     t.m_end = table_at(p.offsets, g + 1);
     t.kbeg = 0;
     t.kend = p.K;
     t.B = (const char*)p.B + (size_t)g * p.gstride_b * esz;
     if (p.bias) t.bias = (const char*)p.bias + (size_t)g * p.gstride_bias * esz;
   } else if (p.mode == GEMM_RAGGED_K) {
+    // with a tile map the groups are walked in the map's order (see balance_ragged_k)
+    const int grp = p.tile_map ? table_at(p.tile_map, TILE_MAP_HEADER + bz) : bz;
     t.m0 = by * BM;
     t.m_end = p.M;
-    t.kbeg = table_at(p.offsets, bz);
-    t.kend = table_at(p.offsets, bz + 1);
-    t.C = (char*)p.C + (size_t)bz * p.gstride_c * sizeof(float);
+    t.kbeg = table_at(p.offsets, grp);
+    t.kend = table_at(p.offsets, grp + 1);
+    t.C = (char*)p.C + (size_t)grp * p.gstride_c * sizeof(float);
   } else {
     t.m0 = by * BM;
     t.m_end = p.M;

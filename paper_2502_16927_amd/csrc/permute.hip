@@ -110,9 +110,8 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ c
     }
   }
   __syncthreads();
-#pragma unroll 1
-  for (int m = 0; m < 2; ++m)
-    if (maps.map[m]) build_tile_map_block(first_slot, N, maps.tile_rows[m], maps.map[m]);
+  if (maps.map[0]) build_tile_map_block(first_slot, N, maps.tile_rows[0], maps.map[0]);
+  if (maps.map[1]) build_tile_map_block(first_slot, N, maps.tile_rows[1], maps.map[1], maps.map[0]);
 }
 
 // One wavefront per chunk walks its pairs in flat order, 64 at a time (all read up front).  A
@@ -229,9 +228,8 @@ __global__ __launch_bounds__(1024) void perm_small_kernel(const int32_t* __restr
       }
     }
   }
-#pragma unroll 1
-  for (int m = 0; m < 2; ++m)
-    if (maps.map[m]) build_tile_map_block(first_slot, N, maps.tile_rows[m], maps.map[m]);
+  if (maps.map[0]) build_tile_map_block(first_slot, N, maps.tile_rows[0], maps.map[0]);
+  if (maps.map[1]) build_tile_map_block(first_slot, N, maps.tile_rows[1], maps.map[1], maps.map[0]);
 }
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));

@@ -6,7 +6,8 @@
 
 namespace bigmac {
 
-constexpr int TILE_MAP_HEADER = 16;   // ints in front of the (group, first row) pairs: [0] tile count, [1..9] split points
+constexpr int TILE_MAP_HEADER = 16;   // ints in front of the group order: [0] tile count, [1..9] split points of the ragged-K schedule;
+                                      // then `groups` ints of group order (positions -> groups), then the (group, first row) pairs
 constexpr int TILE_MAP_K_ROWS = 32;   // rows per k tile in the cost of a group (the square tile's depth)
 
 struct TileMapJobs {   // up to two maps (different tile heights) from one set of offsets; map == NULL: none
@@ -16,7 +17,7 @@ struct TileMapJobs {   // up to two maps (different tile heights) from one set o
 
 // The map for at most 64 groups by one wavefront (lane = group): shuffles take the place of the
 // LDS arrays of the general form below, which it follows step by step.
-__device__ inline void build_tile_map_wave(const int* offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
+__device__ __forceinline__ void build_tile_map_wave(const int* offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
   const int g = threadIdx.x & 63;
   int beg = 0, rows = 0, cnt = 0;
   if (g < groups) {
@@ -35,9 +36,10 @@ __device__ inline void build_tile_map_wave(const int* offsets, int groups, int t
   const int last_tile = inclusive_scan(cnt);
   const int first = last_tile - cnt;
   for (int i = 0; i < cnt; ++i) {
-    tile_map[TILE_MAP_HEADER + 2 * (first + i)] = g;
-    tile_map[TILE_MAP_HEADER + 1 + 2 * (first + i)] = beg + i * tile_rows;
+    tile_map[TILE_MAP_HEADER + groups + 2 * (first + i)] = g;
+    tile_map[TILE_MAP_HEADER + groups + 1 + 2 * (first + i)] = beg + i * tile_rows;
   }
+  if (g < groups) tile_map[TILE_MAP_HEADER + g] = g;   // ragged-K schedule: the groups in their own order
   if (g == 63) tile_map[0] = last_tile;
   const int cost = g < groups ? (rows + TILE_MAP_K_ROWS - 1) / TILE_MAP_K_ROWS + 8 : 0;
   const int upto = inclusive_scan(cost);
@@ -79,7 +81,15 @@ __device__ inline void build_tile_map_wave(const int* offsets, int groups, int t
 // schedule (see balance_ragged_k), then from TILE_MAP_HEADER on (group, first row) per M tile,
 // groups in order.  Called by all 1024 threads of a workgroup, one thread per group; offsets may
 // lie in the LDS.
-__device__ inline void build_tile_map_block(const int* offsets, int groups, int tile_rows, int* __restrict__ tile_map) {
+// schedule_from: a map built before this one by the same workgroup from the same offsets; its
+// ragged-K schedule (split points and group order do not depend on the tile height) is copied
+// instead of being worked out again.
+// Forced inline, like every device function of this library: left to the compiler, the second
+// call site turned this into a real call (stack pointer, scratch, LDS of the callee in a
+// module-wide block), and the one-workgroup counting sort that calls it then lost the counters
+// of whole wavefronts from run to run; inlined, the same source is deterministic.
+__device__ __forceinline__ void build_tile_map_block(const int* offsets, int groups, int tile_rows, int* __restrict__ tile_map,
+                                            const int* schedule_from = nullptr) {
   if (groups <= 64) {                // one wavefront holds every group: the same steps without LDS or barriers
     if (threadIdx.x < 64) build_tile_map_wave(offsets, groups, tile_rows, tile_map);
     return;
@@ -111,10 +121,16 @@ __device__ inline void build_tile_map_block(const int* offsets, int groups, int 
   const int last_tile = inclusive_scan(cnt);
   const int first = last_tile - cnt;
   for (int i = 0; i < cnt; ++i) {
-    tile_map[TILE_MAP_HEADER + 2 * (first + i)] = g;
-    tile_map[TILE_MAP_HEADER + 1 + 2 * (first + i)] = beg + i * tile_rows;
+    tile_map[TILE_MAP_HEADER + groups + 2 * (first + i)] = g;
+    tile_map[TILE_MAP_HEADER + groups + 1 + 2 * (first + i)] = beg + i * tile_rows;
   }
   if (g == 1023) tile_map[0] = last_tile;
+  if (schedule_from) {
+    __syncthreads();                 // the other map's entries were written by this workgroup
+    if (g < 9) tile_map[1 + g] = schedule_from[1 + g];
+    if (g < groups) tile_map[TILE_MAP_HEADER + g] = schedule_from[TILE_MAP_HEADER + g];
+    return;
+  }
   // split points: cost of a group = its k tiles + 8 (set-up and epilogue of a tile, in k tiles)
   __shared__ int cost_of[1024];
   __shared__ int incl[1024];
@@ -146,56 +162,83 @@ __device__ inline void build_tile_map_block(const int* offsets, int groups, int 
   // together and read the group's operand panels through the L2 once, while a run that starts
   // inside a group puts two groups of different cost into every round of the stride, the
   // workgroups drift apart for the rest of the launch and re-read the panels from memory
-  // (measured on zipf_stress: the two weight-gradient products 1.31 -> 1.19 ms and 1.30 -> 1.24 ms
-  // although the fullest run is then 1.12 times the average).  64 candidate caps between the
-  // even share and 1.2 times it are tried at once, one per lane of the first wavefront (greedy
-  // runs of whole groups, each at most the cap, a run's end found by bisection in the inclusive
-  // sums); the smallest cap whose eight runs cover all groups gives the cut, and if none does
-  // the cut of equal cost stays.
-  __shared__ int whole_cut[9];
+  // (measured on zipf_stress: the two weight-gradient products 1.31 -> 1.07 ms and 1.30 -> 1.12
+  // ms).  The groups are dealt out largest first, each to the XCD with the least cost so
+  // far; the map's group order lists the groups XCD by XCD, each XCD's largest first, and the
+  // split points are the XCDs' first positions.  Used when the fullest XCD stays within 1.2
+  // times the even share (one group that outweighs an eighth of the work does not); else the
+  // groups keep their own order and the cut of equal cost.
+  // (16-bit entries: the counting sort's one-workgroup kernels call this with 40 KB of LDS of
+  // their own, and a kernel's static LDS ends at 64 KB)
+  __shared__ unsigned short by_cost[1024];      // groups, largest cost first (ties: lower index first)
+  __shared__ unsigned short xcd_of[1024], place_in_xcd[1024];
+  __shared__ int xcd_first[9];
   __shared__ int whole_ok;
-  __shared__ int largest_cost;
-  if (g == 0) largest_cost = 0;
-  __syncthreads();
-  if (cost > 0) atomicMax(&largest_cost, cost);
-  __syncthreads();
+  if (g < groups) {
+    int rank = 0;
+    for (int o = 0; o < groups; ++o) {
+      const int co = cost_of[o];
+      rank += (co > cost || (co == cost && o < g)) ? 1 : 0;
+    }
+    by_cost[rank] = (unsigned short)g;
+  }
   if (g == 0) whole_ok = 0;
   __syncthreads();
-  if (g < 64) {   // the first wavefront: 64 candidate caps between the even share and 1.2 times it, one per lane
-    auto run_end = [&](int i, long long cap) {        // largest j with cost of groups [i, j) <= cap
-      const long long base = i ? incl[i - 1] : 0;
-      int lo = i, hi = groups;
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (incl[mid - 1] - base <= cap) lo = mid;
-        else hi = mid - 1;
+  if (balanced && g < 64) {
+    // the first wavefront: lane x < 8 keeps XCD x's cost and count; a step finds the least loaded
+    // XCD by a minimum over (cost * 8 + x) across the eight lanes
+    unsigned load = 0;
+    int count = 0;
+    const int lane8 = g & 7;
+    for (int r0 = 0; r0 < groups; r0 += 8) {
+      int grp[8], c[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {                   // eight independent reads, then eight dependent steps
+        grp[u] = by_cost[r0 + u < groups ? r0 + u : groups - 1];
+        c[u] = cost_of[grp[u]];
       }
-      return lo;
-    };
-    const long long share = (total + 7) / 8;
-    const long long lo = largest_cost > share ? largest_cost : share, hi = total * 6 / 40;   // 1.2 x total / 8
-    const long long cap = lo + (hi > lo ? (hi - lo) * g / 63 : 0);
-    int cut[9];
-    cut[0] = 0;
-    int i = 0;
 #pragma unroll
-    for (int x = 1; x <= 8; ++x) {
-      i = i < groups ? run_end(i, cap) : groups;
-      cut[x] = i;
+      for (int u = 0; u < 8; ++u) {
+        if (r0 + u >= groups) break;
+        unsigned key = (load << 3) | (unsigned)lane8;
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) {
+          const unsigned o = (unsigned)__shfl_xor((int)key, off, 64);
+          key = o < key ? o : key;
+        }
+        const int best = (int)(key & 7u);
+        if (lane8 == best) {
+          if (g < 8) {
+            xcd_of[grp[u]] = (unsigned short)best;
+            place_in_xcd[grp[u]] = (unsigned short)count;
+          }
+          load += (unsigned)c[u];
+          ++count;
+        }
+      }
     }
-    const bool fits = hi >= lo && i >= groups;
-    const unsigned long long mask = __ballot(fits);
-    if (mask && g == __builtin_ctzll(mask)) {          // the smallest cap that fits
+    // fullest XCD and the first position of each
+    unsigned fullest = load;
+    int before = count;
 #pragma unroll
-      for (int x = 0; x <= 8; ++x) whole_cut[x] = x == 8 ? groups : cut[x];
-      whole_ok = 1;
+    for (int off = 1; off < 8; off <<= 1) {
+      const unsigned o = (unsigned)__shfl_xor((int)fullest, off, 64);
+      fullest = o > fullest ? o : fullest;
+      const int b = __shfl_up(before, off, 64);       // inclusive scan of the counts over lanes 0..7
+      if (lane8 >= off) before += b;
+    }
+    if (g < 8) xcd_first[g] = before - count;
+    if (g == 0) {
+      xcd_first[8] = groups;
+      whole_ok = (long long)fullest * 40 <= total * 6;   // <= 1.2 x total / 8
     }
   }
   __syncthreads();
+  if (g < groups) tile_map[TILE_MAP_HEADER + (whole_ok ? xcd_first[xcd_of[g]] + place_in_xcd[g] : g)] = g;
 #pragma unroll 1
   for (int x = 0; x <= 8; ++x) {
-    if (balanced && whole_ok) {
-      if (g == 0) tile_map[1 + x] = whole_cut[x] << 16;
+    if (whole_ok) {
+      if (g == 0) tile_map[1 + x] = xcd_first[x] << 16;
       continue;
     }
     if (!balanced) {
