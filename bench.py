@@ -126,6 +126,8 @@ def main():
     ap.add_argument("--wire-bf16", action="store_true",
                     help="all-bf16 wire format (BIGMAC_FLAG_WIRE_BF16): expert outputs and the gradient of the dispatched "
                          "rows in bf16 instead of fp32; less permute traffic, y and dx no longer within 2e-2 at the widest shapes")
+    ap.add_argument("--out-bf16", action="store_true",
+                    help="y and dx in bf16 (BIGMAC_FLAG_OUT_BF16) instead of fp32: half the bytes of the two [T, d] results")
     ap.add_argument("--tiles", default="auto", choices=["auto", "large", "small"],
                     help="tuning: force the 256 x 256 workgroup tiles on every expert product that can take them, or forbid them")
     ap.add_argument("--tokens", type=int, default=0, help="override T (decode sweep)")
@@ -256,9 +258,9 @@ def main():
     data = synth.generate(wl)
     capacity = B.expert_capacity(wl.T, wl.k, wl.N, args.capacity_factor) if args.capacity_factor > 0 else 0
     tile_flag = {"auto": 0, "large": B.FLAG_TILES_LARGE, "small": B.FLAG_TILES_SMALL}[args.tiles]
-    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA, flags=(B.FLAG_WIRE_BF16 if args.wire_bf16 else 0) | tile_flag | (B.FLAG_NO_FUSED_DISPATCH if args.no_fused_dispatch else 0),
+    dims = B.dims_of(wl, B.ORDER_CDAC if cdac else B.ORDER_DCCA, flags=(B.FLAG_WIRE_BF16 if args.wire_bf16 else 0) | (B.FLAG_OUT_BF16 if args.out_bf16 else 0) | tile_flag | (B.FLAG_NO_FUSED_DISPATCH if args.no_fused_dispatch else 0),
                      capacity=capacity, aux_alpha=args.aux_alpha)
-    variant = capacity > 0 or args.aux_alpha > 0 or args.wire_bf16 or args.forward_only or args.no_fused_dispatch   # not the headline configuration
+    variant = capacity > 0 or args.aux_alpha > 0 or args.wire_bf16 or args.out_bf16 or args.forward_only or args.no_fused_dispatch   # not the headline configuration
     x = B.to_device(data["x"], wl.dtype, dev)
     dy = B.to_device(data.get("dy"), wl.dtype, dev)
     wg = B.to_device(data["w_gate"], B.F32, dev)
@@ -374,7 +376,7 @@ def main():
                    "h": wl.h, "pass": "fwd+bwd" if training else "fwd",
                    **({"capacity_factor": args.capacity_factor, "capacity": capacity} if capacity else {}),
                    **({"aux_alpha": args.aux_alpha} if args.aux_alpha > 0 else {}),
-                   **({"wire": "bf16"} if args.wire_bf16 else {}), **({"tiles": args.tiles} if args.tiles != "auto" else {}),
+                   **({"wire": "bf16"} if args.wire_bf16 else {}), **({"out": "bf16"} if args.out_bf16 else {}), **({"tiles": args.tiles} if args.tiles != "auto" else {}),
                    **({"dispatch": "separate kernel"} if args.no_fused_dispatch else {})},
         "timed": timed,
         **({"block_ms_per_step": [round(v, 4) for v in block_ms], "block_ms_median": round(sorted(block_ms)[len(block_ms) // 2], 4),

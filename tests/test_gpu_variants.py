@@ -305,3 +305,54 @@ def test_skewed_mid_size_all_weight_gradients(oracle):
     eff = effective_rows(idx, gate, wl.N)
     print("effective rows", np.round(eff), flush=True)
     print(check_weight_grads({n: host(t) for n, t in layer.grads.items()}, g_ref, eff, TOL, skewed=True), flush=True)
+
+
+def _ragged_k_regime(counts: np.ndarray) -> str:
+    """Which schedule the weight-gradient products take for these rows per expert, restated from
+    the builder's rule: a group costs its 32-row k tiles + 8; eight equal runs of groups are kept
+    while the fullest stays within 9/8 of the even share; else whole groups are dealt to the XCDs
+    largest first if the fullest XCD then stays within 1.2 of the share; else a cut of equal cost
+    that splits groups."""
+    cost = (counts + 31) // 32 + 8
+    total, n = int(cost.sum()), len(counts)
+    incl = np.cumsum(cost)
+
+    def before(q):
+        gi = q >> 16
+        return total if gi >= n else int(incl[gi] - cost[gi]) + (((q & 0xFFFF) * int(cost[gi])) >> 16)
+
+    worst = max(before((n * (x + 1) << 16) // 8) - before((n * x << 16) // 8) for x in range(8))
+    if worst * 64 <= total * 9:
+        return "equal runs"
+    load = [0] * 8
+    for g in sorted(range(n), key=lambda g: (-cost[g], g)):
+        b = min(range(8), key=lambda x: (load[x], x))
+        load[b] += int(cost[g])
+    return "whole groups" if max(load) * 40 <= total * 6 else "split groups"
+
+
+@pytest.mark.parametrize("T,regime", [(8192, "whole groups"), (16384, "split groups")])
+def test_skewed_many_experts_all_weight_gradients(oracle, T, regime):
+    """128 experts under Zipf routing at sizes the oracle redoes in full: more groups than one
+    wavefront holds (the tile maps come from the workgroup-wide builder) and both schedules of the
+    skewed ragged-K products, each group's gradient block checked against the oracle."""
+    wl = synth.small(T=T, d=128, r=64, N=128, k=4, h=128, zipf_s=1.2)
+    data = synth.generate(wl)
+    idx, gate, _ = oracle.route(data["x"], data["w_gate"], data["gate_bias"], wl.k)
+    counts = np.bincount(idx.ravel(), minlength=wl.N)
+    assert _ragged_k_regime(counts) == regime
+    layer = DeviceLayer(wl, data)
+    y = host(layer.forward(training=True))
+    layer.alloc_grads()
+    layer.backward()
+    torch.cuda.synchronize()
+    v = layer.saved_views()
+    assert np.array_equal(v["topk_idx"], idx)
+    r_off, r_slot, _ = oracle.permutation(idx, wl.N)
+    assert np.array_equal(v["expert_offsets"], r_off) and np.array_equal(v["slot_of"], r_slot)
+    args = (data["w_gate"], data["gate_bias"], data["w_down"], data["w_up"], data["w1"], data["w2"], wl.k)
+    assert rel_err(y, oracle.bigmac_forward(data["x"], *args)) < TOL
+    g_ref = oracle.bigmac_backward(data["x"], data["dy"], *args)
+    assert rel_err(host(layer.dx), g_ref["dx"]) < TOL
+    eff = effective_rows(idx, gate, wl.N)
+    print(check_weight_grads({n: host(t) for n, t in layer.grads.items()}, g_ref, eff, TOL, skewed=True), flush=True)
