@@ -70,10 +70,13 @@ enum {
                                   names both inputs): w_gate and d_w_gate are [r, N], the logits are those of
                                   bigmac_route on the stored x' (dtype) with d = r, and the gate's gradient
                                   reaches x through x' (and so W_down).  A fourth of the router's work.   */
-  BIGMAC_FLAG_NO_FUSED_DISPATCH = 64  /* forward-only layer calls with dtype BF16 read the expert-up product's
-                                  rows straight from x' (x in the CDAC order) through src_of and write no
-                                  permuted copy; with this flag they dispatch first, as a training forward
-                                  does.  Same results bit for bit (tests and measurements).               */
+  BIGMAC_FLAG_NO_FUSED_DISPATCH = 64  /* layer calls with dtype BF16 fold the dispatch step into a product:
+                                  forward-only calls read the expert-up product's rows straight from x' (x
+                                  in the CDAC order) through src_of and write no permuted copy; a DCCA
+                                  training forward whose router reads x has the descending projection write
+                                  each row of x' into the places of its pairs in the permuted copy.  With
+                                  this flag the rows are dispatched by the copy kernel of bigmac_dispatch
+                                  instead.  Same results bit for bit (tests and measurements).           */
 };
 
 enum {

@@ -157,6 +157,9 @@ struct GemmDesc {
   int big_tile;              // bf16: 256 x 256 outputs by eight wavefronts, one workgroup per CU (ragged-M: tile map of 256-row tiles)
   const int* gather;         // ragged-M MFMA kernels with a k-contiguous A, GELU or store epilogue: row m of the product is row gather[m] / gather_div of A (device [max_rows]); NULL: A holds the rows in order
   int gather_rows, gather_div; //   rows of A behind the index; the index is divided by gather_div first (flat (row, pick) pairs)
+  const int* scatter;        // dense bf16 products with a k-contiguous A, B not k-contiguous, plain bf16 store: row m of the product is
+                             //   written to the rows scatter[m * scatter_k + j], j < scatter_k, of C (negative: no row); NULL: row m of C
+  int scatter_k, scatter_rows; //   copies per row; rows of C behind the index
   unsigned* claim;           // MFMA kernels, optional: zeroed tile counters of this launch (ClaimScope hands them out; see tile order in gemm_core.hpp)
   const void* touch;         // MFMA kernels, optional: a region (device) every line of which is read once as the kernel starts,
   size_t touch_bytes;        //   so that its first use in a k loop meets the caches and not the memory (0 = off)

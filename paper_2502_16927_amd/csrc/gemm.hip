@@ -20,7 +20,8 @@ namespace bigmac {
 // happen are pushed out of their buffer's range instead of being branched around): the number of
 // instructions in flight behind any load is then a compile-time constant, which is what the
 // counter waits below and the compiler's own ones are derived from.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32, int NS = BIGMAC_TILE_STAGES, bool GATHER = false>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool AK, bool BKC, int EPI, bool OUTF32, int NS = BIGMAC_TILE_STAGES, bool GATHER = false,
+          bool SCATTER = false>
 __global__ __launch_bounds__(64 * WAVES_M* WAVES_N)
     __attribute__((amdgpu_waves_per_eu(BM > BIGMAC_TILE_BM || BK > BIGMAC_TILE_BK ? BIGMAC_TALL_BLOCKS_PER_CU : BIGMAC_BLOCKS_PER_CU)))   // (eight wavefronts, one block per CU: also 2)
 void mfma_gemm_kernel(GemmDesc p) {
@@ -74,6 +75,11 @@ void mfma_gemm_kernel(GemmDesc p) {
   // (an index beyond the table's range arrives as zero): finite values that only reach output rows
   // the epilogue does not store.
   static_assert(!GATHER || AK, "gathered rows are k-contiguous rows of A");
+  // SCATTER (dense product, plain bf16 store): row m of the result goes to the rows
+  // scatter[m * scatter_k + j] of C instead of row m: the shared descending projection writes
+  // each token's narrow row straight into the places of its (token, pick) pairs in the permuted
+  // copy, and the dispatch step (a read of x' and the same writes) is gone.
+  static_assert(!SCATTER || (EPI == EPI_STORE && !OUTF32), "scattered rows leave through the bf16 store epilogue");
   int gather_row[GATHER ? MoveA::NCH : 1];
   unsigned gather_col[GATHER ? MoveA::NCH : 1], gather_idx[GATHER ? MoveA::NCH : 1];
   if (GATHER) {
@@ -456,6 +462,40 @@ void mfma_gemm_kernel(GemmDesc p) {
         for (int q = 0; q < 4; ++q)
           __builtin_amdgcn_raw_buffer_store_b128(v[q], dst, out_off + (unsigned)(i * 4 + q) * pass_step, 0, STREAMING);
       };
+      // SCATTER: the staged rows of a sub-tile leave once per pick.  The slots of the lane's four rows
+      // are read eight picks at a time (the loads are younger than the next tile's prefetch: by the
+      // time they answer, that has landed); a row past M, a pick past scatter_k and a negative slot
+      // (a dropped pair) turn the store's offset out of range by arithmetic, not by a branch.
+      auto flush_scattered = [&](int i) {
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)p.scatter, 0, p.M * p.scatter_k * 4, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(p.C, 0, (int)((size_t)p.scatter_rows * p.ldc * 2), 0x00020000);
+        const unsigned col_off = (unsigned)out_col * 2u | ((unsigned)(p.N - 1 - out_col) >> 31) * OUT_OF_RANGE;
+        const unsigned row_bytes = (unsigned)(p.ldc * 2);
+        u32x4_t v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lds_read_b128(row_at(q), v[q]);
+        lds_wait(v);
+        for (int j0 = 0; j0 < p.scatter_k; j0 += 8) {
+          int slot[4][8];
+          unsigned dead[4][8];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int row = t.m0 + wm + i * 32 + q * 8 + (lane >> 3);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              dead[q][j] = ((unsigned)(t.m_end - 1 - row) >> 31) | ((unsigned)(p.scatter_k - 1 - (j0 + j)) >> 31);
+              slot[q][j] = (int)__builtin_amdgcn_raw_buffer_load_b32(rs, (unsigned)((row * p.scatter_k + j0 + j) * 4) | dead[q][j] * OUT_OF_RANGE, 0, 0);
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              const unsigned gone = dead[q][j] | ((unsigned)slot[q][j] >> 31);
+              __builtin_amdgcn_raw_buffer_store_b128(v[q], rd, ((unsigned)slot[q][j] * row_bytes + col_off) | gone * OUT_OF_RANGE, 0, 0);
+            }
+        }
+      };
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         if (EPI == EPI_DGELU && HALVES == 2 && i == TMH) {
@@ -496,7 +536,8 @@ void mfma_gemm_kernel(GemmDesc p) {
             w.y = f2bf_pair(v[2], v[3]);
             lds_write_b64(quad_at(j, vq), w);
           }
-        flush_rows(rc, i);
+        if (SCATTER) flush_scattered(i);
+        else flush_rows(rc, i);
       }
     }
     BIGMAC_TRACE_AT(cur_id, 3);
@@ -692,6 +733,11 @@ int launch_mfma(const GemmDesc& g, hipStream_t s) {
 #define BIGMAC_MFMA(EPI, OUTF32) \
   hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI, OUTF32>), grid, block, 0, s, g)
   if constexpr (AK && !BKC) {
+    if (g.scatter) {  // scattered rows: the descending projection's plain bf16 store
+      hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI_STORE, false, BIGMAC_TILE_STAGES, false, true>), grid, block, 0, s, g);
+      BIGMAC_CHECK_LAUNCH();
+      return BIGMAC_OK;
+    }
     if (g.gather) {   // gathered rows: the two epilogues of the expert-up product
       if (g.epilogue == EPI_GELU)
         hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, WMs, WNs, AK, BKC, EPI_GELU, false, BIGMAC_TILE_STAGES, true>), grid, block, 0, s, g);
@@ -898,6 +944,12 @@ int launch_gemm(const GemmDesc& desc, hipStream_t s) {
   if (g.gather) {   // see the kernel: ragged-M rows of a k-contiguous A through an index, B not k-contiguous
     if (g.dtype != BIGMAC_BF16 || g.mode != GEMM_RAGGED_M || combo != 2 || g.wide_k || g.deep_tile || g.gather_rows <= 0 || g.gather_div <= 0 ||
         (size_t)g.gather_rows * (size_t)g.lda * 2 >= (1ull << 31))
+      return BIGMAC_ERR_UNSUPPORTED;
+  }
+  if (g.scatter) {  // see the kernel: a dense bf16 product's rows written through an index, the same operand layout as above
+    if (g.dtype != BIGMAC_BF16 || g.mode != GEMM_DENSE || combo != 2 || g.epilogue != EPI_STORE || g.out_f32 || g.ksplit != 1 || g.wide_k ||
+        g.deep_tile || g.big_tile || g.gather || g.bias || g.scatter_k <= 0 || g.scatter_rows <= 0 ||
+        (size_t)g.M * (size_t)g.scatter_k * 4 >= (1ull << 31) || (size_t)g.scatter_rows * (size_t)g.ldc * 2 >= (1ull << 31))
       return BIGMAC_ERR_UNSUPPORTED;
   }
   if (g.big_tile) {

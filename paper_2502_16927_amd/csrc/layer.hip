@@ -618,6 +618,28 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     rc = route(x);
     if (rc) return rc;
   }
+  auto permute = [&]() -> int {
+    BIGMAC_STAGE(BIGMAC_STAGE_PERMUTATION);
+    TileMapJobs maps = {};
+    maps.tile_rows[0] = gemm_ragged_tile_rows(D->dtype, 0); maps.map[0] = tile_map;
+    if (any_tall_rows(*D)) { maps.tile_rows[1] = gemm_ragged_tile_rows(D->dtype, 1); maps.map[1] = tile_map_tall; }
+    return launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s, &maps);
+  };
+  // A training forward on bf16 storage whose router reads x folds the dispatch into the descending
+  // projection: the permutation is built first, and the product's epilogue writes every token's
+  // narrow row straight into the places of its pairs in the permuted copy (x' itself is not
+  // stored: nothing else reads it).  Not where the product is summed from K slices or runs on the
+  // narrow tile shape, nor where the copy is too large for one 32-bit byte offset.
+  const int descend_ksplit = dcca ? forward_ksplit(*D, D->T, D->r, D->d) : 1;
+  const bool descend_tall = dcca && descend_ksplit == 1 && tall_dense(*D, D->T, D->r, D->d);
+  const bool descend_deep = dcca && descend_ksplit == 1 && !descend_tall && deep_dense(*D, D->T, D->r, D->d);
+  const bool scatter_descend = saved && dcca && bf(*D) && !low_router && !(D->flags & BIGMAC_FLAG_NO_FUSED_DISPATCH) &&
+                               descend_ksplit == 1 && !descend_deep && (size_t)D->T * D->k * (size_t)D->r * 2 < (1ull << 31) &&
+                               (size_t)D->T * D->k * 4 < (1ull << 31);
+  if (scatter_descend) {
+    rc = permute();
+    if (rc) return rc;
+  }
   const void* x_low = x;
   if (dcca) {  // x' = x W_down
     GemmDesc g = base_desc(*D);
@@ -627,9 +649,13 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     g.C = x_low_buf; g.ldc = D->r;
     {
       BIGMAC_STAGE(BIGMAC_STAGE_DESCEND);
-      g.ksplit = forward_ksplit(*D, D->T, D->r, D->d);
-      g.tall_tile = g.ksplit == 1 && tall_dense(*D, D->T, D->r, D->d);
-      g.deep_tile = g.ksplit == 1 && !g.tall_tile && deep_dense(*D, D->T, D->r, D->d);
+      g.ksplit = descend_ksplit;
+      g.tall_tile = descend_tall;
+      g.deep_tile = descend_deep;
+      if (scatter_descend) {
+        g.scatter = slot_of; g.scatter_k = D->k; g.scatter_rows = D->T * D->k;
+        g.C = x_perm;
+      }
       if (g.ksplit > 1) {   // fp32 partials, then one rounding to bf16
         g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->r;
         rc = launch_gemm(g, s);
@@ -646,19 +672,15 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     rc = route(x_low);
     if (rc) return rc;
   }
-  {
-    BIGMAC_STAGE(BIGMAC_STAGE_PERMUTATION);
-    TileMapJobs maps = {};
-    maps.tile_rows[0] = gemm_ragged_tile_rows(D->dtype, 0); maps.map[0] = tile_map;
-    if (any_tall_rows(*D)) { maps.tile_rows[1] = gemm_ragged_tile_rows(D->dtype, 1); maps.map[1] = tile_map_tall; }
-    rc = launch_build_permutation(D->T, D->k, D->N, D->capacity, topk_idx, offsets, slot_of, src_of, wsb + F.perm, s, &maps);
+  if (!scatter_descend) {
+    rc = permute();
     if (rc) return rc;
   }
   // Forward-only calls on bf16 storage fold the dispatch into the expert-up product: its A rows are
   // read from x' (or x) through src_of and no permuted copy is written.  A training forward
   // keeps the copy: the backward pass contracts over its rows.
   const bool fuse_dispatch = !saved && bf(*D) && !(D->flags & BIGMAC_FLAG_NO_FUSED_DISPATCH);
-  if (!fuse_dispatch) {
+  if (!fuse_dispatch && !scatter_descend) {
     BIGMAC_STAGE(BIGMAC_STAGE_DISPATCH);
     rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);
   }

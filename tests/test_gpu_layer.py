@@ -134,10 +134,38 @@ def test_dispatch_folded_into_the_expert_product(order, tiles):
         assert np.array_equal(outs[0], outs[2]), "inference differs from the training forward"
 
 
+@pytest.mark.parametrize("case", [dict(T=1100, d=256, r=128, N=24, k=4, h=256, zipf_s=1.5), dict(T=200, d=320, r=64, N=64, k=13, h=64),
+                                  dict(T=1, d=64, r=64, N=8, k=1, h=64), dict(T=4000, d=576, r=448, N=8, k=2, h=64),
+                                  dict(T=200, d=768, r=256, N=8, k=2, h=128)],
+                         ids=lambda c: "T{T}_d{d}_r{r}_N{N}_k{k}_h{h}".format(**c))
+def test_dispatch_folded_into_the_descending_projection(case):
+    """A training forward has the descending projection write x' straight into the permuted copy
+    (one store per pick, dropped pairs none).  Same bits as with the copy kernel
+    (BIGMAC_FLAG_NO_FUSED_DISPATCH) in y, dx and every weight gradient (dW1 contracts over all rows
+    of the permuted copy): more picks than one pass of the epilogue takes, a capacity that drops
+    pairs, T = 1, and shapes whose projection runs on another tile or in K slices (not folded)."""
+    wl = synth.small(**case)
+    data = synth.generate(wl)
+    for capacity in (0, B.expert_capacity(wl.T, wl.k, wl.N, 0.7)):
+        outs = []
+        for flags in (0, B.FLAG_NO_FUSED_DISPATCH):
+            layer = DeviceLayer(wl, data, flags=flags, capacity=capacity)
+            layer.forward(training=True)
+            layer.alloc_grads()
+            layer.backward()
+            torch.cuda.synchronize()
+            outs.append([layer.y.clone(), layer.dx.clone()] + [layer.grads[n].clone() for n in sorted(layer.grads)])
+        assert torch.isfinite(outs[0][0]).all() and outs[0][0].abs().max() > 0
+        for u, v in zip(*outs):
+            assert torch.equal(u, v)
+
+
 def test_variants_agree_bit_for_bit_on_random_shapes():
-    """Tile shape, tile order in time and the folded dispatch only change who computes what and from
-    where the rows are read, never the arithmetic: on seeded random shapes (single experts, k = N,
-    T = 1, skewed and capacity-clipped routing) every variant gives the bits of the plain training step."""
+    """Tile shape, tile order in time and the folded dispatch (rows read through the index by the
+    expert-up product, or written through it by the descending projection) only change who
+    computes what and where the rows travel, never the arithmetic: on seeded random shapes (single
+    experts, k = N, T = 1, skewed and capacity-clipped routing) every variant gives the bits of the
+    plain training step, gradients included (dW1 contracts over every row of the permuted copy)."""
     rng = np.random.default_rng(11)
     for it in range(16):
         d, r = int(rng.choice([64, 128, 192, 256, 512])), int(rng.choice([64, 128, 192, 256, 512]))
@@ -151,8 +179,8 @@ def test_variants_agree_bit_for_bit_on_random_shapes():
         wl = synth.small(**case)
         data = synth.generate(wl)
         ref = None
-        for flags, training in ((0, True), (0, False), (B.FLAG_NO_FUSED_DISPATCH, False), (B.FLAG_TILES_LARGE, False),
-                                (B.FLAG_TILES_LARGE, True), (B.FLAG_TILES_SMALL, True)):
+        for flags, training in ((B.FLAG_NO_FUSED_DISPATCH, True), (0, True), (0, False), (B.FLAG_NO_FUSED_DISPATCH, False),
+                                (B.FLAG_TILES_LARGE, False), (B.FLAG_TILES_LARGE, True), (B.FLAG_TILES_SMALL, True)):
             layer = DeviceLayer(wl, data, flags=flags, capacity=capacity)
             out = {"y": host(layer.forward(training=training)).copy()}
             if training and N % 8 == 0:
