@@ -133,8 +133,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=0, help="override T (decode sweep)")
     ap.add_argument("--forward-only", action="store_true", help="time the inference forward of the workload (no saved block, no backward)")
     ap.add_argument("--no-fused-dispatch", action="store_true",
-                    help="forward-only runs: dispatch the rows first instead of reading them through the index in the "
-                         "expert-up product (BIGMAC_FLAG_NO_FUSED_DISPATCH)")
+                    help="dispatch the rows with the copy kernel instead of folding the step into a product (forward-only: "
+                         "rows read through the index by the expert-up product; training: rows written through it by "
+                         "the descending projection) (BIGMAC_FLAG_NO_FUSED_DISPATCH)")
     ap.add_argument("--order", default="dcca", choices=["dcca", "cdac"])
     ap.add_argument("--cpu-sample", type=int, default=4096, help="tokens of the oracle timing sample (0: skip)")
     ap.add_argument("--no-stage-events", action="store_true")
@@ -342,6 +343,14 @@ def main():
         for tb in tables:
             for s, ms in tb.elapsed_ms(set(live)).items():
                 stage_ms[names[s]] = stage_ms.get(names[s], 0.0) + ms / args.steps
+    # a dispatch folded into a product has no stage of its own: its bytes are that product's
+    folding = B.dispatch_folding(dims, training)
+    if folding and "dispatch" in stage_ms:
+        del stage_ms["dispatch"]
+        if folding == 2:
+            kind, flops, nbytes = work["descend"]
+            e = 2 if wl.dtype == B.BF16 else 4
+            work["descend"] = (kind, flops, nbytes + (wl.T * wl.k - wl.T) * wl.r * e + 4 * wl.T * wl.k)   # k rows written per token, not one
     roofline, stage_roofline = None, {}
     if stage_ms and not capacity:   # with dropped rows the algorithmic work is not the closed form below
         dom = max(stage_ms, key=stage_ms.get)
@@ -385,6 +394,8 @@ def main():
         "roofline": roofline,
         "matrix_tflops": fwd_flops * (3 if training else 1) / (elapsed / args.steps) / 1e12,
         "permute_bytes_per_step": B.permute_bytes(dims) * (1.0 if training else 0.5),
+        "dispatch": {0: "copy kernel", 1: "folded into the expert-up product (rows read through src_of)",
+                     2: "folded into the descending projection (rows written through slot_of)"}[folding],
         "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
         "stage_roofline": stage_roofline,
         "stage_sum_ms": round(sum(stage_ms.values()), 4),

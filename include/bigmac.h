@@ -273,6 +273,13 @@ int bigmac_mfma_probe(int blocks, int iters, float *sink /*device*/, double *flo
 int bigmac_gather_probe(const void *table, const int32_t *order, int64_t rows, int64_t row_bytes, int streaming,
                         uint32_t *sink, void *stream);
 const char *bigmac_stage_name(int stage);
+/* Where a layer forward with these dims does its dispatch step (Section 3.1's first All-to-All,
+ * on one GPU a row copy): 0 = the copy kernel of bigmac_dispatch; 1 = folded into the expert-up
+ * product, which reads its rows through src_of (forward-only calls, saved == NULL); 2 = folded
+ * into the descending projection, whose epilogue writes the rows of x' through slot_of (training
+ * calls).  See BIGMAC_FLAG_NO_FUSED_DISPATCH.  Measurement code uses it to price the stages.
+ * training: 0 = a call with saved == NULL.  Negative: an error code for bad dims. */
+int bigmac_dispatch_folding(const bigmac_dims *dims, int training);
 
 #ifdef __cplusplus
 }

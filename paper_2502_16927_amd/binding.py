@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.bigmac_layer_backward.argtypes = [dp, ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.bigmac_set_stage_events.restype = ci
         L.bigmac_set_stage_events.argtypes = [ctypes.POINTER(vp)]
+        L.bigmac_dispatch_folding.restype = ci
+        L.bigmac_dispatch_folding.argtypes = [dp, ci]
         L.bigmac_stage_name.restype = ctypes.c_char_p
         L.bigmac_stage_name.argtypes = [ci]
         L.bigmac_gather_probe.restype = ci
@@ -84,7 +86,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("bigmac_workspace_bytes", "bigmac_status_string", "bigmac_forward_matrix_flops", "bigmac_permute_bytes",
            "bigmac_saved_layout", "bigmac_saved_aux_layout", "bigmac_aux_loss", "bigmac_route", "bigmac_dispatch", "bigmac_dispatch_static", "bigmac_grouped_ffn", "bigmac_combine",
-           "bigmac_layer_forward", "bigmac_layer_backward", "bigmac_set_stage_events", "bigmac_stage_name",
+           "bigmac_layer_forward", "bigmac_layer_backward", "bigmac_set_stage_events", "bigmac_stage_name", "bigmac_dispatch_folding",
            "bigmac_mfma_probe", "bigmac_gather_probe")
 STAGE_COUNT = 22
 
@@ -210,6 +212,14 @@ def bigmac_layer_backward(dims, params, x, dy, saved, dx, d_w_down, d_w_up, d_w_
     _check(lib().bigmac_layer_backward(ctypes.byref(dims), ctypes.byref(params), _ptr(x), _ptr(dy), _ptr(saved), _ptr(dx),
                                        _ptr(d_w_down), _ptr(d_w_up), _ptr(d_w_gate), _ptr(d_w1), _ptr(d_w2), _ptr(d_b1), _ptr(d_b2),
                                        _ptr(ws), _nbytes(ws), _stream(stream)), "bigmac_layer_backward")
+
+
+def dispatch_folding(dims, training: bool) -> int:
+    """0: copy kernel; 1: folded into the expert-up product; 2: folded into the descending projection."""
+    rc = lib().bigmac_dispatch_folding(ctypes.byref(dims), int(bool(training)))
+    if rc < 0:
+        _check(rc, "bigmac_dispatch_folding")
+    return rc
 
 
 def stage_name(stage: int) -> str:

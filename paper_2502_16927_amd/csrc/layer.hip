@@ -469,6 +469,24 @@ int bigmac_set_stage_events(void* const* events) {
   return BIGMAC_OK;
 }
 
+namespace {
+// training forward: the descending projection writes x' straight into the permuted copy (see
+// bigmac_layer_forward)
+bool descend_scatters(const bigmac_dims& D) {
+  if (D.order != BIGMAC_ORDER_DCCA || !bf(D) || route_low(D) || (D.flags & BIGMAC_FLAG_NO_FUSED_DISPATCH)) return false;
+  if (forward_ksplit(D, D.T, D.r, D.d) != 1) return false;
+  if (!tall_dense(D, D.T, D.r, D.d) && deep_dense(D, D.T, D.r, D.d)) return false;
+  return (size_t)D.T * D.k * (size_t)D.r * 2 < (1ull << 31) && (size_t)D.T * D.k * 4 < (1ull << 31);
+}
+}  // namespace
+
+int bigmac_dispatch_folding(const bigmac_dims* D, int training) {
+  const int rc = check_dims(D);
+  if (rc) return rc;
+  if (training) return descend_scatters(*D) ? 2 : 0;
+  return bf(*D) && !(D->flags & BIGMAC_FLAG_NO_FUSED_DISPATCH) ? 1 : 0;
+}
+
 const char* bigmac_stage_name(int stage) {
   static const char* names[BIGMAC_STAGE_COUNT] = {
       "router_logits", "topk_gate", "descend", "permutation", "dispatch", "expert_up", "expert_down", "combine", "ascend",
@@ -633,9 +651,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   const int descend_ksplit = dcca ? forward_ksplit(*D, D->T, D->r, D->d) : 1;
   const bool descend_tall = dcca && descend_ksplit == 1 && tall_dense(*D, D->T, D->r, D->d);
   const bool descend_deep = dcca && descend_ksplit == 1 && !descend_tall && deep_dense(*D, D->T, D->r, D->d);
-  const bool scatter_descend = saved && dcca && bf(*D) && !low_router && !(D->flags & BIGMAC_FLAG_NO_FUSED_DISPATCH) &&
-                               descend_ksplit == 1 && !descend_deep && (size_t)D->T * D->k * (size_t)D->r * 2 < (1ull << 31) &&
-                               (size_t)D->T * D->k * 4 < (1ull << 31);
+  const bool scatter_descend = saved && descend_scatters(*D);
   if (scatter_descend) {
     rc = permute();
     if (rc) return rc;
