@@ -372,7 +372,7 @@ __global__ __launch_bounds__(256) void router_logits_pipelined_kernel(const XT* 
   }
 }
 
-// One wavefront per token.  Every lane ranks its logits against all N by broadcast (rank = how
+// One wavefront per token.  More than 128 experts: every lane ranks its logits against all N by broadcast (rank = how
 // many logits come first: greater, or equal with a lower index, which is the order k rounds of
 // arg-max with ties to the lowest index would pick them in); ranks below k are the selection, in
 // pick order.  Then the softmax over the k picked logits, summed in pick order.  PER = logits
@@ -383,22 +383,39 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(const float* __restrict_
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
-  if constexpr (PER == 1) {
-    // Up to 64 experts: one logit per lane, sorted across the wavefront by a bitonic network under
-    // the same order (greater logit first, equal logits by lower index: a strict total order, so
-    // the result is the unique sorted sequence); lanes 0 .. k-1 then hold the picks in pick order.
+  // "a comes first": greater logit, equal logits by lower index (a strict total order)
+  auto first = [](float av, int ai, float bv, int bi) { return av > bv || (av == bv && ai < bi); };
+  // one compare-exchange step of a bitonic network over the wavefront: partner lane ^ j, the pair's
+  // first element goes to the lane for which want_first holds
+  auto exchange = [&](float& mv, int& mi, int j, bool want_first) {
+    const float ov = __shfl_xor(mv, j, 64);
+    const int oi = __shfl_xor(mi, j, 64);
+    if (first(mv, mi, ov, oi) != want_first) { mv = ov; mi = oi; }
+  };
+  auto sort64 = [&](float& mv, int& mi) {   // lane 0 ends with the first element
+#pragma unroll
+    for (int size = 2; size <= 64; size <<= 1)
+#pragma unroll
+      for (int j = size >> 1; j > 0; j >>= 1) exchange(mv, mi, j, ((lane & j) == 0) == ((lane & size) == 0));   // lower lane of an ascending block
+  };
+  if constexpr (PER <= 2) {
+    // Up to 64 experts: one logit per lane, sorted across the wavefront by a bitonic network (the
+    // order is strict and total, so the result is the unique sorted sequence); lanes 0 .. k-1 then
+    // hold the picks in pick order.  Up to 128: two logits per lane, both halves sorted the same
+    // way; the first 64 of their union are, lane by lane, the first of (half 0 at lane l, half 1
+    // at lane 63 - l), a bitonic sequence that six more steps sort.  k <= 64 picks are all there.
     float mv = lane < N ? logits[(size_t)t * N + lane] : -INFINITY;
     int mi = lane;
+    sort64(mv, mi);
+    if constexpr (PER == 2) {
+      float uv = 64 + lane < N ? logits[(size_t)t * N + 64 + lane] : -INFINITY;
+      int ui = 64 + lane;
+      sort64(uv, ui);
+      const float rv = __shfl(uv, 63 - lane, 64);
+      const int ri = __shfl(ui, 63 - lane, 64);
+      if (!first(mv, mi, rv, ri)) { mv = rv; mi = ri; }
 #pragma unroll
-    for (int size = 2; size <= 64; size <<= 1) {
-#pragma unroll
-      for (int j = size >> 1; j > 0; j >>= 1) {
-        const float ov = __shfl_xor(mv, j, 64);
-        const int oi = __shfl_xor(mi, j, 64);
-        const bool mine_first = mv > ov || (mv == ov && mi < oi);
-        const bool want_first = ((lane & j) == 0) == ((lane & size) == 0);   // lower lane of an ascending block
-        if (mine_first != want_first) { mv = ov; mi = oi; }
-      }
+      for (int j = 32; j > 0; j >>= 1) exchange(mv, mi, j, (lane & j) == 0);
     }
     const float m = __shfl(mv, 0, 64);
     const float e = lane < k ? expf(mv - m) : 0.0f;

@@ -67,6 +67,20 @@ def test_route_ties_and_order_cases(oracle):
     ref_idx, ref_gate, ref_logits = oracle.route(x, wg, None, 4)
     assert np.array_equal(host(lg).view(np.uint32), ref_logits.view(np.uint32))
     assert np.array_equal(host(idx), ref_idx)
+    # the same across the two registers of the 65..128-expert path: every logit has equal copies in
+    # both halves, more picks than distinct values, and the full k = 64 of 128
+    for N, k in ((100, 33), (128, 64), (65, 2)):
+        col = rng.standard_normal((d, 7)).astype(np.float32)
+        wg = np.ascontiguousarray(col[:, np.arange(N) % 7])
+        dims = B.make_dims(T, d, 64, N, k, 64, B.BF16)
+        idx = torch.empty((T, k), dtype=torch.int32, device=DEV)
+        w = torch.empty((T, k), dtype=torch.float32, device=DEV)
+        lg = torch.empty((T, N), dtype=torch.float32, device=DEV)
+        B.bigmac_route(dims, B.to_device(x, B.BF16), B.to_device(wg, B.F32), None, idx, w, lg)
+        torch.cuda.synchronize()
+        ref_idx, ref_gate, _ = oracle.route(x, wg, None, k)
+        assert np.array_equal(host(idx), ref_idx), (N, k)
+        assert np.abs(host(w) - ref_gate).max() < 1e-6
     # absorption cases where the summation order shows
     xo = np.zeros((3, d), np.float32)
     xo[0, 0], xo[0, 1], xo[0, 64] = 1e8, 1.0, -1e8
