@@ -27,7 +27,7 @@ constexpr int R_NB = 16;    // experts per pass
 constexpr int R_QT = 4;     // 64-row blocks of W_g staged per LDS tile
 constexpr int ROUTER_DX_PICKS = 1024;   // (token, pick) pairs a workgroup of the router's dx kernel stages
 #ifndef ROUTER_DX_CPL
-#define ROUTER_DX_CPL 4                 // output columns per lane of that kernel (N <= 64; half of it above)
+#define ROUTER_DX_CPL 4                 // output columns per lane of that kernel
 #endif
 #ifndef ROUTER_DX_THREADS
 #define ROUTER_DX_THREADS 1024
@@ -697,18 +697,33 @@ __global__ __launch_bounds__(ROUTER_DX_THREADS) void router_dx_kernel(const int3
   __shared__ float s_dl[ROUTER_DX_PICKS];
   __shared__ int s_e[ROUTER_DX_PICKS];
   const int c0 = blockIdx.x * TC;
-  const int t_beg = blockIdx.y * tokens_per_block, t_end = min(T, t_beg + tokens_per_block);
-  // the picks are requested first and stored last, so that their latency hides behind the rows
+  // A workgroup fills its rows of w_gate once and then walks the token groups blockIdx.y,
+  // blockIdx.y + gridDim.y, ...: the picks of a group are requested before the work in front of
+  // them (the fill; the sums of the group before) and stored into the LDS behind it.
   constexpr int PICK_LOADS = (ROUTER_DX_PICKS + ROUTER_DX_THREADS - 1) / ROUTER_DX_THREADS;
-  const int picks_here = (t_end - t_beg) * k;
+  const int groups = (T + tokens_per_block - 1) / tokens_per_block;
   float pick_dl[PICK_LOADS];
   int pick_e[PICK_LOADS];
+  auto request_picks = [&](int group) {
+    const int t_beg = group * tokens_per_block, picks_here = (min(T, t_beg + tokens_per_block) - t_beg) * k;
 #pragma unroll
-  for (int u = 0; u < PICK_LOADS; ++u) {
-    const size_t at = (size_t)t_beg * k + min(u * ROUTER_DX_THREADS + (int)threadIdx.x, picks_here - 1);
-    pick_dl[u] = dl_picked[at];
-    pick_e[u] = topk_idx[at];
-  }
+    for (int u = 0; u < PICK_LOADS; ++u) {
+      const size_t at = (size_t)t_beg * k + min(u * ROUTER_DX_THREADS + (int)threadIdx.x, picks_here - 1);
+      pick_dl[u] = dl_picked[at];
+      pick_e[u] = topk_idx[at];
+    }
+  };
+  auto stage_picks = [&](int group) {
+    const int t_beg = group * tokens_per_block, picks_here = (min(T, t_beg + tokens_per_block) - t_beg) * k;
+#pragma unroll
+    for (int u = 0; u < PICK_LOADS; ++u) {
+      const int i = u * ROUTER_DX_THREADS + (int)threadIdx.x;
+      if (i < picks_here) { s_dl[i] = pick_dl[u]; s_e[i] = pick_e[u]; }
+    }
+  };
+  int group = blockIdx.y;
+  if (group >= groups) return;
+  request_picks(group);
   if ((N & 3) == 0) {
     // 16-byte loads, a batch in flight per lane.  Work item g = (group, quad in row % 4, row % 16):
     // 16 lanes take the same quad of 16 consecutive rows, 4 such sets make a wavefront.  Its four
@@ -743,41 +758,45 @@ __global__ __launch_bounds__(ROUTER_DX_THREADS) void router_dx_kernel(const int3
       wt[n * PITCH + c] = c0 + c < d ? w_gate[(size_t)(c0 + c) * N + n] : 0.0f;
     }
   }
-#pragma unroll
-  for (int u = 0; u < PICK_LOADS; ++u) {
-    const int i = u * ROUTER_DX_THREADS + (int)threadIdx.x;
-    if (i < picks_here) { s_dl[i] = pick_dl[u]; s_e[i] = pick_e[u]; }
-  }
-  __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float* mine = wt + lane * CPL;
-  for (int t = t_beg + wave; t < t_end; t += ROUTER_DX_THREADS / 64) {
-    const int base = (t - t_beg) * k;
-    // lane j holds pick j (k <= 64); every lane then reads them back one by one
-    const int at = base + min(lane, k - 1);
-    const int dl_bits = __float_as_int(s_dl[at]), e_mine = s_e[at];
-    cols_t acc = 0.0f;
-    // U picks at a time: their LDS reads are independent, the sums keep the order j = 0, 1, ...
-    auto picks = [&](auto width, int j) {
-      constexpr int U = decltype(width)::value;
-      float dj[U];
-      cols_t w[U];
+  while (true) {
+    stage_picks(group);
+    __syncthreads();                    // the picks (and, the first time, the rows of w_gate) are in the LDS
+    const int next = group + (int)gridDim.y;
+    if (next < groups) request_picks(next);
+    const int t_beg = group * tokens_per_block, t_end = min(T, t_beg + tokens_per_block);
+    for (int t = t_beg + wave; t < t_end; t += ROUTER_DX_THREADS / 64) {
+      const int base = (t - t_beg) * k;
+      // lane j holds pick j (k <= 64); every lane then reads them back one by one
+      const int at = base + min(lane, k - 1);
+      const int dl_bits = __float_as_int(s_dl[at]), e_mine = s_e[at];
+      cols_t acc = 0.0f;
+      // U picks at a time: their LDS reads are independent, the sums keep the order j = 0, 1, ...
+      auto picks = [&](auto width, int j) {
+        constexpr int U = decltype(width)::value;
+        float dj[U];
+        cols_t w[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        dj[u] = __int_as_float(__builtin_amdgcn_readlane(dl_bits, j + u));
-        w[u] = *(const cols_t*)(mine + __builtin_amdgcn_readlane(e_mine, j + u) * PITCH);
-      }
+        for (int u = 0; u < U; ++u) {
+          dj[u] = __int_as_float(__builtin_amdgcn_readlane(dl_bits, j + u));
+          w[u] = *(const cols_t*)(mine + __builtin_amdgcn_readlane(e_mine, j + u) * PITCH);
+        }
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int q = 0; q < CPL; ++q) acc[q] = fmaf(dj[u], w[u][q], acc[q]);
-    };
-    int j = 0;
-    for (; j + 8 <= k; j += 8) picks(std::integral_constant<int, 8>{}, j);
-    if (j + 4 <= k) { picks(std::integral_constant<int, 4>{}, j); j += 4; }
-    for (; j < k; ++j) picks(std::integral_constant<int, 1>{}, j);
-    const int c = c0 + lane * CPL;
-    if (c < d) *(cols_t*)(dx + (size_t)t * d + c) = acc;
+          for (int q = 0; q < CPL; ++q) acc[q] = fmaf(dj[u], w[u][q], acc[q]);
+      };
+      int j = 0;
+      for (; j + 8 <= k; j += 8) picks(std::integral_constant<int, 8>{}, j);
+      if (j + 4 <= k) { picks(std::integral_constant<int, 4>{}, j); j += 4; }
+      for (; j < k; ++j) picks(std::integral_constant<int, 1>{}, j);
+      const int c = c0 + lane * CPL;
+      if (c < d) __builtin_nontemporal_store(acc, (cols_t*)(dx + (size_t)t * d + c));
+    }
+    if (next >= groups) break;
+    __syncthreads();                    // everyone is done with this group's picks
+    group = next;
   }
 }
 
@@ -885,16 +904,20 @@ int launch_route_backward(const bigmac_dims& D, const float* w_gate, const int32
   BIGMAC_CHECK_LAUNCH();
   if (tiled) {
     // tokens per workgroup: as many as the staging holds, fewer while the grid would leave CUs idle
-    const int width = D.N <= 64 ? ROUTER_DX_CPL * 64 : ROUTER_DX_CPL * 32;
+    const int width = ROUTER_DX_CPL * 64;
     const unsigned gx = (unsigned)((D.d + width - 1) / width);
     int tokens = std::min(ROUTER_DX_TOKENS, ROUTER_DX_PICKS / D.k);
     while (tokens > 16 && (long)gx * ((D.T + tokens - 1) / tokens) < 256) tokens /= 2;
-    const dim3 grid_dx(gx, (unsigned)((D.T + tokens - 1) / tokens));
+    // token groups per workgroup: the rows of w_gate are filled once per workgroup, so each walks
+    // several groups once the grid has four workgroups per CU anyway
+    unsigned gy_dx = (unsigned)((D.T + tokens - 1) / tokens);
+    if ((long)gx * gy_dx > 1024) gy_dx = std::max(1u, 1024u / gx);
+    const dim3 grid_dx(gx, gy_dx);
     if (D.N <= 64)
       hipLaunchKernelGGL((router_dx_kernel<ROUTER_DX_CPL, 64>), grid_dx, dim3(ROUTER_DX_THREADS), 0, s,
                          topk_idx, dl_picked, w_gate, dx_f32, D.T, D.d, D.N, D.k, tokens);
     else
-      hipLaunchKernelGGL((router_dx_kernel<ROUTER_DX_CPL / 2, 128>), grid_dx, dim3(ROUTER_DX_THREADS), 0, s,
+      hipLaunchKernelGGL((router_dx_kernel<ROUTER_DX_CPL, 128>), grid_dx, dim3(ROUTER_DX_THREADS), 0, s,
                          topk_idx, dl_picked, w_gate, dx_f32, D.T, D.d, D.N, D.k, tokens);
     BIGMAC_CHECK_LAUNCH();
     return BIGMAC_OK;
