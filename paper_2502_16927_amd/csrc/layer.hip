@@ -350,7 +350,8 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.epilogue = EPI_GELU;
   g.big_tile = big_rows(D, W.hid, W.win);
   g.tall_tile = !g.big_tile && tall_rows(D, W.hid, W.win); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
-  g.wide_k = !g.tall_tile && !g.big_tile && !gather && wide_k_ok(D, W.win, 1);
+  if (g.tall_tile) { g.tall_tile = 0; g.long_tile = 1; g.tile_map = tile_map; }   // this product: the tall tile on its side (see launch_mfma_long)
+  g.wide_k = !g.tall_tile && !g.big_tile && !g.long_tile && !gather && wide_k_ok(D, W.win, 1);
   g.A = x_perm; g.lda = W.win; g.K = W.win;
   g.gather = gather; g.gather_rows = D.T; g.gather_div = D.k;   // with an index, x_perm is the [T, win] rows before the dispatch
   g.B = w1; g.ldb = W.hid; g.gstride_b = (long)W.win * W.hid; g.N = W.hid;
@@ -374,6 +375,7 @@ int run_experts_forward(const bigmac_dims& D, const void* x_perm, const int* off
   g.C = o_perm; g.ldc = W.win;
   g.bias = b2; g.gstride_bias = W.win;
   g.big_tile = big_rows(D, W.win, W.hid);
+  g.long_tile = 0;
   g.tall_tile = !g.big_tile && tall_rows(D, W.win, W.hid); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
   g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(D, W.hid, 2);
   g.kloop_priority = 1;
@@ -871,7 +873,7 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.C = dx_perm; g.ldc = W.win;
     g.big_tile = big_rows(*D, W.win, W.hid);
     g.tall_tile = !g.big_tile && tall_rows(*D, W.win, W.hid); g.tile_map = (g.tall_tile || g.big_tile) ? tile_map_tall : tile_map;
-    g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(*D, W.hid, 8);
+      g.wide_k = !g.tall_tile && !g.big_tile && wide_k_ok(*D, W.hid, 8);
     g.kloop_priority = 1;
     if (!g.big_tile) touch_weights(*D, g, P->w1, 8);
     BIGMAC_STAGE(BIGMAC_STAGE_BWD_UP_DGRAD);

@@ -27,6 +27,8 @@ SMALL = [
     # enough rows, tiles and K for the 256-row workgroup tiles in expert-up and the GELU' product
     # (not in expert-down and its counterpart, which have 4 column tiles): both tile maps in one step
     dict(T=2560, d=512, r=512, N=16, k=8, h=2048, dtype=B.BF16),
+    # the same with a hidden width that ends inside a 256-column tile (expert-up's 128 x 256 tiles)
+    dict(T=2560, d=512, r=512, N=16, k=8, h=1984, dtype=B.BF16, zipf_s=0.8),
     # the router's share of dx: 65..128 experts (narrower LDS tile), N % 4 != 0 (scalar tile fill),
     # k = 8 + 4 + 1 picks, k = 64 (staging limit), d not a multiple of the tile width, and more than
     # 128 experts (per-token kernel on a transposed copy of the router weights)
@@ -92,7 +94,7 @@ def test_small_forward_backward(oracle, case):
     check_weight_grads({n: host(v) - init[n] for n, v in layer2.grads.items()}, g_ref, counts, tol, few_rows=wl.dtype == B.BF16 and few_rows_per_expert(counts))
 
 
-@pytest.mark.parametrize("case", [SMALL[1], SMALL[3], SMALL[5], SMALL[8], dict(T=700, d=128, r=192, N=8, k=2, h=448, dtype=B.BF16)],
+@pytest.mark.parametrize("case", [SMALL[1], SMALL[3], SMALL[5], SMALL[8], SMALL[9], dict(T=700, d=128, r=192, N=8, k=2, h=448, dtype=B.BF16)],
                          ids=lambda c: "T{T}_d{d}_r{r}_N{N}_k{k}_h{h}".format(**c))
 def test_large_tiles_give_the_same_bits(case):
     """The 256 x 256 workgroup tiles add the same products in the same order as the smaller ones:
