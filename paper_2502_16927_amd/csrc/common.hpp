@@ -154,7 +154,8 @@ struct GemmDesc {
   int wide_k;                // bf16, k-contiguous A, K % 64 == 0: the square tile with 64-deep k tiles, two ring stages
   int kloop_priority;        // MFMA kernels: raise the wave priority inside the k loop (see the kernel)
   int deep_tile;             // bf16, dense, store or accumulate (K % 64 == 0 with a k-contiguous operand): 128 x 64 outputs, 64-deep k tiles
-  int long_tile;             // bf16, ragged-M, k-contiguous A only, GELU epilogue: 128 x 256 outputs (four wavefronts side by side, each 128 x 64), tile map of 128-row tiles
+  int long_tile;             // bf16, k-contiguous A only; ragged-M with the GELU epilogue or dense with the plain store: 128 x 256 outputs
+                             //   (four wavefronts side by side, each 128 x 64); ragged-M: tile map of 128-row tiles
   int big_tile;              // bf16: 256 x 256 outputs by eight wavefronts, one workgroup per CU (ragged-M: tile map of 256-row tiles)
   const int* gather;         // ragged-M MFMA kernels with a k-contiguous A, GELU or store epilogue: row m of the product is row gather[m] / gather_div of A (device [max_rows]); NULL: A holds the rows in order
   int gather_rows, gather_div; //   rows of A behind the index; the index is divided by gather_div first (flat (row, pick) pairs)

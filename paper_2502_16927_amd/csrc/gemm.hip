@@ -803,11 +803,18 @@ int launch_mfma_wide(const GemmDesc& g, hipStream_t s) {
 // bytes of a row per k tile, half a cache line) while its B rows are whole lines: half the A rows
 // and twice the B columns per tile mean fewer of the half-line requests per flop, and an expert's
 // last tile pads half as many rows.  Measured against the tall tile: expert-up -5.5 % at
-// zipf_stress, -7 % at gpt_xl and gpt_6p7b.  (Products whose B is k-contiguous too gain nothing.)
+// zipf_stress, -7 % at gpt_xl and gpt_6p7b; the two shared projections of the forward pass, which
+// have the same operand layouts, -6 % and -9 % at zipf_stress.  (Products whose B is k-contiguous
+// too gain nothing.)
 int launch_mfma_long(const GemmDesc& g, hipStream_t s) {
   constexpr int BM = 128, BN = 256, BK = BIGMAC_TILE_BK;
   dim3 grid = grid_for<BM, BN>(g, true, BIGMAC_TALL_BLOCKS_PER_CU), block(256);
-  if (g.gather) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 1, 4, true, false, EPI_GELU, false, BIGMAC_TILE_STAGES, true>), grid, block, 0, s, g);
+  if (g.epilogue == EPI_ACCUM) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 1, 4, true, false, EPI_ACCUM, true>), grid, block, 0, s, g);
+  else if (g.epilogue == EPI_STORE) {   // the dense projections
+    if (g.scatter) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 1, 4, true, false, EPI_STORE, false, BIGMAC_TILE_STAGES, false, true>), grid, block, 0, s, g);
+    else if (g.out_f32) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 1, 4, true, false, EPI_STORE, true>), grid, block, 0, s, g);
+    else hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 1, 4, true, false, EPI_STORE, false>), grid, block, 0, s, g);
+  } else if (g.gather) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 1, 4, true, false, EPI_GELU, false, BIGMAC_TILE_STAGES, true>), grid, block, 0, s, g);
   else hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 1, 4, true, false, EPI_GELU, false>), grid, block, 0, s, g);
   BIGMAC_CHECK_LAUNCH();
   return BIGMAC_OK;
@@ -967,9 +974,11 @@ int launch_gemm(const GemmDesc& desc, hipStream_t s) {
         (size_t)g.M * (size_t)g.scatter_k * 4 >= (1ull << 31) || (size_t)g.scatter_rows * (size_t)g.ldc * 2 >= (1ull << 31))
       return BIGMAC_ERR_UNSUPPORTED;
   }
-  if (g.long_tile) {   // the expert-up product only
-    if (g.dtype != BIGMAC_BF16 || g.mode != GEMM_RAGGED_M || combo != 2 || g.epilogue != EPI_GELU || g.tall_tile || g.big_tile || g.wide_k ||
-        g.deep_tile || g.scatter)
+  if (g.long_tile) {   // the expert-up product and the forward pass's shared projections
+    const bool expert_up = g.mode == GEMM_RAGGED_M && g.epilogue == EPI_GELU && !g.scatter;
+    const bool projection = g.mode == GEMM_DENSE && (g.epilogue == EPI_STORE || g.epilogue == EPI_ACCUM) && g.ksplit == 1 && !g.gather &&
+                            (!g.scatter || g.epilogue == EPI_STORE);
+    if (g.dtype != BIGMAC_BF16 || combo != 2 || !(expert_up || projection) || g.tall_tile || g.big_tile || g.wide_k || g.deep_tile)
       return BIGMAC_ERR_INVALID_ARG;
     return launch_mfma_long(g, s);
   }

@@ -73,7 +73,7 @@ struct FwdPlan {
   size_t logits, perm, x_low, partials, aux, claims, total;
 };
 struct BwdPlan {
-  size_t dy_low, dgate, do_perm, dx_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, bias_sums, gate_low, claims, total;
+  size_t dy_low, dgate, do_perm, dx_perm, dact, dx_low, dL, route, dx_f32, part_up, part_gate, part_down, tmp_f32, bias_sums, gate_low, w_up_t, w_down_t, claims, total;
 };
 
 inline bool bf(const bigmac_dims& D) { return D.dtype == BIGMAC_BF16; }
@@ -275,6 +275,26 @@ inline TileShape token_wgrad_shape(const bigmac_dims& D, int M, int N) {
 }
 inline int token_wgrad_ksplit(const bigmac_dims& D, int M, int N) { return choose_ksplit(M, N, D.T, token_wgrad_shape(D, M, N)); }
 
+// The data gradients of the two shared projections (dy W_up^T, dx' W_down^T) contract over the
+// fast index of the weight as it is stored: both operands k-contiguous, half a cache line per
+// row and k tile.  Where those products are large enough for the 256-row tile, a transposed copy
+// of the weight (8 MB at d = 4096, r = 1024: two launches of a few microseconds) gives them the
+// operand layouts of the forward projections and with them the 128 x 256 tile.
+inline bool transposed_projections(const bigmac_dims& D) {
+  return D.order == BIGMAC_ORDER_DCCA && bf(D) && tall_dense(D, D.T, D.r, D.d) && tall_dense(D, D.T, D.d, low_ld(D)) &&
+         D.r % 8 == 0 && D.d % 8 == 0;
+}
+// out[c][r] = in[r][c] for 16-bit elements, 64 x 64 tiles through the LDS
+__global__ __launch_bounds__(256) void transpose_b16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out, int rows, int cols) {
+  __shared__ uint16_t tile[64][66];
+  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64, tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4)
+    if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = in[(size_t)(r0 + i) * cols + c0 + tx];
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4)
+    if (c0 + i < cols && r0 + tx < rows) out[(size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
 BwdPlan plan_bwd(const bigmac_dims& D) {
   const Widths W = widths(D);
   const size_t Tk = (size_t)D.T * D.k, es = esize(D.dtype);
@@ -297,6 +317,9 @@ BwdPlan plan_bwd(const bigmac_dims& D) {
   p.part_up = c.take(dcca ? (size_t)token_wgrad_ksplit(D, D.r, D.d) * D.r * D.d * 4 : 0);
   p.part_down = c.take(dcca ? (size_t)token_wgrad_ksplit(D, D.d, D.r) * D.d * D.r * 4 : 0);
   p.tmp_f32 = 0;
+  // transposed copies of the two shared matrices for the data gradients of the projections (see transposed_projections)
+  p.w_up_t = c.take(transposed_projections(D) ? (size_t)D.d * D.r * es : 0);
+  p.w_down_t = c.take(transposed_projections(D) ? (size_t)D.d * D.r * es : 0);
   // expert biases: partial column sums (sized for the wider of the two bias vectors; taken always,
   // the plan does not see the parameters); router on x': its share of dx' in fp32
   p.bias_sums = c.take(ragged_colsum_ws_bytes(D.N, W.hid > W.win ? W.hid : W.win));
@@ -674,6 +697,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
         g.scatter = slot_of; g.scatter_k = D->k; g.scatter_rows = D->T * D->k;
         g.C = x_perm;
       }
+      if (g.tall_tile) { g.tall_tile = 0; g.long_tile = 1; }   // k-contiguous A, whole-line B: the tall tile on its side (see launch_mfma_long)
       if (g.ksplit > 1) {   // fp32 partials, then one rounding to bf16
         g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->r;
         rc = launch_gemm(g, s);
@@ -725,6 +749,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
     g.ksplit = forward_ksplit(*D, D->T, D->d, low_ld(*D));
     g.tall_tile = g.ksplit == 1 && tall_dense(*D, D->T, D->d, low_ld(*D));
     g.wide_k = g.ksplit == 1 && !g.tall_tile && wide_k_ok(*D, low_ld(*D), 32);
+    if (g.tall_tile) { g.tall_tile = 0; g.long_tile = 1; }     // as for the descending projection
     if (g.ksplit > 1) {
       g.out_f32 = 1; g.C = wsb + F.partials; g.gstride_c = (long)D->T * D->d;
       rc = launch_gemm(g, s);
@@ -795,6 +820,13 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
     g.deep_tile = !g.tall_tile && deep_dense(*D, D->T, D->r, D->d);
     {
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_ASCEND_DGRAD);
+      if (transposed_projections(*D)) {   // W_up^T [d, r]: B with the output index fast
+        hipLaunchKernelGGL(transpose_b16_kernel, dim3((D->d + 63) / 64, (D->r + 63) / 64), dim3(256), 0, s, (const uint16_t*)P->w_up,
+                           (uint16_t*)(wsb + B.w_up_t), D->r, D->d);
+        BIGMAC_CHECK_LAUNCH();
+        g.B = wsb + B.w_up_t; g.ldb = D->r; g.b_kcontig = 0;
+        g.tall_tile = 0; g.long_tile = 1;
+      }
       rc = launch_gemm(g, s);
     }
     if (rc) return rc;
@@ -916,6 +948,13 @@ int bigmac_layer_backward(const bigmac_dims* D, const bigmac_params* P, const vo
       g.tall_tile = tall_dense(*D, D->T, D->d, low_ld(*D));
       g.wide_k = !g.tall_tile && wide_k_ok(*D, low_ld(*D), 16);
       BIGMAC_STAGE(BIGMAC_STAGE_BWD_DESCEND_DGRAD);
+      if (transposed_projections(*D)) {   // W_down^T [r, d]
+        hipLaunchKernelGGL(transpose_b16_kernel, dim3((D->r + 63) / 64, (D->d + 63) / 64), dim3(256), 0, s, (const uint16_t*)P->w_down,
+                           (uint16_t*)(wsb + B.w_down_t), D->d, D->r);
+        BIGMAC_CHECK_LAUNCH();
+        g.B = wsb + B.w_down_t; g.ldb = D->d; g.b_kcontig = 0;
+        g.tall_tile = 0; g.long_tile = 1;
+      }
       rc = launch_gemm(g, s);
       if (rc) return rc;
     }
