@@ -42,7 +42,7 @@ void mfma_gemm_kernel(GemmDesc p) {
   // Fragment reads address a stage through the 16-bit instruction offset where the whole ring is
   // within its reach; in a larger ring the stage's start is added to the address register instead.
   constexpr bool NEAR_RING = (NS - 1) * STAGE_BYTES + 8192 <= 65536;
-  static_assert(NEAR_RING || STAGE_BYTES + 8192 <= 65536, "a stage must be within reach of the instruction offset");
+  static_assert(NEAR_RING || (TM > TN ? TM : TN) * 32 * (BK / 8) * 16 <= 65536, "a wave tile's sub-tiles must be within reach of the instruction offset");
   __shared__ uint4 ring[NS * STAGE_CHUNKS];
   const unsigned ring_at = lds_address(ring);
   constexpr unsigned OUT_OF_RANGE = 0x80000000u;
@@ -307,48 +307,53 @@ void mfma_gemm_kernel(GemmDesc p) {
         __builtin_amdgcn_s_barrier();                    // ... and so has everyone's; stage (s - 1) is free
         if (it == 0) BIGMAC_TRACE_AT(cur_id, 1);
         if (it + NS - 1 < nk) fetch(cur, it + NS - 1, ring + ((s + NS - 1) % NS) * STAGE_CHUNKS);
-        // all fragments of the k tile are requested at once; the products of k step 0 start as
-        // soon as its fragments are there, while those of the later steps are still arriving
-        Frag<AK> fa[KS][TM];
-        Frag<BKC> fb[KS][TN];
+        // The fragments of two k steps are requested at once; the products of the first start as
+        // soon as its fragments are there, while those of the second are still arriving.  (A
+        // 64-deep k tile takes two such rounds: its fragments would not fit the registers at once.)
+        constexpr int KG = KS < 2 ? KS : 2;
         constexpr int S_IMM = NEAR_RING ? s * STAGE_BYTES : 0;
         constexpr unsigned S_REG = NEAR_RING ? 0u : (unsigned)(s * STAGE_BYTES);
-        static_for<0, KS>([&](auto kstep) {
-          constexpr int ks = decltype(kstep)::value;
-          static_for<0, TM>([&](auto sub) {
-            constexpr int i = decltype(sub)::value;
-            if constexpr (AK) lds_read_b128<S_IMM + i * 32 * (BK / 8) * 16>(pa[ks][0][0] + S_REG, fa[ks][i].q);
-            else {
-              lds_read_tr_b64<S_IMM>(pa[ks][0][i] + S_REG, fa[ks][i].h[0]);
-              lds_read_tr_b64<S_IMM>(pa[ks][1][i] + S_REG, fa[ks][i].h[1]);
-            }
-          });
-          static_for<0, TN>([&](auto sub) {
-            constexpr int j = decltype(sub)::value;
-            if constexpr (BKC) lds_read_b128<S_IMM + j * 32 * (BK / 8) * 16>(pb[ks][0][0] + S_REG, fb[ks][j].q);
-            else {
-              lds_read_tr_b64<S_IMM>(pb[ks][0][j] + S_REG, fb[ks][j].h[0]);
-              lds_read_tr_b64<S_IMM>(pb[ks][1][j] + S_REG, fb[ks][j].h[1]);
-            }
-          });
-        });
         constexpr int READS_PER_STEP = (AK ? TM : 2 * TM) + (BKC ? TN : 2 * TN);
-        static_for<0, KS>([&](auto kstep) {
-          constexpr int ks = decltype(kstep)::value;
-          // the reads of the later k steps may still be under way (the counter saturates at 15:
-          // asking for fewer in flight than allowed only waits a little longer)
-          constexpr int LATER_READS = (KS - 1 - ks) * READS_PER_STEP;
-          lds_wait_for<(LATER_READS < 15 ? LATER_READS : 15)>();
+        static_for<0, KS / KG>([&](auto round) {
+          constexpr int k0 = decltype(round)::value * KG;
+          Frag<AK> fa[KG][TM];
+          Frag<BKC> fb[KG][TN];
+          static_for<0, KG>([&](auto kstep) {
+            constexpr int kk = decltype(kstep)::value, ks = k0 + kk;
+            static_for<0, TM>([&](auto sub) {
+              constexpr int i = decltype(sub)::value;
+              if constexpr (AK) lds_read_b128<S_IMM + i * 32 * (BK / 8) * 16>(pa[ks][0][0] + S_REG, fa[kk][i].q);
+              else {
+                lds_read_tr_b64<S_IMM>(pa[ks][0][i] + S_REG, fa[kk][i].h[0]);
+                lds_read_tr_b64<S_IMM>(pa[ks][1][i] + S_REG, fa[kk][i].h[1]);
+              }
+            });
+            static_for<0, TN>([&](auto sub) {
+              constexpr int j = decltype(sub)::value;
+              if constexpr (BKC) lds_read_b128<S_IMM + j * 32 * (BK / 8) * 16>(pb[ks][0][0] + S_REG, fb[kk][j].q);
+              else {
+                lds_read_tr_b64<S_IMM>(pb[ks][0][j] + S_REG, fb[kk][j].h[0]);
+                lds_read_tr_b64<S_IMM>(pb[ks][1][j] + S_REG, fb[kk][j].h[1]);
+              }
+            });
+          });
+          static_for<0, KG>([&](auto kstep) {
+            constexpr int kk = decltype(kstep)::value;
+            // the reads of the later k step may still be under way (the counter saturates at 15:
+            // asking for fewer in flight than allowed only waits a little longer)
+            constexpr int LATER_READS = (KG - 1 - kk) * READS_PER_STEP;
+            lds_wait_for<(LATER_READS < 15 ? LATER_READS : 15)>();
 #pragma unroll
-          for (int i = 0; i < TM; ++i) fa[ks][i].settle();
+            for (int i = 0; i < TM; ++i) fa[kk][i].settle();
 #pragma unroll
-          for (int j = 0; j < TN; ++j) fb[ks][j].settle();
+            for (int j = 0; j < TN; ++j) fb[kk][j].settle();
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-              acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][j].value(), fa[ks][i].value(), acc[i][j], 0, 0, 0)
-                               : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i].value(), fb[ks][j].value(), acc[i][j], 0, 0, 0);
+              for (int j = 0; j < TN; ++j)
+                acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk][j].value(), fa[kk][i].value(), acc[i][j], 0, 0, 0)
+                                 : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i].value(), fb[kk][j].value(), acc[i][j], 0, 0, 0);
+          });
         });
       });
     }
@@ -820,6 +825,21 @@ int launch_mfma_long(const GemmDesc& g, hipStream_t s) {
   return BIGMAC_OK;
 }
 
+// The 256 x 256 tile with 64-deep k tiles in a ring of two 64 KB stages: k-contiguous operands
+// arrive as whole 128-byte lines, half the requests to the L2.  Plain stores and the GELU' epilogue.
+template <bool AK, bool BKC>
+int launch_mfma_wide64(const GemmDesc& g, hipStream_t s) {
+  constexpr int BM = 256, BN = 256, BK = 64;
+  dim3 grid = grid_for<BM, BN>(g, true, 1), block(512);
+  if (g.gather || g.scatter) return BIGMAC_ERR_UNSUPPORTED;
+  if (g.epilogue == EPI_DGELU) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 2, 4, AK, BKC, EPI_DGELU, false, 2>), grid, block, 0, s, g);
+  else if (g.epilogue != EPI_STORE) return BIGMAC_ERR_UNSUPPORTED;
+  else if (g.out_f32) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 2, 4, AK, BKC, EPI_STORE, true, 2>), grid, block, 0, s, g);
+  else hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 2, 4, AK, BKC, EPI_STORE, false, 2>), grid, block, 0, s, g);
+  BIGMAC_CHECK_LAUNCH();
+  return BIGMAC_OK;
+}
+
 // Few output tiles under a long K (the shared projections onto the narrow width): twice the
 // tiles and half the k steps.  128 x 64 outputs, 64-deep k tiles, four wavefronts stacked in M
 // (each 32 x 64: the bf16 epilogue's strip), 72 KB of ring: two workgroups per CU.
@@ -984,6 +1004,11 @@ int launch_gemm(const GemmDesc& desc, hipStream_t s) {
   }
   if (g.big_tile) {
     if (g.dtype != BIGMAC_BF16 || g.tall_tile || g.wide_k || g.deep_tile || g.touch_bytes) return BIGMAC_ERR_INVALID_ARG;
+    // k-contiguous A and a K of whole 64-deep k tiles: the 64-deep form (whole-line requests).  Measured at
+    // zipf_stress against the 32-deep ring of four: expert-down -3.5 %, the first matrix's data gradient
+    // (both operands k-contiguous) -8.3 %, the GELU' product -1.3 %; expert-up +6 %, which keeps its own tile.
+    if (g.a_kcontig && g.K % 64 == 0 && !g.gather && (g.epilogue == EPI_STORE || g.epilogue == EPI_DGELU))
+      return g.b_kcontig ? launch_mfma_wide64<true, true>(g, s) : launch_mfma_wide64<true, false>(g, s);
     switch (combo) {
       case 2: return launch_mfma_wide<true, false>(g, s);
       case 3: return launch_mfma_wide<true, true>(g, s);
