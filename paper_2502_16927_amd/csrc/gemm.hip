@@ -5,8 +5,10 @@
 // in the same orientation they have in memory (so global reads are row-contiguous for every
 // transposition) with XOR swizzles against bank conflicts; operands whose contraction index is
 // not the fast one in memory are fetched with the gfx950 LDS transpose read (ds_read_b64_tr_b16).
-// Three workgroup tiles: 128 x 128; 256 x 128 for products with many tiles and a long K; 256 x 256
-// (eight wavefronts, one workgroup per CU) for the per-expert row products with K of 2048 and more.
+// Workgroup tiles: 128 x 128; 256 x 128 for products with many tiles and a long K, and the same on
+// its side (128 x 256) where only A is k-contiguous; 256 x 256 (eight wavefronts, one workgroup per
+// CU, 64-deep k tiles) for the per-expert row products with a long K; 128 x 64 and 128 x 128 with
+// 64-deep k tiles for products with few tiles.
 // fp32 storage: a plain tiled FMA kernel (only the tiny fp32 workload uses it).
 #include "gemm_core.hpp"
 
