@@ -877,7 +877,10 @@ int launch_mfma_deep(const GemmDesc& g, hipStream_t s) {
   if (grid.x > 512) grid.x = 512;
 #define BIGMAC_MFMA_DEEP(EPI, OUTF32) \
   hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 4, 1, AK, BKC, EPI, OUTF32>), grid, block, 0, s, g)
-  if (g.epilogue == EPI_ACCUM) BIGMAC_MFMA_DEEP(EPI_ACCUM, true);
+  if (g.scatter) {   // the descending projection writing the dispatched rows (k-contiguous A, whole-line B only)
+    if constexpr (AK && !BKC) hipLaunchKernelGGL((mfma_gemm_kernel<BM, BN, BK, 4, 1, AK, BKC, EPI_STORE, false, BIGMAC_TILE_STAGES, false, true>), grid, block, 0, s, g);
+    else return BIGMAC_ERR_UNSUPPORTED;
+  } else if (g.epilogue == EPI_ACCUM) BIGMAC_MFMA_DEEP(EPI_ACCUM, true);
   else if (g.out_f32) BIGMAC_MFMA_DEEP(EPI_STORE, true);
   else BIGMAC_MFMA_DEEP(EPI_STORE, false);
 #undef BIGMAC_MFMA_DEEP
@@ -992,7 +995,7 @@ int launch_gemm(const GemmDesc& desc, hipStream_t s) {
   }
   if (g.scatter) {  // see the kernel: a dense bf16 product's rows written through an index, the same operand layout as above
     if (g.dtype != BIGMAC_BF16 || g.mode != GEMM_DENSE || combo != 2 || g.epilogue != EPI_STORE || g.out_f32 || g.ksplit != 1 || g.wide_k ||
-        g.deep_tile || g.big_tile || g.gather || g.bias || g.scatter_k <= 0 || g.scatter_rows <= 0 ||
+        g.big_tile || g.gather || g.bias || g.scatter_k <= 0 || g.scatter_rows <= 0 ||
         (size_t)g.M * (size_t)g.scatter_k * 4 >= (1ull << 31) || (size_t)g.scatter_rows * (size_t)g.ldc * 2 >= (1ull << 31))
       return BIGMAC_ERR_UNSUPPORTED;
   }

@@ -500,7 +500,6 @@ namespace {
 bool descend_scatters(const bigmac_dims& D) {
   if (D.order != BIGMAC_ORDER_DCCA || !bf(D) || route_low(D) || (D.flags & BIGMAC_FLAG_NO_FUSED_DISPATCH)) return false;
   if (forward_ksplit(D, D.T, D.r, D.d) != 1) return false;
-  if (!tall_dense(D, D.T, D.r, D.d) && deep_dense(D, D.T, D.r, D.d)) return false;
   return (size_t)D.T * D.k * (size_t)D.r * 2 < (1ull << 31) && (size_t)D.T * D.k * 4 < (1ull << 31);
 }
 }  // namespace
@@ -671,8 +670,8 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   // A training forward on bf16 storage whose router reads x folds the dispatch into the descending
   // projection: the permutation is built first, and the product's epilogue writes every token's
   // narrow row straight into the places of its pairs in the permuted copy (x' itself is not
-  // stored: nothing else reads it).  Not where the product is summed from K slices or runs on the
-  // narrow tile shape, nor where the copy is too large for one 32-bit byte offset.
+  // stored: nothing else reads it).  Not where the product is summed from K slices, nor where the
+  // copy is too large for one 32-bit byte offset.
   const int descend_ksplit = dcca ? forward_ksplit(*D, D->T, D->r, D->d) : 1;
   const bool descend_tall = dcca && descend_ksplit == 1 && tall_dense(*D, D->T, D->r, D->d);
   const bool descend_deep = dcca && descend_ksplit == 1 && !descend_tall && deep_dense(*D, D->T, D->r, D->d);

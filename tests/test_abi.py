@@ -103,7 +103,7 @@ def test_null_pointers_and_small_workspaces_are_rejected():
 def test_where_the_dispatch_step_runs():
     """bigmac_dispatch_folding: host logic only.  Forward-only bf16 calls fold the dispatch into the
     expert-up product; DCCA training calls into the descending projection unless the router reads
-    x', the flag forbids it, the storage is fp32 or the projection runs on its short-and-deep tile."""
+    x', the flag forbids it, the storage is fp32 or the projection is summed from K slices."""
     big = dict(T=32768, d=4096, r=1024, N=128, k=8, h=2048)
     assert B.dispatch_folding(B.make_dims(**big), training=True) == 2
     assert B.dispatch_folding(B.make_dims(**big), training=False) == 1
@@ -113,4 +113,5 @@ def test_where_the_dispatch_step_runs():
     assert B.dispatch_folding(B.make_dims(4096, 4096, 4096, 8, 2, 4096, order=B.ORDER_CDAC), training=True) == 0
     assert B.dispatch_folding(B.make_dims(256, 256, 64, 8, 2, 256, dtype=B.F32), training=True) == 0
     assert B.dispatch_folding(B.make_dims(256, 256, 64, 8, 2, 256, dtype=B.F32), training=False) == 0
-    assert B.dispatch_folding(B.make_dims(8192, 1024, 256, 64, 8, 1024), training=True) == 0   # 128 x 64 tiles with 64-deep k tiles
+    assert B.dispatch_folding(B.make_dims(8192, 1024, 256, 64, 8, 1024), training=True) == 2
+    assert B.dispatch_folding(B.make_dims(200, 768, 256, 8, 2, 128), training=True) == 0         # the projection is summed from K slices

@@ -145,7 +145,7 @@ def test_dispatch_folded_into_the_descending_projection(case):
     (one store per pick, dropped pairs none).  Same bits as with the copy kernel
     (BIGMAC_FLAG_NO_FUSED_DISPATCH) in y, dx and every weight gradient (dW1 contracts over all rows
     of the permuted copy): more picks than one pass of the epilogue takes, a capacity that drops
-    pairs, T = 1, and shapes whose projection runs on another tile or in K slices (not folded)."""
+    pairs, T = 1, a shape whose projection runs on its 128 x 64 tile, and one summed from K slices (not folded)."""
     wl = synth.small(**case)
     data = synth.generate(wl)
     for capacity in (0, B.expert_capacity(wl.T, wl.k, wl.N, 0.7)):
