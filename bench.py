@@ -30,8 +30,8 @@ PEAK_ALU_F32 = 157.3e12    # flop/s, published fp32 vector peak (unpacked v_fmac
 # the committed summaries of those runs (the *_hbm_traffic files under profiles/).
 MEASURED_TRAFFIC = {   # stage -> (MiB read, MiB written) per launch
     ("gpt_medium", "dcca"): {"source": "profiles/gpt_medium_hbm_traffic.md",
-                             "expert_up": (98.9, 256.3), "expert_down": (169.9, 64.1), "bwd_down_dgrad": (195.9, 128.2),
-                             "bwd_down_wgrad": (161.0, 64.0), "bwd_up_wgrad": (160.3, 64.0), "bwd_up_dgrad": (170.8, 64.1)},
+                             "expert_up": (98.9, 256.2), "expert_down": (168.5, 64.1), "bwd_down_dgrad": (195.9, 128.2),
+                             "bwd_down_wgrad": (160.8, 64.0), "bwd_up_wgrad": (160.3, 64.0), "bwd_up_dgrad": (170.7, 64.1)},
     ("zipf_stress", "dcca"): {"source": "profiles/zipf_stress_hbm_traffic.md",
                               "expert_up": (3834.0, 2048.5), "expert_down": (2061.0, 1024.2), "bwd_down_dgrad": (3480.6, 1161.2),
                               "bwd_down_wgrad": (2446.9, 1024.0), "bwd_up_wgrad": (3409.1, 1024.1), "bwd_up_dgrad": (2066.0, 1024.2)},
