@@ -198,6 +198,38 @@ def test_variants_agree_bit_for_bit_on_random_shapes():
                     assert np.array_equal(ref[n], out[n]), (n, case, flags, training)
 
 
+def test_variants_agree_bit_for_bit_on_mid_size_shapes():
+    """The same at sizes where the tile policy leaves the square tile (128 x 256 and 256 x 256 tiles,
+    64-deep k tiles, 128 experts with whole-group weight-gradient schedules, hidden widths that end
+    inside a column tile): every variant gives the bits of the step that forbids the large tiles
+    and dispatches with the copy kernel, gradients included."""
+    rng = np.random.default_rng(5)
+    for it in range(8):
+        d, r = int(rng.choice([512, 1024, 2048])), int(rng.choice([512, 1024]))
+        h = int(rng.choice([1024, 1984, 2048, 2304]))
+        N, k, T = int(rng.choice([8, 16, 72, 128])), int(rng.choice([2, 4, 8])), int(rng.choice([2560, 6000, 8192, 12000]))
+        case = dict(T=T, d=d, r=r, N=N, k=k, h=h, zipf_s=float(rng.choice([0.0, 0.8, 1.2])))
+        capacity = B.expert_capacity(T, k, N, 0.8) if rng.random() < 0.25 else 0
+        print("mid-size shape", it, case, "capacity", capacity, flush=True)
+        wl = synth.small(**case)
+        data = synth.generate(wl)
+        ref = None
+        for flags, training in ((B.FLAG_NO_FUSED_DISPATCH | B.FLAG_TILES_SMALL, True), (0, True), (B.FLAG_TILES_LARGE, True), (0, False)):
+            layer = DeviceLayer(wl, data, flags=flags, capacity=capacity)
+            out = {"y": host(layer.forward(training=training)).copy()}
+            if training:
+                layer.alloc_grads()
+                layer.backward()
+                torch.cuda.synchronize()
+                out.update({n: host(g).copy() for n, g in layer.grads.items()}, dx=host(layer.dx).copy())
+            del layer
+            if ref is None:
+                ref = out
+                assert np.isfinite(ref["y"]).all() and np.abs(ref["y"]).max() > 0
+            for n in out:
+                assert np.array_equal(ref[n], out[n]), (n, case, flags, training)
+
+
 def test_all_bf16_wire_format(oracle):
     """BIGMAC_FLAG_WIRE_BF16 (Table 4's BF16 transfers taken literally: expert outputs and the gradient
     of the dispatched rows rounded to bf16 between the expert products and the combine kernels):
