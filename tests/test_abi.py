@@ -115,3 +115,4 @@ def test_where_the_dispatch_step_runs():
     assert B.dispatch_folding(B.make_dims(256, 256, 64, 8, 2, 256, dtype=B.F32), training=False) == 0
     assert B.dispatch_folding(B.make_dims(8192, 1024, 256, 64, 8, 1024), training=True) == 2
     assert B.dispatch_folding(B.make_dims(200, 768, 256, 8, 2, 128), training=True) == 0         # the projection is summed from K slices
+    assert B.dispatch_folding(B.make_dims(262144, 4096, 1024, 128, 8, 2048), training=True) == 0  # permuted copy of 4 GiB: past one 32-bit offset
