@@ -502,13 +502,18 @@ bool descend_scatters(const bigmac_dims& D) {
   if (forward_ksplit(D, D.T, D.r, D.d) != 1) return false;
   return (size_t)D.T * D.k * (size_t)D.r * 2 < (1ull << 31) && (size_t)D.T * D.k * 4 < (1ull << 31);
 }
+// forward-only call: the expert-up product reads its rows through src_of (see bigmac_layer_forward);
+// the rows behind the index must lie within one 32-bit byte offset
+bool expert_up_gathers(const bigmac_dims& D) {
+  return bf(D) && !(D.flags & BIGMAC_FLAG_NO_FUSED_DISPATCH) && (size_t)D.T * (size_t)widths(D).win * 2 < (1ull << 31);
+}
 }  // namespace
 
 int bigmac_dispatch_folding(const bigmac_dims* D, int training) {
   const int rc = check_dims(D);
   if (rc) return rc;
   if (training) return descend_scatters(*D) ? 2 : 0;
-  return bf(*D) && !(D->flags & BIGMAC_FLAG_NO_FUSED_DISPATCH) ? 1 : 0;
+  return expert_up_gathers(*D) ? 1 : 0;
 }
 
 const char* bigmac_stage_name(int stage) {
@@ -720,7 +725,7 @@ int bigmac_layer_forward(const bigmac_dims* D, const bigmac_params* P, const voi
   // Forward-only calls on bf16 storage fold the dispatch into the expert-up product: its A rows are
   // read from x' (or x) through src_of and no permuted copy is written.  A training forward
   // keeps the copy: the backward pass contracts over its rows.
-  const bool fuse_dispatch = !saved && bf(*D) && !(D->flags & BIGMAC_FLAG_NO_FUSED_DISPATCH);
+  const bool fuse_dispatch = !saved && expert_up_gathers(*D);
   if (!fuse_dispatch && !scatter_descend) {
     BIGMAC_STAGE(BIGMAC_STAGE_DISPATCH);
     rc = launch_dispatch_rows(D->dtype, D->T, D->k, W.win, x_low, slot_of, x_perm, s);

@@ -116,3 +116,5 @@ def test_where_the_dispatch_step_runs():
     assert B.dispatch_folding(B.make_dims(8192, 1024, 256, 64, 8, 1024), training=True) == 2
     assert B.dispatch_folding(B.make_dims(200, 768, 256, 8, 2, 128), training=True) == 0         # the projection is summed from K slices
     assert B.dispatch_folding(B.make_dims(262144, 4096, 1024, 128, 8, 2048), training=True) == 0  # permuted copy of 4 GiB: past one 32-bit offset
+    assert B.dispatch_folding(B.make_dims(262144, 4096, 1024, 128, 8, 2048), training=False) == 1  # x' is 512 MiB
+    assert B.dispatch_folding(B.make_dims(262144, 4096, 4096, 128, 8, 4096, order=B.ORDER_CDAC), training=False) == 0   # x is 2 GiB
