@@ -11,6 +11,8 @@ SOURCES = ["gemm.hip", "route.hip", "permute.hip", "layer.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          # hipcc must not form packed fp32 instructions on its own
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # no device function is ever compiled as a real call (see the note at build_tile_map_block in tile_map.hpp)
+         "-mllvm", "-amdgpu-function-calls=false",
          "-Wno-unused-command-line-argument"]
 
 
