@@ -127,6 +127,8 @@ def run_training_workload(oracle, name, n_fwd, experts_dense=None, n_sel=0, flag
         print(f"{name}: dense-dy gradients of expert {e} ({len(tok)} rows), max-abs/rms of the block: "
               f"{ {n: round(v, 4) for n, v in errs.items()} }", flush=True)
         assert all(v < TOL for v in errs.values()), errs
+    if n_sel == 0:
+        return {}
     # sampled dy: all weight gradients against the oracle's token selection (the shared ones as whole
     # tensors, the experts' block by block where the sample leaves an expert enough rows)
     sel2 = sample_tokens(wl.T, n_sel, 3)
@@ -254,9 +256,15 @@ def test_decode_sweep_forward(oracle, T):
 
 
 def test_zipf_stress(oracle):
-    def pick(counts, eff):
-        # an expert with a few thousand rows and the most loaded one (about 30 k rows): the latter is the
-        # long ragged K of the weight-gradient products and the tall ragged-M tiles under real data
-        order = [int(e) for e in np.argsort(counts)]
-        return [min(order, key=lambda e: abs(int(counts[e]) - 4000)), order[-1]]
+    def pick(counts, eff):   # an expert with a few thousand rows under the dense dy
+        return [min(range(len(counts)), key=lambda e: abs(int(counts[e]) - 4000))]
     run_training_workload(oracle, "zipf_stress", n_fwd=128, n_sel=3072, experts_dense=pick)
+
+
+def test_zipf_stress_most_loaded_expert(oracle):
+    """The most loaded expert (about 30 k rows) under the dense dy, a test of its own because the
+    oracle redoes nearly every token for it: the long ragged K of the weight-gradient products and
+    the many row tiles of one expert under real data."""
+    def pick(counts, eff):
+        return [int(np.argmax(counts))]
+    run_training_workload(oracle, "zipf_stress", n_fwd=16, n_sel=0, experts_dense=pick)
